@@ -1,0 +1,132 @@
+/*
+ * libdapq — DapQ eviction scoring for MI355X (gfx950), C ABI.
+ *
+ * DapQ ("Where Matters More Than What", Sec. 4) decides which prompt keys to keep before decoding
+ * starts: N pseudo queries that carry the RoPE positions of the first N decode steps
+ * (L_p .. L_p+N-1, Sec. 4.1) attend to the L_p prompt keys; the attention mass each key receives
+ * is summed over the pseudo queries (Sec. 4.2, importance score S(j)), and only the TopK keys per
+ * head survive (Sec. 4.2, M_retain); their K/V rows form the compact cache that decoding uses.
+ *
+ * Conventions for every entry point
+ *   - C linkage, plain C types.  Returns DAPQ_OK (0) or a negative DAPQ_ERR_* code;
+ *     dapq_last_error() gives a thread-local message for the last failure on this thread.
+ *   - Every data pointer is DEVICE memory unless the comment says "host".  The caller owns all
+ *     buffers (inputs, outputs, workspace); the library allocates nothing, frees nothing and keeps
+ *     no pointer after the call returns.  Inputs are never written.
+ *   - Arguments are validated on the host before anything is enqueued; a failing call enqueues
+ *     nothing.  Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default
+ *     stream) and the call returns without synchronising.
+ *   - Results are deterministic: the same inputs give the same bits on every run.
+ *   - bf16 tensors are passed as void* (16-bit patterns).  head_dim must be 128.
+ *
+ * Tensor layouts (element strides, the last dimension d is contiguous)
+ *   Q  pseudo queries, bf16, already rotated to positions L_p+i:
+ *        q[layer*q_stride_layer + seq*q_stride_seq + head*q_stride_head + i*q_stride_row + c]
+ *   K, V  prompt keys / values, bf16, keys already rotated to their positions:
+ *        k[layer*k_stride_layer + seq*k_stride_seq + kv_head*k_stride_head + t*k_stride_token + c]
+ *        where t = cu_seqlens[seq] + j is the packed token index of key j of sequence seq
+ *        (set k_stride_seq = 0 for a packed [tokens][heads][d] layout).
+ *   scores / pooled   fp32 [n_layers][n_kv_heads][total_tokens]   (packed token index)
+ *   idx     int32 [n_layers][batch][n_kv_heads][budget]   positions j inside the sequence, ascending
+ *   count   int32 [n_layers][batch][n_kv_heads]           = min(budget of the sequence, L_p)
+ *   k_out, v_out  bf16 [n_layers][batch][n_kv_heads][budget][d]
+ */
+#ifndef DAPQ_H
+#define DAPQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  DAPQ_OK = 0,
+  DAPQ_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, heads not divisible, even pool width ... */
+  DAPQ_ERR_UNSUPPORTED = -2, /* head_dim != 128, stride not a multiple of 8 elements, misaligned base */
+  DAPQ_ERR_WORKSPACE = -3,   /* workspace smaller than dapq_workspace_bytes() */
+  DAPQ_ERR_HIP = -4          /* the HIP runtime refused a launch */
+};
+
+typedef struct dapq_shape {
+  int32_t n_layers;
+  int32_t batch;          /* sequences */
+  int32_t n_q_heads;      /* H_q, a multiple of n_kv_heads; query head h belongs to KV head h / (H_q/H_kv) */
+  int32_t n_kv_heads;     /* H_kv */
+  int32_t head_dim;       /* d_k = 128 */
+  int32_t n_pseudo;       /* N pseudo queries per query head (Sec. 4.1) */
+  int64_t total_tokens;   /* sum of L_p over the batch */
+  const int32_t* cu_seqlens; /* device, [batch+1], cu_seqlens[0] = 0, non-decreasing, last = total_tokens;
+                                NULL = every sequence has L_p = total_tokens / batch */
+  int64_t k_stride_layer, k_stride_seq, k_stride_head, k_stride_token;
+  int64_t v_stride_layer, v_stride_seq, v_stride_head, v_stride_token;
+  int64_t q_stride_layer, q_stride_seq, q_stride_head, q_stride_row;
+  float scale;            /* 1/sqrt(d_k) (App. C.1: Attention(q,K) = softmax(qK^T/sqrt(d_k))) */
+} dapq_shape;
+
+/* Bytes of device workspace dapq_score / dapq_score_stats / dapq_topk need for this shape
+ * (one figure covers all of them).  Returns 0 if the shape is invalid. */
+size_t dapq_workspace_bytes(const dapq_shape* shape);
+
+/* Message for the last error returned on the calling thread ("" if none). Host pointer, owned by the library. */
+const char* dapq_last_error(void);
+
+/* Sec. 4.1 — position assignment.  Rotates every (row, head) vector of x_in to the absolute
+ * position pos[row] with rotary embedding: channel pair c turns by pos * theta^(-2c/head_dim).
+ * For the pseudo queries of a prompt of length L_p the caller passes pos = L_p .. L_p+N-1.
+ *   x_in, x_out  bf16, element (row, head, c) at row*stride_row + head*stride_head + c; x_out may
+ *                equal x_in (in place) but must not otherwise overlap it.
+ *   pos          int32 [rows], >= 0.
+ *   pairing      0: channel c pairs with c + head_dim/2;  1: channel 2c pairs with 2c+1.
+ * Angles and the rotation are evaluated in fp64, the result is rounded to bf16 once (nearest even). */
+int dapq_rope_apply(const void* x_in, void* x_out, const int32_t* pos, int64_t rows, int32_t heads,
+                    int32_t head_dim, int64_t stride_row, int64_t stride_head, double theta,
+                    int32_t pairing, void* stream);
+
+/* Sec. 4.2, importance score — S(j) = sum_i Attention(q_i, k_j), summed also over the query heads
+ * that share the KV head; Attention is the softmax over the L_p prompt keys of one sequence
+ * (App. C.1).  Two streaming passes over K, no N x L_p matrix is stored.
+ *   scores   out, fp32 [n_layers][n_kv_heads][total_tokens]
+ *   workspace  device scratch of at least dapq_workspace_bytes(shape), 256-byte aligned.
+ * Equivalent to dapq_score_stats followed by dapq_score_accumulate. */
+int dapq_score(const dapq_shape* shape, const void* q, const void* k, float* scores, void* workspace,
+               size_t workspace_bytes, void* stream);
+
+/* First pass of dapq_score: for every pseudo query row, lse2 = log2 sum_j 2^(c*l_j) with
+ * l_j = q.k_j and c = scale*log2(e), i.e. the softmax normaliser of App. C.1 Step 1 in log2 form.
+ *   lse2   out, fp32 [n_layers][batch][n_q_heads][n_pseudo] */
+int dapq_score_stats(const dapq_shape* shape, const void* q, const void* k, float* lse2, void* workspace,
+                     size_t workspace_bytes, void* stream);
+
+/* Second pass of dapq_score: recomputes the logits, forms alpha = 2^(c*l - lse2) and writes its
+ * sum over the pseudo queries and the group for every key.  lse2 as written by dapq_score_stats
+ * (it may live outside the workspace; inside it only the region dapq_score itself uses is safe). */
+int dapq_score_accumulate(const dapq_shape* shape, const void* q, const void* k, const float* lse2,
+                          float* scores, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Pooling of the accumulated scores before selection (Sec. 1 / Sec. 5.1: selection runs on pooled
+ * accumulated attention scores): pooled(j) = max of scores over |t-j| <= (width-1)/2 inside the
+ * same sequence (the window is clipped at the sequence ends).  width odd, 1 <= width <= 63.
+ * pooled must not alias scores. */
+int dapq_pool(const dapq_shape* shape, const float* scores, float* pooled, int32_t width, void* stream);
+
+/* Sec. 4.2, M_retain = TopK_j S(j).  For every (layer, sequence, KV head): the min(budget, L_p)
+ * positions with the largest pooled score; equal scores are taken lowest position first; the
+ * result is written in ascending position.  Scores must be non-negative and finite.
+ *   budget           slots per head in idx (>= 1)
+ *   budget_per_seq   optional device int32 [batch]: budget of each sequence (clamped to [0, budget]); NULL = budget
+ *   idx, count       out; idx slots past count are left untouched */
+int dapq_topk(const dapq_shape* shape, const float* pooled, int32_t budget, const int32_t* budget_per_seq,
+              int32_t* idx, int32_t* count, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Sec. 4.2 — cache pruning: copies the retained K and V rows, bit for bit, into the compact cache;
+ * nothing of the pseudo segment is kept.  Rows past count are left untouched.
+ * k_out / v_out must not overlap k / v. */
+int dapq_gather(const dapq_shape* shape, const void* k, const void* v, const int32_t* idx,
+                const int32_t* count, int32_t budget, void* k_out, void* v_out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DAPQ_H */

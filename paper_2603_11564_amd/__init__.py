@@ -1,0 +1,9 @@
+"""DapQ eviction scoring for MI355X: a thin ctypes binding over libdapq.so (hand-written HIP, gfx950).
+
+Only argument marshalling happens here; every step of the path runs in the library's kernels.
+There is no fallback: if libdapq.so is missing, importing `paper_2603_11564_amd.binding` raises.
+"""
+from .binding import (  # noqa: F401
+    DapqError, Shape, lib_path, load_library, make_shape, workspace_bytes,
+    dapq_rope_apply, dapq_score, dapq_score_stats, dapq_score_accumulate, dapq_pool, dapq_topk, dapq_gather,
+)

@@ -1,0 +1,82 @@
+// Position assignment (Sec. 4.1): rotary embedding of bf16 vectors at given absolute positions.
+// The pseudo queries get positions L_p .. L_p+N-1, the positions of the first N decode steps.
+//
+// One thread owns one (row, channel pair): it evaluates the angle pos * theta^(-2c/d) and its
+// sine / cosine once in fp64 and then walks the heads of that row, so the transcendental work is
+// shared by all heads.  fp64 keeps the angle exact enough at positions beyond 10^5 (an fp32
+// product pos * omega would be off by ~1e-2 rad there); the result is rounded to bf16 once.
+#include <math.h>
+
+#include "dapq_internal.h"
+
+namespace dapq {
+namespace {
+
+__device__ __forceinline__ double bf16_to_f64(uint16_t b) { return (double)__uint_as_float((uint32_t)b << 16); }
+
+// fp64 -> bf16, round to nearest even, without an intermediate fp32 rounding: the fp32 conversion
+// truncates toward zero (the discarded fp64 bits are folded into a sticky bit), then the 16 low
+// bits are rounded.
+__device__ __forceinline__ uint16_t f64_to_bf16(double x) {
+  float f = __double2float_rz(x);
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7F800000u) == 0x7F800000u) return (uint16_t)(u >> 16);  // inf / nan pass through
+  const bool sticky = (double)f != x;
+  const uint32_t low = u & 0xFFFFu;
+  uint32_t hi = u >> 16;
+  const bool up = low > 0x8000u || (low == 0x8000u && (sticky || (hi & 1u)));
+  return (uint16_t)(hi + (up ? 1u : 0u));
+}
+
+__global__ void rope_kernel(const uint16_t* __restrict__ x_in, uint16_t* x_out, const int32_t* __restrict__ pos,
+                            int64_t rows, int heads, int head_dim, int64_t stride_row, int64_t stride_head,
+                            double neg_log2_theta_2_over_d, int pairing) {
+  const int half = head_dim >> 1;
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= rows * half) return;
+  const int64_t row = gid / half;
+  const int c = (int)(gid - row * half);
+  const double omega = exp2((double)c * neg_log2_theta_2_over_d);  // theta^(-2c/d)
+  double sn, cs;
+  sincos((double)pos[row] * omega, &sn, &cs);
+  const int ia = pairing == 0 ? c : 2 * c;
+  const int ib = pairing == 0 ? c + half : 2 * c + 1;
+  const uint16_t* src = x_in + row * stride_row;
+  uint16_t* dst = x_out + row * stride_row;
+  for (int hd = 0; hd < heads; ++hd) {
+    const double a = bf16_to_f64(src[hd * stride_head + ia]);
+    const double b = bf16_to_f64(src[hd * stride_head + ib]);
+    dst[hd * stride_head + ia] = f64_to_bf16(a * cs - b * sn);
+    dst[hd * stride_head + ib] = f64_to_bf16(b * cs + a * sn);
+  }
+}
+
+}  // namespace
+}  // namespace dapq
+
+using namespace dapq;
+
+extern "C" DAPQ_API int dapq_rope_apply(const void* x_in, void* x_out, const int32_t* pos, int64_t rows, int32_t heads,
+                               int32_t head_dim, int64_t stride_row, int64_t stride_head, double theta,
+                               int32_t pairing, void* stream) {
+  DAPQ_REQUIRE(x_in != nullptr && x_out != nullptr && pos != nullptr, DAPQ_ERR_INVALID_ARG,
+               "x_in, x_out and pos must not be NULL");
+  DAPQ_REQUIRE(rows >= 0 && heads >= 1, DAPQ_ERR_INVALID_ARG, "rows (%lld) must be >= 0 and heads (%d) >= 1",
+               (long long)rows, heads);
+  DAPQ_REQUIRE(head_dim >= 2 && head_dim % 2 == 0, DAPQ_ERR_INVALID_ARG, "head_dim (%d) must be even and >= 2",
+               head_dim);
+  DAPQ_REQUIRE(pairing == 0 || pairing == 1, DAPQ_ERR_INVALID_ARG, "pairing must be 0 (half) or 1 (interleaved)");
+  DAPQ_REQUIRE(theta > 0.0 && isfinite(theta), DAPQ_ERR_INVALID_ARG, "theta must be finite and > 0");
+  DAPQ_REQUIRE(stride_head >= head_dim && stride_row >= 0, DAPQ_ERR_INVALID_ARG,
+               "stride_head (%lld) must cover head_dim and stride_row (%lld) must be >= 0", (long long)stride_head,
+               (long long)stride_row);
+  const int64_t work = rows * (head_dim / 2);
+  DAPQ_REQUIRE(work / 256 < ((int64_t)1 << 31), DAPQ_ERR_UNSUPPORTED, "too many rows");
+  if (work == 0) return DAPQ_OK;
+  const double e = -2.0 * log2(theta) / (double)head_dim;
+  hipLaunchKernelGGL(rope_kernel, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const uint16_t*>(x_in), static_cast<uint16_t*>(x_out), pos, rows, heads, head_dim,
+                     stride_row, stride_head, e, pairing);
+  DAPQ_HIP_LAUNCH_CHECK("rope_kernel");
+  return DAPQ_OK;
+}

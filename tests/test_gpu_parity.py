@@ -1,0 +1,354 @@
+"""GPU parity: every C-ABI entry point of libdapq.so against the float64 oracle, element by element,
+on seeded inputs that span several tiles and ragged tails, plus the degenerate cases."""
+import sys
+import zlib
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from oracle import dapq_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+def announce(msg):
+    print(f"[gpu-case] {msg}", file=sys.__stderr__, flush=True)
+
+
+@pytest.fixture(scope="module")
+def H():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import dapq_harness
+    return dapq_harness
+
+
+def random_problem(seed, layers, lens, Hq, Hkv, N, d=128, gain=1.0):
+    r = np.random.default_rng(seed)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    q = W.to_bf16_bits(r.standard_normal((layers, len(lens), Hq, N, d)) * gain)
+    k = W.to_bf16_bits(r.standard_normal((layers, int(cu[-1]), Hkv, d)) * gain)
+    v = r.integers(0, 65536, size=k.shape, dtype=np.uint16)
+    return q, k, v, cu
+
+
+# ----------------------------------------------------------------------------------------- rope
+@pytest.mark.parametrize("pairing", [0, 1])
+def test_rope_matches_oracle_bits(H, pairing):
+    announce(f"rope pairing={pairing}")
+    r = np.random.default_rng(100 + pairing)
+    bits = W.to_bf16_bits(r.standard_normal((777, 5, 128)))
+    pos = r.integers(0, 140000, size=777).astype(np.int32)
+    pos[:3] = [0, 1, 131071 + 63]
+    got = H.rope_gpu(bits, pos, 500000.0, pairing)
+    want = O.rope_apply(bits, pos, 500000.0, "half" if pairing == 0 else "interleaved")
+    diff = got.astype(np.int32) - want.astype(np.int32)
+    mism = np.count_nonzero(diff)
+    # both sides evaluate the rotation in fp64 and round once: a mismatch needs an fp64 last-bit
+    # difference to straddle a bf16 rounding boundary
+    assert np.abs(diff).max() <= 1 and mism <= 2, f"{mism} of {diff.size} elements differ"
+    assert np.array_equal(got[0], bits[0])                     # position 0 is the identity
+
+
+def test_rope_in_place_and_pseudo_query_positions(H):
+    announce("rope in place, C1 pseudo queries")
+    w = W.workload("C1")
+    p = W.host_problem(w, 5)
+    q_rows = np.ascontiguousarray(p["q"][0, 0].transpose(1, 0, 2))          # [N, Hq, d]
+    x = H.dev_bf16(q_rows)
+    pos = torch.from_numpy(p["q_pos"][0]).cuda()
+    import paper_2603_11564_amd as D
+    D.dapq_rope_apply(x, x, pos, w.n_pseudo, w.n_q_heads, 128, w.n_q_heads * 128, 128, w.theta, 0)
+    want = O.rope_apply(q_rows, p["q_pos"][0], w.theta)
+    assert np.array_equal(H.host_bits(x), want)
+
+
+# ----------------------------------------------------------------------------------------- score
+SCORE_CASES = [
+    # name, layers, lens, Hq, Hkv, N, layout
+    ("c1-like hnd", 1, [1024], 32, 8, 64, "hnd"),
+    ("ragged tail thd", 2, [1000], 8, 2, 64, "thd"),
+    ("tiny lengths", 1, [1, 5, 31, 33, 129, 2], 4, 2, 8, "thd"),
+    ("N=1 g=1", 1, [300], 2, 2, 1, "thd"),
+    ("N=3 g=4 (12 rows)", 1, [700], 8, 2, 3, "hnd"),
+    ("R=64", 1, [513], 4, 1, 64, "thd"),
+    ("R=128", 1, [515], 8, 2, 32, "thd"),
+    ("R=512 two super-groups", 1, [400, 260], 8, 2, 128, "thd"),
+    ("R=640 g=5", 1, [257], 5, 1, 128, "thd"),
+    ("long chunked", 1, [9000], 4, 1, 64, "hnd"),
+    ("ragged with empty", 1, [130, 0, 64, 0], 4, 2, 16, "thd"),
+]
+
+
+@pytest.mark.parametrize("case", SCORE_CASES, ids=[c[0] for c in SCORE_CASES])
+def test_score_matches_oracle(H, case):
+    name, layers, lens, Hq, Hkv, N, layout = case
+    announce(f"score {name}")
+    q, k, v, cu = random_problem(zlib.crc32(name.encode()) % 1000, layers, lens, Hq, Hkv, N)
+    ragged = len(lens) > 1
+    prob = H.Problem(q, k, v, Hkv, cu if ragged else None, layout)
+    S = prob.score().cpu().numpy()
+    lse = prob.stats().cpu().numpy()
+    want = O.score(q, k, Hkv, cu if ragged else None)
+    worst = H.assert_scores_close(S, want, name)
+    # every row's normaliser: log2 sum_j exp(l_j)
+    g = Hq // Hkv
+    for l in range(layers):
+        for b, (s, e) in enumerate(prob.seq_bounds()):
+            if e == s:
+                continue
+            for h in range(Hq):
+                logits = O.bf16_bits_to_f64(q[l, b, h]) @ O.bf16_bits_to_f64(k[l, s:e, h // g]).T / np.sqrt(128)
+                m = logits.max(axis=1)
+                ref = (m + np.log(np.exp(logits - m[:, None]).sum(axis=1))) / np.log(2)
+                assert np.abs(lse[l, b, h] - ref).max() < 2e-4, name
+    for l in range(layers):
+        for kv in range(Hkv):
+            for b, (s, e) in enumerate(prob.seq_bounds()):
+                if e > s:
+                    assert abs(S[l, kv, s:e].sum() - g * N) < 1e-3 * g * N
+    announce(f"score {name}: max rel err {worst:.2e}")
+
+
+def test_score_c1_workload_with_needles(H):
+    announce("score C1 workload")
+    w = W.workload("C1")
+    p = W.host_problem(w, 0)
+    q, k = H.rope_problem_oracle(p, w.theta)
+    prob = H.Problem(q, k, p["v"], w.n_kv_heads, None, "hnd", w.scale)
+    S = prob.score().cpu().numpy()
+    H.assert_scores_close(S, O.score(q, k, w.n_kv_heads), "C1")
+    S2 = prob.score().cpu().numpy()
+    assert np.array_equal(S, S2), "two runs differ bit for bit"
+
+
+def test_score_dominant_late_key_takes_overflow_path(H):
+    # one key far above the reference logit of the first sub-block: the fast pass overflows and the
+    # chunk is redone with a running maximum; all mass must land on that key
+    announce("score dominant late key")
+    q, k, v, cu = random_problem(7, 1, [3000], 4, 1, 16)
+    qf = O.bf16_bits_to_f64(q[0, 0, 0, 0])
+    k[0, 2500, 0] = W.to_bf16_bits(40.0 * qf)             # logit ~ 40*128/11.3 ~ 450 for that row
+    k[0, 17, 0] = W.to_bf16_bits(-40.0 * qf)
+    prob = H.Problem(q, k, v, 1, None, "thd")
+    S = prob.score().cpu().numpy()
+    want = O.score(q, k, 1)
+    H.assert_scores_close(S, want, "dominant key")
+    assert S[0, 0, 2500] > 1.0
+
+
+def test_score_all_equal_keys_uniform(H):
+    announce("score all-equal keys")
+    q, k, v, cu = random_problem(8, 1, [517], 8, 2, 8)
+    k[:] = k[:, :1]
+    prob = H.Problem(q, k, v, 2, None, "thd")
+    S = prob.score().cpu().numpy()
+    assert np.allclose(S, 4 * 8 / 517, rtol=1e-5)
+
+
+def test_score_scale_and_large_gain(H):
+    announce("score custom scale / heavy keys")
+    q, k, v, cu = random_problem(9, 1, [640], 4, 2, 32, gain=1.0)
+    k[0, ::10] = W.to_bf16_bits(4.0 * W.from_bf16_bits(k[0, ::10]))        # heavy-hitter tail
+    prob = H.Problem(q, k, v, 2, None, "thd", scale=0.2)
+    S = prob.score().cpu().numpy()
+    H.assert_scores_close(S, O.score(q, k, 2, None, 0.2), "scale 0.2")
+
+
+# ----------------------------------------------------------------------------------------- pool
+@pytest.mark.parametrize("width", [1, 3, 7, 9, 11, 63])
+def test_pool_bit_exact(H, width):
+    announce(f"pool width={width}")
+    r = np.random.default_rng(width)
+    lens = [1, 2, 6, 7, 8, 255, 256, 257, 1000, 3, 0, 1029]
+    q, k, v, cu = random_problem(1, 2, lens, 2, 2, 1)
+    prob = H.Problem(q, k, v, 2, cu, "thd")
+    S = r.random((2, 2, int(cu[-1]))).astype(np.float32)
+    S[0, 0, ::5] = S[0, 0, 1]                                   # ties
+    P = prob.pool(torch.from_numpy(S).cuda(), width).cpu().numpy()
+    for l in range(2):
+        for kv in range(2):
+            for b in range(len(lens)):
+                s, e = cu[b], cu[b + 1]
+                want = O.pool(S[l, kv, s:e].astype(np.float64), width)
+                assert np.array_equal(P[l, kv, s:e].astype(np.float64), want), (width, l, kv, b)
+
+
+def test_pool_dense_batch_unaligned_total(H):
+    announce("pool dense, total % 4 != 0")
+    q, k, v, cu = random_problem(2, 1, [333, 333, 333], 2, 1, 1)
+    prob = H.Problem(q, k, v, 1, None, "thd")
+    S = np.random.default_rng(3).random((1, 1, 999)).astype(np.float32)
+    P = prob.pool(torch.from_numpy(S).cuda(), 7).cpu().numpy()
+    for b in range(3):
+        want = O.pool(S[0, 0, 333 * b:333 * (b + 1)].astype(np.float64), 7)
+        assert np.array_equal(P[0, 0, 333 * b:333 * (b + 1)].astype(np.float64), want)
+
+
+# ----------------------------------------------------------------------------------------- top-K
+def _topk_case(H, lens, budget, P, per_seq=None, layers=1, Hkv=2):
+    q, k, v, cu = random_problem(4, layers, lens, Hkv, Hkv, 1)
+    prob = H.Problem(q, k, v, Hkv, cu, "thd")
+    idx, count = prob.topk(torch.from_numpy(P).cuda(), budget, per_seq)
+    idx, count = idx.cpu().numpy(), count.cpu().numpy()
+    for l in range(layers):
+        for b in range(len(lens)):
+            kb = budget if per_seq is None else max(0, min(budget, per_seq[b]))
+            n = min(kb, lens[b])
+            for kv in range(Hkv):
+                assert count[l, b, kv] == n
+                want = O.topk(P[l, kv, cu[b]:cu[b + 1]].astype(np.float64), kb)
+                assert np.array_equal(idx[l, b, kv, :n], want), (l, b, kv)
+                assert (idx[l, b, kv, n:] == -7).all()          # slots past count untouched
+
+
+def test_topk_bit_exact_with_ties_and_plateaus(H):
+    announce("topk ties / plateaus")
+    r = np.random.default_rng(5)
+    lens = [1, 7, 100, 1023, 1024, 1025, 5000, 0, 40000]
+    tot = sum(lens)
+    P = r.random((1, 2, tot)).astype(np.float32)
+    P[0, 0] = np.round(P[0, 0] * 8) / 8                         # 9 distinct values: huge ties
+    P[0, 1, 10000:30000] = 0.5                                  # plateau straddling the boundary
+    for budget in (1, 64, 983, 5000):
+        _topk_case(H, lens, budget, P)
+
+
+def test_topk_pooled_scores_and_per_sequence_budgets(H):
+    announce("topk on pooled scores, per-sequence budgets")
+    r = np.random.default_rng(6)
+    lens = [3000, 50, 2048]
+    S = (r.random((2, 2, sum(lens))) ** 8).astype(np.float64)
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    P = np.zeros_like(S)
+    for l in range(2):
+        for kv in range(2):
+            for b in range(3):
+                P[l, kv, cu[b]:cu[b + 1]] = O.pool(S[l, kv, cu[b]:cu[b + 1]], 7)
+    _topk_case(H, lens, 300, P.astype(np.float32), per_seq=[300, 0, 10000], layers=2)
+
+
+def test_topk_all_equal_and_tiny_values(H):
+    announce("topk all equal / denormal-scale values")
+    lens = [777]
+    P = np.full((1, 2, 777), 0.25, dtype=np.float32)
+    P[0, 1] = (np.arange(777) % 13).astype(np.float32) * np.float32(1e-41)   # subnormals and zeros
+    _topk_case(H, lens, 100, P)
+
+
+def test_topk_long_sequence_not_staged_in_lds(H):
+    announce("topk L=70000 (streams from memory)")
+    r = np.random.default_rng(7)
+    P = r.random((1, 1, 70000)).astype(np.float32)
+    P[0, 0, 5000:5100] = 2.0
+    _topk_case(H, [70000], 2048, P, Hkv=1)
+
+
+# ----------------------------------------------------------------------------------------- gather
+@pytest.mark.parametrize("layout", ["thd", "hnd"])
+def test_gather_bit_exact(H, layout):
+    announce(f"gather {layout}")
+    lens = [300, 5, 64] if layout == "thd" else [400]
+    q, k, v, cu = random_problem(11, 2, lens, 4, 2, 1)
+    prob = H.Problem(q, k, v, 2, cu if len(lens) > 1 else None, layout)
+    r = np.random.default_rng(12)
+    budget = 40
+    idx = np.full((2, len(lens), 2, budget), -1, dtype=np.int32)
+    count = np.zeros((2, len(lens), 2), dtype=np.int32)
+    for l in range(2):
+        for b, L in enumerate(lens):
+            for kv in range(2):
+                n = min(budget, L) if (l + b + kv) % 3 else min(budget, L) // 2
+                count[l, b, kv] = n
+                idx[l, b, kv, :n] = np.sort(r.choice(L, size=n, replace=False))
+    ko, vo = prob.gather(torch.from_numpy(idx).cuda(), torch.from_numpy(count).cuda(), budget)
+    ko, vo = H.host_bits(ko), H.host_bits(vo)
+    for l in range(2):
+        for b in range(len(lens)):
+            for kv in range(2):
+                n = count[l, b, kv]
+                rows = idx[l, b, kv, :n]
+                assert np.array_equal(ko[l, b, kv, :n], O.gather(k[l, cu[b]:cu[b + 1], kv], rows))
+                assert np.array_equal(vo[l, b, kv, :n], O.gather(v[l, cu[b]:cu[b + 1], kv], rows))
+                assert (ko[l, b, kv, n:] == 0).all() and (vo[l, b, kv, n:] == 0).all()
+
+
+# ----------------------------------------------------------------------------------------- chain
+def run_chain(H, prob, budget, width, per_seq=None):
+    S = prob.score()
+    P = prob.pool(S, width)
+    idx, count = prob.topk(P, budget, per_seq)
+    ko, vo = prob.gather(idx, count, budget)
+    return S.cpu().numpy(), P.cpu().numpy(), idx.cpu().numpy(), count.cpu().numpy(), H.host_bits(ko), H.host_bits(vo)
+
+
+def compare_chain(H, prob, q, k, v, budget, width, per_seq=None, scale=None):
+    cu = prob.cu_host
+    S, P, idx, count, ko, vo = run_chain(H, prob, budget, width, per_seq)
+    ref = O.compress(q, k, v, prob.Hkv, budget if per_seq is None else per_seq, cu, width, scale)
+    H.assert_scores_close(S, ref["S"], "S")
+    H.assert_scores_close(P, ref["P"], "P")
+    classes = {"exact": 0, "margin": 0}
+    for l in range(prob.layers):
+        for b, (s, e) in enumerate(prob.seq_bounds()):
+            kb = budget if per_seq is None else per_seq[b]
+            for kv in range(prob.Hkv):
+                n = min(kb, e - s)
+                assert count[l, b, kv] == n == ref["count"][l, b, kv]
+                classes[H.check_retained(ref["P"][l, kv, s:e], idx[l, b, kv], kb)] += 1
+                rows = idx[l, b, kv, :n]
+                assert np.array_equal(ko[l, b, kv, :n], k[l, s:e, kv][rows])
+                assert np.array_equal(vo[l, b, kv, :n], v[l, s:e, kv][rows])
+    return classes, idx
+
+
+def test_chain_c1_workload_keeps_needles(H):
+    announce("chain C1")
+    w = W.workload("C1")
+    for seed in (0, 1):
+        p = W.host_problem(w, seed)
+        # the GPU rotates its own inputs; the oracle rotates its own
+        q_gpu = np.stack([H.rope_gpu(np.ascontiguousarray(p["q"][0, 0].transpose(1, 0, 2)), p["q_pos"][0],
+                                     w.theta).transpose(1, 0, 2)])[None]
+        k_gpu = H.rope_gpu(p["k"][0], p["k_pos"], w.theta)[None]
+        q_ref, k_ref = H.rope_problem_oracle(p, w.theta)
+        assert np.array_equal(q_gpu, q_ref) and np.array_equal(k_gpu, k_ref)
+        prob = H.Problem(q_gpu, k_gpu, p["v"], w.n_kv_heads, None, "hnd", w.scale)
+        classes, idx = compare_chain(H, prob, q_ref, k_ref, p["v"], w.budget, w.pool_width)
+        for kv in range(w.n_kv_heads):
+            pos, _, _ = W.needle_plan(w, seed, 0, 0, kv, w.seq_len)
+            assert set(pos.tolist()) <= set(idx[0, 0, kv].tolist())
+        announce(f"chain C1 seed {seed}: {classes}")
+
+
+def test_chain_ragged_batch_heavy_hitters(H):
+    announce("chain ragged heavy hitters (C3-like, small)")
+    w = W.workload("C3")
+    lens = [700, 1, 2500, 130]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    layers, N = 2, 128
+    q = np.empty((layers, len(lens), w.n_q_heads, N, 128), dtype=np.uint16)
+    k = np.empty((layers, int(cu[-1]), w.n_kv_heads, 128), dtype=np.uint16)
+    v = np.empty_like(k)
+    for l in range(layers):
+        for b, L in enumerate(lens):
+            qb = W.q_pre(w, 21, l, b)
+            q[l, b] = O.rope_apply(qb.transpose(1, 0, 2), W.q_positions(L, N), w.theta).transpose(1, 0, 2)
+            for kv in range(w.n_kv_heads):
+                kb = W.k_pre(w, 21, l, b, kv, L)
+                k[l, cu[b]:cu[b + 1], kv] = O.rope_apply(kb[:, None, :], W.k_positions(L), w.theta)[:, 0]
+                v[l, cu[b]:cu[b + 1], kv] = W.v_rows(w, 21, l, b, kv, L)
+    prob = H.Problem(q, k, v, w.n_kv_heads, cu, "thd", w.scale)
+    classes, _ = compare_chain(H, prob, q, k, v, 512, 7)
+    announce(f"chain ragged: {classes}")
+
+
+def test_chain_budget_edges(H):
+    announce("chain budget >= L, budget 1, L < pool width")
+    q, k, v, cu = random_problem(31, 1, [5, 900, 64], 8, 2, 16)
+    prob = H.Problem(q, k, v, 2, cu, "thd")
+    compare_chain(H, prob, q, k, v, 64, 7)
+    compare_chain(H, prob, q, k, v, 1, 7)
+    compare_chain(H, prob, q, k, v, 1000, 7, per_seq=[2, 1000, 0])
