@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the DapQ eviction step on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic batch, all layers and heads:
+  dapq_rope_apply (pseudo queries to positions L_p..L_p+N-1) -> dapq_score_stats (pass 1 over K)
+  -> dapq_score_accumulate (pass 2 over K) -> dapq_pool -> dapq_topk -> dapq_gather.
+Inputs are resident in HBM before the timed region.  Prints one JSON line:
+  value     prompt keys scored+evicted per second (layers x KV heads x prompt keys / step time)
+  roofline  the dominant kernel against the HBM roof: algorithmic bytes of one launch / its
+            average duration, timed with events on the launch stream inside the timed region
+  cpu_baseline  the float64 oracle on the host cores, on a bounded sample of the same workload
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE,
+# scaled by a copy kernel of known size); see profiles/.  None until measured for that workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C2", help="C1..C5 (C2 is the configuration the metric is quoted on)")
+    ap.add_argument("--n-pseudo", type=int, default=None, help="override N (the C4 sweep)")
+    ap.add_argument("--layers", type=int, default=None, help="override the layer count (fits memory / quick runs)")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--cpu-layers", type=int, default=None, help="layers the CPU oracle baseline runs (0 = skip)")
+    return ap.parse_args()
+
+
+def cpu_baseline(w, seed, n_layers):
+    """Times the oracle (rope of the pseudo queries + the eviction step) on n_layers layers of the
+    workload, sequence 0 only for ragged batches.  Input generation and the rotation of K are
+    preparation and are not timed, as on the GPU side."""
+    import numpy as np
+    import threadpoolctl
+    import workloads as W
+    from oracle import dapq_oracle as O
+
+    lens = W.seq_lens(w, seed)
+    L = lens[0]
+    qs, ks, vs = [], [], []
+    for layer in range(n_layers):
+        qp = W.q_pre(w, seed, layer, 0)
+        k = np.empty((L, w.n_kv_heads, w.head_dim), dtype=np.uint16)
+        v = np.empty_like(k)
+        for kv in range(w.n_kv_heads):
+            k[:, kv] = W.k_pre(w, seed, layer, 0, kv, L, qp)
+            v[:, kv] = W.v_rows(w, seed, layer, 0, kv, L)
+        qs.append(qp)
+        ks.append(O.rope_apply(k, W.k_positions(L), w.theta))
+        vs.append(v)
+    k = np.stack(ks)
+    v = np.stack(vs)
+    t0 = time.perf_counter()
+    q = np.stack([O.rope_apply(qp.transpose(1, 0, 2), W.q_positions(L, w.n_pseudo), w.theta).transpose(1, 0, 2)
+                  for qp in qs])[:, None]
+    O.compress(q, k, v, w.n_kv_heads, w.budget, None, w.pool_width, w.scale)
+    dt = time.perf_counter() - t0
+    keys = n_layers * w.n_kv_heads * L
+    blas = [p["num_threads"] for p in threadpoolctl.threadpool_info() if p.get("user_api") == "blas"]
+    return {
+        "value": keys / dt, "unit": "keys/s", "cores": max(blas) if blas else 1, "kind": "oracle",
+        "sample": f"{n_layers} of {w.n_layers} layers x {w.n_kv_heads} KV heads x {L} keys of {w.name} "
+                  f"(sequence 0), {dt:.1f} s; matmul on the BLAS threads, the rest single-threaded",
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus must be 1 "
+              "(the path shards by layer / KV head / sequence with no communication, see DESIGN.md)",
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import paper_2603_11564_amd as D
+    import workloads as W
+    from dataclasses import replace
+
+    D.load_library()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = W.workload(args.workload, args.n_pseudo)
+    if args.layers is not None:
+        w = replace(w, n_layers=args.layers)
+
+    # ---------------------------------------------------------------- inputs (resident in HBM)
+    data = W.device_fill(w, args.seed, dev)
+    lens = data["lens"]
+    cu = data["cu_seqlens"] if w.ragged is not None else None
+    tokens = int(sum(lens))
+    k, v = data["k"], data["v"]
+    d, Hq, Hkv, N, nl, B = w.head_dim, w.n_q_heads, w.n_kv_heads, w.n_pseudo, w.n_layers, w.batch
+    if w.layout == "hnd":
+        kstr = (Hkv * tokens * d, 0, tokens * d, d)
+        rope_k = dict(stride_row=d, stride_head=tokens * d)
+    else:
+        kstr = (tokens * Hkv * d, 0, d, Hkv * d)
+        rope_k = dict(stride_row=Hkv * d, stride_head=d)
+    for li in range(nl):           # keys are cached already rotated; done once, outside the timed region
+        D.dapq_rope_apply(k[li], k[li], data["k_pos"], tokens, Hkv, d, rope_k["stride_row"],
+                          rope_k["stride_head"], w.theta, 0)
+    # pseudo queries laid out [batch][layer][Hq][N][d] so that one rope call covers a sequence
+    q_pre = data["q"].permute(1, 0, 2, 3, 4).contiguous()
+    q = torch.empty_like(q_pre)
+    qstr = (Hq * N * d, nl * Hq * N * d, N * d, d)
+    shape = D.make_shape(n_layers=nl, batch=B, n_q_heads=Hq, n_kv_heads=Hkv, n_pseudo=N, total_tokens=tokens,
+                         cu_seqlens=cu, k_strides=kstr, v_strides=kstr, q_strides=qstr, scale=w.scale)
+    ws = torch.empty(D.workspace_bytes(shape), dtype=torch.uint8, device=dev)
+    lse2 = torch.empty((nl, B, Hq, N), dtype=torch.float32, device=dev)
+    S = torch.empty((nl, Hkv, tokens), dtype=torch.float32, device=dev)
+    P = torch.empty_like(S)
+    idx = torch.zeros((nl, B, Hkv, w.budget), dtype=torch.int32, device=dev)
+    count = torch.zeros((nl, B, Hkv), dtype=torch.int32, device=dev)
+    k_out = torch.zeros((nl, B, Hkv, w.budget, d), dtype=torch.bfloat16, device=dev)
+    v_out = torch.zeros_like(k_out)
+    q_pos = data["q_pos"]
+    stream = torch.cuda.current_stream()
+
+    names = ["rope", "score_pass1", "score_pass2", "pool", "topk", "gather"]
+
+    def step(events=None):
+        def mark(i):
+            if events is not None:
+                events[i].record(stream)
+        mark(0)
+        for b in range(B):
+            D.dapq_rope_apply(q_pre[b], q[b], q_pos[b], N, nl * Hq, d, d, N * d, w.theta, 0, stream)
+        mark(1)
+        D.dapq_score_stats(shape, q, k, lse2, ws, stream)
+        mark(2)
+        D.dapq_score_accumulate(shape, q, k, lse2, S, ws, stream)
+        mark(3)
+        D.dapq_pool(shape, S, P, w.pool_width, stream)
+        mark(4)
+        D.dapq_topk(shape, P, w.budget, None, idx, count, None, stream)
+        mark(5)
+        D.dapq_gather(shape, k, v, idx, count, w.budget, k_out, v_out, stream)
+        mark(6)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(7)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(evs[s])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / args.steps
+    per = {n: float(np.mean([evs[s][i].elapsed_time(evs[s][i + 1]) for s in range(args.steps)]))
+           for i, n in enumerate(names)}
+
+    key_units = nl * Hkv * tokens
+    value = key_units / (ms_per_step * 1e-3)
+
+    # ---------------------------------------------------------------- roofline of the dominant kernel
+    # algorithmic bytes of one score pass: every key row once (2*d bytes) + the 4-byte score (pass 2)
+    # or nothing (pass 1), + the pseudo queries once per KV head
+    q_bytes = nl * B * Hq * N * d * 2
+    bytes_pass = {"score_pass1": key_units * 2 * d + q_bytes, "score_pass2": key_units * (2 * d + 4) + q_bytes}
+    dom = max(bytes_pass, key=lambda n: per[n])
+    achieved = bytes_pass[dom] / (per[dom] * 1e-3) / 1e9
+    flops_pass = 2.0 * key_units * (Hq // Hkv) * N * d
+    roofline = {
+        "bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
+        "algorithmic_bytes_per_launch": bytes_pass[dom], "avg_launch_ms": per[dom],
+        "mfma_tflops": flops_pass / (per[dom] * 1e-3) / 1e12,
+    }
+
+    out = {
+        "metric": "prompt keys scored+evicted/sec (all layers x KV heads)", "value": value, "unit": "keys/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {nl} layers, {Hq} q / {Hkv} kv heads, d {d}, batch {B}, "
+                               f"L_p {lens if w.ragged else lens[0]}, N {N}, budget {w.budget}, pool {w.pool_width}, "
+                               f"K layout {w.layout}"},
+        "kernel_ms": per,
+        "roofline": roofline,
+    }
+    ncpu = args.cpu_layers
+    if ncpu is None:
+        ncpu = max(1, min(nl, int(round(6 * (32768 * 8 * 256) / (lens[0] * Hkv * (Hq // Hkv) * N)))))
+    if ncpu > 0:
+        out["cpu_baseline"] = cpu_baseline(w, args.seed, min(ncpu, nl))
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,9 +1,9 @@
 // Position assignment (Sec. 4.1): rotary embedding of bf16 vectors at given absolute positions.
 // The pseudo queries get positions L_p .. L_p+N-1, the positions of the first N decode steps.
 //
-// One thread owns one (row, channel pair): it evaluates the angle pos * theta^(-2c/d) and its
-// sine / cosine once in fp64 and then walks the heads of that row, so the transcendental work is
-// shared by all heads.  fp64 keeps the angle exact enough at positions beyond 10^5 (an fp32
+// One thread owns one (row, channel pair) and a run of up to 8 heads: it evaluates the angle
+// pos * theta^(-2c/d) and its sine / cosine once in fp64 and then walks its heads, so the
+// transcendental work is shared by the heads of a run.  fp64 keeps the angle exact enough at positions beyond 10^5 (an fp32
 // product pos * omega would be off by ~1e-2 rad there); the result is rounded to bf16 once.
 #include <math.h>
 
@@ -28,6 +28,8 @@ __device__ __forceinline__ uint16_t f64_to_bf16(double x) {
   return (uint16_t)(hi + (up ? 1u : 0u));
 }
 
+constexpr int kHeadsPerThread = 8;
+
 __global__ void rope_kernel(const uint16_t* __restrict__ x_in, uint16_t* x_out, const int32_t* __restrict__ pos,
                             int64_t rows, int heads, int head_dim, int64_t stride_row, int64_t stride_head,
                             double neg_log2_theta_2_over_d, int pairing) {
@@ -43,11 +45,13 @@ __global__ void rope_kernel(const uint16_t* __restrict__ x_in, uint16_t* x_out, 
   const int ib = pairing == 0 ? c + half : 2 * c + 1;
   const uint16_t* src = x_in + row * stride_row;
   uint16_t* dst = x_out + row * stride_row;
-  for (int hd = 0; hd < heads; ++hd) {
-    const double a = bf16_to_f64(src[hd * stride_head + ia]);
-    const double b = bf16_to_f64(src[hd * stride_head + ib]);
-    dst[hd * stride_head + ia] = f64_to_bf16(a * cs - b * sn);
-    dst[hd * stride_head + ib] = f64_to_bf16(b * cs + a * sn);
+  const int hd0 = blockIdx.y * kHeadsPerThread;
+  const int hd1 = hd0 + kHeadsPerThread < heads ? hd0 + kHeadsPerThread : heads;
+  for (int hd = hd0; hd < hd1; ++hd) {
+    const double a = bf16_to_f64(src[(int64_t)hd * stride_head + ia]);
+    const double b = bf16_to_f64(src[(int64_t)hd * stride_head + ib]);
+    dst[(int64_t)hd * stride_head + ia] = f64_to_bf16(a * cs - b * sn);
+    dst[(int64_t)hd * stride_head + ib] = f64_to_bf16(b * cs + a * sn);
   }
 }
 
@@ -73,8 +77,11 @@ extern "C" DAPQ_API int dapq_rope_apply(const void* x_in, void* x_out, const int
   const int64_t work = rows * (head_dim / 2);
   DAPQ_REQUIRE(work / 256 < ((int64_t)1 << 31), DAPQ_ERR_UNSUPPORTED, "too many rows");
   if (work == 0) return DAPQ_OK;
+  const int64_t head_runs = ((int64_t)heads + kHeadsPerThread - 1) / kHeadsPerThread;
+  DAPQ_REQUIRE(head_runs <= 65535, DAPQ_ERR_UNSUPPORTED, "heads (%d) exceeds %d", heads, 65535 * kHeadsPerThread);
   const double e = -2.0 * log2(theta) / (double)head_dim;
-  hipLaunchKernelGGL(rope_kernel, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
+  hipLaunchKernelGGL(rope_kernel, dim3((unsigned)((work + 255) / 256), (unsigned)head_runs), dim3(256), 0,
+                     static_cast<hipStream_t>(stream),
                      static_cast<const uint16_t*>(x_in), static_cast<uint16_t*>(x_out), pos, rows, heads, head_dim,
                      stride_row, stride_head, e, pairing);
   DAPQ_HIP_LAUNCH_CHECK("rope_kernel");

@@ -27,6 +27,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));  // 16 bytes; native vector, stays in registers
 
 struct ScoreParams {
   const uint16_t* q;
@@ -89,16 +90,16 @@ __device__ __forceinline__ Work locate(const ScoreParams& p, int gchunk) {
 }
 
 // Coalesced 16-byte loads of one 128-key tile: thread t takes chunk (t & 15) of keys (t >> 4) + 16*i.
-__device__ __forceinline__ void tile_load(uint4 (&st)[8], const uint16_t* kbase, int64_t stride_token,
+// Branch-free: nkeys >= 1 and out-of-range rows are clamped to the last key of the chunk.
+__device__ __forceinline__ void tile_load(u32x4 (&st)[8], const uint16_t* kbase, int64_t stride_token,
                                           int tile_key0, int nkeys, int tid) {
   const int ch = tid & 15;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int key = (tid >> 4) + 16 * i;
-    const int gk = tile_key0 + key;
-    uint4 v = make_uint4(0u, 0u, 0u, 0u);
-    if (gk < nkeys) v = *reinterpret_cast<const uint4*>(kbase + (int64_t)gk * stride_token + ch * 8);
-    st[i] = v;
+    int gk = tile_key0 + key;
+    gk = gk < nkeys ? gk : nkeys - 1;  // rows past the end repeat the last key; callers mask or drop them
+    st[i] = *reinterpret_cast<const u32x4*>(kbase + (int64_t)gk * stride_token + ch * 8);
   }
 }
 
@@ -106,7 +107,7 @@ __device__ __forceinline__ void tile_load(uint4 (&st)[8], const uint16_t* kbase,
 // the row so that 16 consecutive rows reading the same logical chunk hit 16 different bank groups.
 __device__ __forceinline__ int lds_chunk_index(int key, int ch) { return key * 16 + (ch ^ (key & 15)); }
 
-__device__ __forceinline__ void tile_store(uint4* buf, const uint4 (&st)[8], int tid) {
+__device__ __forceinline__ void tile_store(u32x4* buf, const u32x4 (&st)[8], int tid) {
   const int ch = tid & 15;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
@@ -117,28 +118,22 @@ __device__ __forceinline__ void tile_store(uint4* buf, const uint4 (&st)[8], int
 
 // MFMA operand fragments of one 32-row sub-block held in LDS: fragment s of lane (n, h) is the
 // 8 channels [(2s+h)*8, +8) of row n.
-__device__ __forceinline__ void frag_from_lds(bf16x8 (&f)[8], const uint4* buf, int sub, int n, int h) {
+__device__ __forceinline__ void frag_from_lds(bf16x8 (&f)[8], const u32x4* buf, int sub, int n, int h) {
 #pragma unroll
   for (int s = 0; s < 8; ++s) {
-    const uint4 v = buf[lds_chunk_index(sub * 32 + n, 2 * s + h)];
+    const u32x4 v = buf[lds_chunk_index(sub * 32 + n, 2 * s + h)];
     f[s] = __builtin_bit_cast(bf16x8, v);
   }
 }
 
-// The same fragments for a 32-row block of Q read straight from global memory; rows >= p.rows are zero.
+// The same fragments for a 32-row block of Q read straight from global memory.
 __device__ __forceinline__ void frag_from_q(bf16x8 (&f)[8], const ScoreParams& p, const uint16_t* qbase, int row,
                                             int h) {
-  uint4 v[8];
+  const int rc = row < p.rows ? row : p.rows - 1;  // padding rows repeat the last row; their results are dropped
+  const int head = rc / p.n_pseudo, i = rc - head * p.n_pseudo;
+  const uint16_t* src = qbase + (int64_t)head * p.q_stride_head + (int64_t)i * p.q_stride_row;
 #pragma unroll
-  for (int s = 0; s < 8; ++s) v[s] = make_uint4(0u, 0u, 0u, 0u);
-  if (row < p.rows) {
-    const int head = row / p.n_pseudo, i = row - head * p.n_pseudo;
-    const uint16_t* src = qbase + (int64_t)head * p.q_stride_head + (int64_t)i * p.q_stride_row;
-#pragma unroll
-    for (int s = 0; s < 8; ++s) v[s] = *reinterpret_cast<const uint4*>(src + (2 * s + h) * 8);
-  }
-#pragma unroll
-  for (int s = 0; s < 8; ++s) f[s] = __builtin_bit_cast(bf16x8, v[s]);
+  for (int s = 0; s < 8; ++s) f[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(src + (2 * s + h) * 8));
 }
 
 __device__ __forceinline__ float xhalf(float v) { return __shfl_xor(v, 32, 64); }
@@ -147,11 +142,135 @@ __device__ __forceinline__ float xhalf(float v) { return __shfl_xor(v, 32, 64); 
 __device__ __forceinline__ int acc_row(int v, int h) { return 8 * (v >> 2) + 4 * h + (v & 3); }
 
 // ---------------------------------------------------------------------------------------------
+// Software-pipelined tiles.  A slice is one MFMA of the current unit followed by the exponentials of
+// two logits of the previous unit (2 FMAs, 2 adds of the exponentials issued one slice earlier,
+// 2 transcendentals), optionally one LDS fragment read for the next sub-block: the matrix pipe and
+// the vector pipe are both fed from a single wave, with no result consumed right after it issues.
+// ---------------------------------------------------------------------------------------------
+// The slice order is pinned with an empty asm statement after each slice that takes the slice's
+// results and the next slice's inputs as read-write operands: everything that produces them must
+// come before it, everything that consumes them after it.  It emits no instruction.
+#define DAPQ_SLICE_END(cur, prev, e0, e1, sa, sb, addr) \
+  asm volatile("" : "+v"(cur), "+v"(prev), "+v"(e0), "+v"(e1), "+v"(sa), "+v"(sb), "+v"(addr))
+
+__device__ __forceinline__ bf16x8 lds_frag(const u32x4* buf, int sub, int s, int n, int h) {
+  return __builtin_bit_cast(bf16x8, buf[lds_chunk_index(sub * 32 + n, 2 * s + h)]);
+}
+
+// Same fragment addressed from a per-lane base index lane_base = n*16 (in 16-byte units).
+__device__ __forceinline__ bf16x8 lds_frag_at(const u32x4* buf, int lane_base, int sub, int s, int n, int h) {
+  return __builtin_bit_cast(bf16x8, buf[lane_base + sub * 512 + ((2 * s + h) ^ (n & 15))]);
+}
+
+// ---------------------------------------------------------------------------------------------
 // Pass 1
 // ---------------------------------------------------------------------------------------------
+// One full tile, software pipelined: a "unit" is one 32-key sub-block against one 32-row block of
+// Q (8 MFMAs, 16 logits per lane).  While the MFMAs of unit u run, the lane exponentiates the
+// logits of unit u-1.  ref is fixed, so there is nothing to rescale.
+template <int RW>
+__device__ __forceinline__ void pass1_tile_pipelined(const u32x4* buf, const bf16x8 (&qf)[2][8], float c,
+                                                     const float (&ref)[2], float (&z)[2], int kw, int n, int h) {
+  constexpr int KW = 4 / RW, NSUB = 4 / KW, NUNIT = 2 * NSUB;
+  const float nref[2] = {-ref[0], -ref[1]};
+  bf16x8 kf[8];
+#pragma unroll
+  for (int s = 0; s < 8; ++s) kf[s] = lds_frag(buf, kw, s, n, h);
+  f32x16 prev = {0};
+#pragma unroll
+  for (int s = 0; s < 8; ++s) prev = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[0][s], prev, 0, 0, 0);
+  float e0 = 0.0f, e1 = 0.0f;  // exponentials issued in the previous slice, added in this one
+  float sa = 0.0f, sb = 0.0f;  // running sums of the unit whose exponentials are being added
+  int lane_base = n * 16;
+#pragma unroll
+  for (int u = 1; u < NUNIT; ++u) {
+    const int j = u >> 1, rb = u & 1, rbp = (u - 1) & 1;
+    const bool reload = rb == 1 && j + 1 < NSUB;
+    f32x16 cur = {0};
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[rb][s], cur, 0, 0, 0);
+      if (reload) kf[s] = lds_frag_at(buf, lane_base, kw + (j + 1) * KW, s, n, h);
+      const float x0 = fmaf(prev[2 * s], c, nref[rbp]);
+      const float x1 = fmaf(prev[2 * s + 1], c, nref[rbp]);
+      sa += e0;
+      sb += e1;
+      if (s == 0) {  // those were the last two logits of the unit before: close its sum
+        z[rbp ^ 1] += sa + sb;
+        sa = sb = 0.0f;
+      }
+      e0 = __builtin_amdgcn_exp2f(x0);
+      e1 = __builtin_amdgcn_exp2f(x1);
+      DAPQ_SLICE_END(cur, prev, e0, e1, sa, sb, lane_base);
+    }
+    prev = cur;
+  }
+#pragma unroll
+  for (int s = 0; s < 8; ++s) {
+    const float x0 = fmaf(prev[2 * s], c, nref[1]);
+    const float x1 = fmaf(prev[2 * s + 1], c, nref[1]);
+    sa += e0;
+    sb += e1;
+    if (s == 0) {
+      z[0] += sa + sb;
+      sa = sb = 0.0f;
+    }
+    e0 = __builtin_amdgcn_exp2f(x0);
+    e1 = __builtin_amdgcn_exp2f(x1);
+  }
+  z[1] += (sa + e0) + (sb + e1);
+}
+
+// One tile the plain way: handles partial tiles (keys >= nkeys are masked out), fixes the reference
+// logit on the wave's first sub-block (first), or tracks a running maximum (SAFE).
+template <int RW, bool SAFE>
+__device__ __forceinline__ void pass1_tile_simple(const u32x4* buf, const bf16x8 (&qf)[2][8], float c,
+                                                  float (&ref)[2], float (&z)[2], int tile_key0, int nkeys, bool& first,
+                                                  int kw, int n, int h) {
+  constexpr int KW = 4 / RW;
+  const bool full = tile_key0 + kTileKeys <= nkeys;
+#pragma unroll 1
+  for (int sub = kw; sub < 4; sub += KW) {
+    const int sub_key0 = tile_key0 + sub * 32;
+    if (sub_key0 >= nkeys) break;
+    bf16x8 kf[8];
+    frag_from_lds(kf, buf, sub, n, h);
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+      f32x16 acc = {0};
+#pragma unroll
+      for (int s = 0; s < 8; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[rb][s], acc, 0, 0, 0);
+      if (!full) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          if (sub_key0 + acc_row(v, h) >= nkeys) acc[v] = -INFINITY;
+      }
+      if (SAFE || first) {
+        float m = acc[0];
+#pragma unroll
+        for (int v = 1; v < 16; ++v) m = fmaxf(m, acc[v]);
+        m = fmaxf(m, xhalf(m)) * c;
+        if (SAFE) {
+          const float mnew = fmaxf(ref[rb], m);
+          z[rb] *= __builtin_amdgcn_exp2f(ref[rb] - mnew);
+          ref[rb] = mnew;
+        } else {
+          ref[rb] = m;
+        }
+      }
+      const float nref = -ref[rb];
+      float sum = 0.0f;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) sum += __builtin_amdgcn_exp2f(fmaf(acc[v], c, nref));
+      z[rb] += sum;
+    }
+    first = false;
+  }
+}
+
 template <int RW, bool SAFE>
 __device__ __forceinline__ bool pass1_chunk(const ScoreParams& p, const Work& w, const uint16_t* kbase,
-                                            const bf16x8 (&qf)[2][8], uint4* lds, float (&ref)[2], float (&z)[2]) {
+                                            const bf16x8 (&qf)[2][8], u32x4* lds, float (&ref)[2], float (&z)[2]) {
   constexpr int KW = 4 / RW;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, h = lane >> 5;
   const int kw = wave / RW;
@@ -161,52 +280,20 @@ __device__ __forceinline__ bool pass1_chunk(const ScoreParams& p, const Work& w,
   ref[0] = ref[1] = -INFINITY;
   z[0] = z[1] = 0.0f;
 
-  uint4 st[8];
+  u32x4 st[8];
   tile_load(st, kbase, p.k_stride_token, 0, w.nkeys, tid);
   for (int t = 0; t < ntiles; ++t) {
-    uint4* buf = lds + (t & 1) * (kTileBytes / 16);
+    u32x4* buf = lds + (t & 1) * (kTileBytes / 16);
     tile_store(buf, st, tid);
     __syncthreads();
-    if (t + 1 < ntiles) tile_load(st, kbase, p.k_stride_token, (t + 1) * kTileKeys, w.nkeys, tid);
+    // unconditional prefetch: past the last tile the clamped addresses re-read its last key
+    tile_load(st, kbase, p.k_stride_token, (t + 1) * kTileKeys, w.nkeys, tid);
     const int tile_key0 = t * kTileKeys;
-    const bool full = tile_key0 + kTileKeys <= w.nkeys;
-#pragma unroll 1
-    for (int sub = kw; sub < 4; sub += KW) {
-      const int sub_key0 = tile_key0 + sub * 32;
-      if (sub_key0 >= w.nkeys) break;
-      bf16x8 kf[8];
-      frag_from_lds(kf, buf, sub, n, h);
-#pragma unroll
-      for (int rb = 0; rb < 2; ++rb) {
-        f32x16 acc = {0};
-#pragma unroll
-        for (int s = 0; s < 8; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[rb][s], acc, 0, 0, 0);
-        if (!full) {
-#pragma unroll
-          for (int v = 0; v < 16; ++v)
-            if (sub_key0 + acc_row(v, h) >= w.nkeys) acc[v] = -INFINITY;
-        }
-        if (SAFE || first) {
-          float m = acc[0];
-#pragma unroll
-          for (int v = 1; v < 16; ++v) m = fmaxf(m, acc[v]);
-          m = fmaxf(m, xhalf(m)) * c;
-          if (SAFE) {
-            const float mnew = fmaxf(ref[rb], m);
-            z[rb] *= __builtin_amdgcn_exp2f(ref[rb] - mnew);
-            ref[rb] = mnew;
-          } else {
-            ref[rb] = m;
-          }
-        }
-        const float nref = -ref[rb];
-        float sum = 0.0f;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) sum += __builtin_amdgcn_exp2f(fmaf(acc[v], c, nref));
-        z[rb] += sum;
-      }
-      first = false;
-    }
+    // the first tile fixes the reference logits; full tiles after it take the pipelined path
+    if (!SAFE && t > 0 && tile_key0 + kTileKeys <= w.nkeys)
+      pass1_tile_pipelined<RW>(buf, qf, c, ref, z, kw, n, h);
+    else
+      pass1_tile_simple<RW, SAFE>(buf, qf, c, ref, z, tile_key0, w.nkeys, first, kw, n, h);
   }
   __syncthreads();  // every wave is done with the last tile before a caller reuses the buffers
   // a sum that is not finite means a logit sat more than ~127 binades above the reference
@@ -216,7 +303,7 @@ __device__ __forceinline__ bool pass1_chunk(const ScoreParams& p, const Work& w,
 
 template <int RW>
 __global__ __launch_bounds__(kThreads, 2) void score_pass1_kernel(ScoreParams p) {
-  extern __shared__ uint4 lds[];
+  extern __shared__ u32x4 lds[];
   constexpr int KW = 4 / RW;
   const Work w = locate(p, blockIdx.x);
   if (w.nkeys == 0) return;
@@ -299,9 +386,88 @@ __global__ void score_combine_kernel(ScoreParams p, int key_waves) {
 // ---------------------------------------------------------------------------------------------
 // Pass 2
 // ---------------------------------------------------------------------------------------------
+// Column sums of one full tile, software pipelined like pass 1; nb holds -lse2 of the lane's rows.
 template <int RW>
+__device__ __forceinline__ void pass2_tile_pipelined(const u32x4* buf, const bf16x8 (&qf)[2][8], float c,
+                                                     const float (&nb)[2][16], float (&col)[4], int kw, int n, int h) {
+  constexpr int KW = 4 / RW, NSUB = 4 / KW, NUNIT = 2 * NSUB;
+  bf16x8 kf[8];
+#pragma unroll
+  for (int s = 0; s < 8; ++s) kf[s] = lds_frag(buf, kw, s, n, h);
+  f32x16 prev = {0};
+#pragma unroll
+  for (int s = 0; s < 8; ++s) prev = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[0][s], kf[s], prev, 0, 0, 0);
+  float e0 = 0.0f, e1 = 0.0f;  // exponentials issued in the previous slice, added in this one
+  float sa = 0.0f, sb = 0.0f;  // running sums of the unit whose exponentials are being added
+  int lane_base = n * 16;
+#pragma unroll
+  for (int u = 1; u < NUNIT; ++u) {
+    const int j = u >> 1, rb = u & 1, rbp = (u - 1) & 1;
+    const int jpp = u >= 2 ? (u - 2) >> 1 : 0;  // sub-block of the unit before the previous one
+    const bool reload = rb == 1 && j + 1 < NSUB;
+    f32x16 cur = {0};
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][s], kf[s], cur, 0, 0, 0);
+      if (reload) kf[s] = lds_frag_at(buf, lane_base, kw + (j + 1) * KW, s, n, h);
+      const float x0 = fmaf(prev[2 * s], c, nb[rbp][2 * s]);
+      const float x1 = fmaf(prev[2 * s + 1], c, nb[rbp][2 * s + 1]);
+      sa += e0;
+      sb += e1;
+      if (s == 0) {  // those were the last two logits of the unit before: close its sum
+        col[jpp] += sa + sb;
+        sa = sb = 0.0f;
+      }
+      e0 = __builtin_amdgcn_exp2f(x0);
+      e1 = __builtin_amdgcn_exp2f(x1);
+      DAPQ_SLICE_END(cur, prev, e0, e1, sa, sb, lane_base);
+    }
+    prev = cur;
+  }
+#pragma unroll
+  for (int s = 0; s < 8; ++s) {
+    const float x0 = fmaf(prev[2 * s], c, nb[1][2 * s]);
+    const float x1 = fmaf(prev[2 * s + 1], c, nb[1][2 * s + 1]);
+    sa += e0;
+    sb += e1;
+    if (s == 0) {
+      col[(NUNIT - 2) >> 1] += sa + sb;
+      sa = sb = 0.0f;
+    }
+    e0 = __builtin_amdgcn_exp2f(x0);
+    e1 = __builtin_amdgcn_exp2f(x1);
+  }
+  col[NSUB - 1] += (sa + e0) + (sb + e1);
+}
+
+// The plain way, for partial tiles and when the Q slab changes per super-group.
+template <int RW>
+__device__ __forceinline__ void pass2_tile_simple(const u32x4* buf, const bf16x8 (&qf)[2][8], float c,
+                                                  const float (&nb)[2][16], float (&col)[4], int tile_key0, int nkeys,
+                                                  int kw, int n, int h) {
+  constexpr int KW = 4 / RW, NSUB = 4 / KW;
+#pragma unroll
+  for (int j = 0; j < NSUB; ++j) {
+    const int sub = kw + j * KW;
+    if (tile_key0 + sub * 32 >= nkeys) continue;
+    bf16x8 kf[8];
+    frag_from_lds(kf, buf, sub, n, h);
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+      f32x16 acc = {0};
+#pragma unroll
+      for (int s = 0; s < 8; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][s], kf[s], acc, 0, 0, 0);
+      float sum = 0.0f;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) sum += __builtin_amdgcn_exp2f(fmaf(acc[v], c, nb[rb][v]));
+      col[j] += sum;
+    }
+  }
+}
+
+template <int RW, bool MULTI>
 __global__ __launch_bounds__(kThreads, 2) void score_pass2_kernel(ScoreParams p) {
-  extern __shared__ uint4 lds[];
+  extern __shared__ u32x4 lds[];
   constexpr int KW = 4 / RW;
   constexpr int NSUB = 4 / KW;  // sub-blocks of a tile per wave
   float* red = reinterpret_cast<float*>(lds + kLdsScore / 16);  // [RW][128] partial column sums
@@ -319,7 +485,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_pass2_kernel(ScoreParams p)
   const float* lse = p.lse2 + (((int64_t)layer * p.batch + w.seq) * p.n_q_heads + (int64_t)kv * p.group) * p.n_pseudo;
   float* out = p.scores + ((int64_t)layer * p.n_kv_heads + kv) * p.total_tokens + w.tok0;
 
-  // Q slab and the normalisers of its rows; reloaded per super-group when R > RW*64.
+  // Q slab and the normalisers of its rows; reloaded per super-group when R > RW*64 (MULTI).
   bf16x8 qf[2][8];
   float nb[2][16];  // -lse2 of the lane's accumulator rows; -inf for padding rows, which then add 0
   auto load_slab = [&](int sg) {
@@ -331,43 +497,34 @@ __global__ __launch_bounds__(kThreads, 2) void score_pass2_kernel(ScoreParams p)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = row0 + rb * 32 + acc_row(v, h);
-        nb[rb][v] = row < p.rows ? -lse[row] : -INFINITY;  // rows are laid out head-major: row = head*N + i
+        const int rc = row < p.rows ? row : p.rows - 1;
+        const float l = lse[rc];  // rows are laid out head-major: row = head*N + i
+        nb[rb][v] = row < p.rows ? -l : -INFINITY;
       }
   };
-  if (p.n_super == 1) load_slab(0);
+  if (!MULTI) load_slab(0);
 
   const int ntiles = (w.nkeys + kTileKeys - 1) / kTileKeys;
-  uint4 st[8];
+  u32x4 st[8];
   tile_load(st, kbase, p.k_stride_token, 0, w.nkeys, tid);
   for (int t = 0; t < ntiles; ++t) {
-    uint4* buf = lds + (t & 1) * (kTileBytes / 16);
+    u32x4* buf = lds + (t & 1) * (kTileBytes / 16);
     tile_store(buf, st, tid);
     __syncthreads();
-    if (t + 1 < ntiles) tile_load(st, kbase, p.k_stride_token, (t + 1) * kTileKeys, w.nkeys, tid);
+    // unconditional prefetch: past the last tile the clamped addresses re-read its last key
+    tile_load(st, kbase, p.k_stride_token, (t + 1) * kTileKeys, w.nkeys, tid);
     const int tile_key0 = t * kTileKeys;
 
-    float col[NSUB];
-#pragma unroll
-    for (int j = 0; j < NSUB; ++j) col[j] = 0.0f;
-    for (int sg = 0; sg < p.n_super; ++sg) {
-      if (p.n_super > 1) load_slab(sg);
-#pragma unroll
-      for (int j = 0; j < NSUB; ++j) {
-        const int sub = kw + j * KW;
-        if (tile_key0 + sub * 32 >= w.nkeys) continue;
-        bf16x8 kf[8];
-        frag_from_lds(kf, buf, sub, n, h);
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-          f32x16 acc = {0};
-#pragma unroll
-          for (int s = 0; s < 8; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][s], kf[s], acc, 0, 0, 0);
-          float sum = 0.0f;
-#pragma unroll
-          for (int v = 0; v < 16; ++v) sum += __builtin_amdgcn_exp2f(fmaf(acc[v], c, nb[rb][v]));
-          col[j] += sum;
-        }
+    float col[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (MULTI) {
+      for (int sg = 0; sg < p.n_super; ++sg) {
+        load_slab(sg);
+        pass2_tile_simple<RW>(buf, qf, c, nb, col, tile_key0, w.nkeys, kw, n, h);
       }
+    } else if (tile_key0 + kTileKeys <= w.nkeys) {
+      pass2_tile_pipelined<RW>(buf, qf, c, nb, col, kw, n, h);
+    } else {
+      pass2_tile_simple<RW>(buf, qf, c, nb, col, tile_key0, w.nkeys, kw, n, h);
     }
     // lane halves hold different query rows of the same key; then add the RW slabs through LDS
 #pragma unroll
@@ -454,20 +611,21 @@ int launch_accumulate(const dapq_shape* s, const ScorePlan& plan, ScoreParams p,
   const dim3 grid((unsigned)plan.max_chunks, 1, (unsigned)(s->n_layers * s->n_kv_heads));
   const int lds_bytes = kLdsScore + 4 * kTileKeys * (int)sizeof(float);
   int rc = DAPQ_OK;
-  switch (plan.row_waves) {
-    case 1:
-      if ((rc = set_lds(score_pass2_kernel<1>, lds_bytes)) != DAPQ_OK) return rc;
-      hipLaunchKernelGGL(score_pass2_kernel<1>, grid, dim3(kThreads), lds_bytes, stream, p);
-      break;
-    case 2:
-      if ((rc = set_lds(score_pass2_kernel<2>, lds_bytes)) != DAPQ_OK) return rc;
-      hipLaunchKernelGGL(score_pass2_kernel<2>, grid, dim3(kThreads), lds_bytes, stream, p);
-      break;
-    default:
-      if ((rc = set_lds(score_pass2_kernel<4>, lds_bytes)) != DAPQ_OK) return rc;
-      hipLaunchKernelGGL(score_pass2_kernel<4>, grid, dim3(kThreads), lds_bytes, stream, p);
-      break;
+#define DAPQ_LAUNCH_P2(RWV, MULTIV)                                                                       \
+  do {                                                                                                    \
+    if ((rc = set_lds(score_pass2_kernel<RWV, MULTIV>, lds_bytes)) != DAPQ_OK) return rc;                 \
+    hipLaunchKernelGGL((score_pass2_kernel<RWV, MULTIV>), grid, dim3(kThreads), lds_bytes, stream, p);    \
+  } while (0)
+  if (plan.n_super > 1) {
+    DAPQ_LAUNCH_P2(4, true);  // more than 256 rows always uses four row waves
+  } else if (plan.row_waves == 1) {
+    DAPQ_LAUNCH_P2(1, false);
+  } else if (plan.row_waves == 2) {
+    DAPQ_LAUNCH_P2(2, false);
+  } else {
+    DAPQ_LAUNCH_P2(4, false);
   }
+#undef DAPQ_LAUNCH_P2
   DAPQ_HIP_LAUNCH_CHECK("score_pass2_kernel");
   return DAPQ_OK;
 }
