@@ -52,6 +52,8 @@ int check_shape(const dapq_shape* s, bool need_q, bool need_k, bool need_v) {
     DAPQ_REQUIRE(stride_ok(s->k_stride_layer) && stride_ok(s->k_stride_seq) && stride_ok(s->k_stride_head) &&
                      stride_ok(s->k_stride_token) && s->k_stride_token >= kHeadDim,
                  DAPQ_ERR_UNSUPPORTED, "k strides must be non-negative multiples of 8 elements (token >= 128)");
+    DAPQ_REQUIRE(s->k_stride_token < ((int64_t)1 << 26), DAPQ_ERR_UNSUPPORTED,
+                 "k_stride_token (%lld) must be below 2^26 elements", (long long)s->k_stride_token);
   }
   if (need_v) {
     DAPQ_REQUIRE(stride_ok(s->v_stride_layer) && stride_ok(s->v_stride_seq) && stride_ok(s->v_stride_head) &&

@@ -18,6 +18,11 @@
 // Pass 1 does not track a running maximum: it exponentiates against a per-row reference logit taken
 // from the first sub-block (2^x has 127 binades of headroom above it) and only if a sum overflows
 // redoes the chunk with a conventional online maximum.
+//
+// The vector ALU is the busiest unit of this kernel (one FMA, one exponential, one add per logit),
+// the matrix pipe second, so the full tiles run software pipelined from a single wave: while the
+// MFMAs of one (sub-block, row block) unit execute, the lane exponentiates the logits of the unit
+// before it, across tile boundaries, with one barrier per tile.
 #include <math.h>
 
 #include "dapq_internal.h"
@@ -47,7 +52,9 @@ struct ScoreParams {
 
 constexpr int kThreads = 256;
 constexpr int kTileBytes = kTileKeys * kHeadDim * 2;  // 32 KB
+constexpr int kTileVec = kTileBytes / 16;             // 16-byte chunks per tile
 constexpr int kLdsScore = 2 * kTileBytes;
+constexpr int kSubBytes = 32 * kHeadDim * 2;          // one 32-key sub-block
 
 // Which (sequence, chunk) a workgroup works on.
 struct Work {
@@ -116,6 +123,47 @@ __device__ __forceinline__ void tile_store(u32x4* buf, const u32x4 (&st)[8], int
   }
 }
 
+// The same tile moved straight from global memory into LDS (global_load_lds_dwordx4): no staging
+// registers, no LDS store instructions.  Each wave instruction fills 1 KB = 4 tile rows; the lane
+// that owns LDS slot (row, pos) fetches the logical chunk pos ^ (row & 15), which is the swizzle of
+// lds_chunk_index.  Nothing is issued for a tile that starts past the end of the chunk.  The data
+// is in LDS once the issuing wave's vmcnt has drained (tile_dma_wait) and a barrier has passed.
+__device__ __forceinline__ void tile_dma(u32x4* buf, const uint16_t* kbase, int64_t stride_token, int tile_key0,
+                                         int nkeys, int tid) {
+  if (tile_key0 >= nkeys) return;
+  const int wave = tid >> 6, lane = tid & 63;
+  const int row0 = wave * 4 + (lane >> 4);  // tile rows of this lane: row0 + 16*i
+  const int ch = (lane & 15) ^ (row0 & 15);
+  if (tile_key0 + kTileKeys <= nkeys) {
+    // full tile: one per-lane byte offset for all eight transfers, the rest is a uniform base
+    const unsigned lane_off = (unsigned)row0 * (unsigned)stride_token * 2u + (unsigned)ch * 16u;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const char* base = reinterpret_cast<const char*>(kbase + (int64_t)(tile_key0 + 16 * i) * stride_token);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(base + lane_off),
+                                       (__attribute__((address_space(3))) void*)(buf + (i * 4 + wave) * 64), 16, 0, 0);
+    }
+  } else {
+    // partial tile: rows past the end repeat the last key; callers mask or drop them
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      int gk = tile_key0 + row0 + 16 * i;
+      gk = gk < nkeys ? gk : nkeys - 1;
+      const uint16_t* src = kbase + (int64_t)gk * stride_token + ch * 8;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                       (__attribute__((address_space(3))) void*)(buf + (i * 4 + wave) * 64), 16, 0, 0);
+    }
+  }
+}
+
+// Waits until at most `pending` of this wave's vector memory operations are still in flight.
+template <int pending>
+__device__ __forceinline__ void tile_dma_wait() {
+  static_assert(pending == 0 || pending == 8, "only the two counts the kernels use");
+  if (pending == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+}
+
 // MFMA operand fragments of one 32-row sub-block held in LDS: fragment s of lane (n, h) is the
 // 8 channels [(2s+h)*8, +8) of row n.
 __device__ __forceinline__ void frag_from_lds(bf16x8 (&f)[8], const u32x4* buf, int sub, int n, int h) {
@@ -142,85 +190,180 @@ __device__ __forceinline__ float xhalf(float v) { return __shfl_xor(v, 32, 64); 
 __device__ __forceinline__ int acc_row(int v, int h) { return 8 * (v >> 2) + 4 * h + (v & 3); }
 
 // ---------------------------------------------------------------------------------------------
-// Software-pipelined tiles.  A slice is one MFMA of the current unit followed by the exponentials of
-// two logits of the previous unit (2 FMAs, 2 adds of the exponentials issued one slice earlier,
-// 2 transcendentals), optionally one LDS fragment read for the next sub-block: the matrix pipe and
-// the vector pipe are both fed from a single wave, with no result consumed right after it issues.
+// Software-pipelined walk over the full tiles of a chunk (both passes).
+//
+// A unit is one 32-key sub-block against one 32-row block of Q: 8 MFMAs, 16 logits per lane.  A
+// slice is one MFMA of the current unit plus the exponentials of two logits of the previous unit
+// (2 FMAs, the 2 adds of the exponentials issued one slice earlier, 2 transcendentals) and, in the
+// second row block of a sub-block, one LDS fragment read for the next sub-block.  The slice order
+// is pinned with an empty asm statement after each slice that takes the slice's results and the
+// next slice's inputs as read-write operands: what produces them must come before it, what
+// consumes them after it.  It emits no instruction.
 // ---------------------------------------------------------------------------------------------
-// The slice order is pinned with an empty asm statement after each slice that takes the slice's
-// results and the next slice's inputs as read-write operands: everything that produces them must
-// come before it, everything that consumes them after it.  It emits no instruction.
 #define DAPQ_SLICE_END(cur, prev, e0, e1, sa, sb, addr) \
   asm volatile("" : "+v"(cur), "+v"(prev), "+v"(e0), "+v"(e1), "+v"(sa), "+v"(sb), "+v"(addr))
 
-__device__ __forceinline__ bf16x8 lds_frag(const u32x4* buf, int sub, int s, int n, int h) {
-  return __builtin_bit_cast(bf16x8, buf[lds_chunk_index(sub * 32 + n, 2 * s + h)]);
+typedef const u32x4 __attribute__((address_space(3))) * lds_vec_ptr;
+
+// 16-byte LDS read at a per-lane byte address plus a compile-time offset (folds into the instruction).
+__device__ __forceinline__ bf16x8 lds_read16(unsigned lane_addr, int const_off) {
+  return __builtin_bit_cast(bf16x8, *(lds_vec_ptr)(uintptr_t)(lane_addr + const_off));
 }
 
-// Same fragment addressed from a per-lane base index lane_base = n*16 (in 16-byte units).
-__device__ __forceinline__ bf16x8 lds_frag_at(const u32x4* buf, int lane_base, int sub, int s, int n, int h) {
-  return __builtin_bit_cast(bf16x8, buf[lane_base + sub * 512 + ((2 * s + h) ^ (n & 15))]);
-}
-
-// ---------------------------------------------------------------------------------------------
-// Pass 1
-// ---------------------------------------------------------------------------------------------
-// One full tile, software pipelined: a "unit" is one 32-key sub-block against one 32-row block of
-// Q (8 MFMAs, 16 logits per lane).  While the MFMAs of unit u run, the lane exponentiates the
-// logits of unit u-1.  ref is fixed, so there is nothing to rescale.
+// Column sums of a tile -> S (pass 2): lane halves hold different query rows of the same key (one
+// shuffle), the RW slabs of a workgroup are added through LDS by the first 128 threads after a barrier.
 template <int RW>
-__device__ __forceinline__ void pass1_tile_pipelined(const u32x4* buf, const bf16x8 (&qf)[2][8], float c,
-                                                     const float (&ref)[2], float (&z)[2], int kw, int n, int h) {
+__device__ __forceinline__ void publish_columns(float* red, const float* col, int kw, int rw, int n, int h) {
+  constexpr int KW = 4 / RW, NSUB = 4 / KW;
+#pragma unroll
+  for (int j = 0; j < NSUB; ++j) {
+    const float v = col[j] + xhalf(col[j]);
+    if (h == 0) red[rw * kTileKeys + (kw + j * KW) * 32 + n] = v;
+  }
+}
+
+template <int RW>
+__device__ __forceinline__ void store_columns(const float* red, float* out, int tile_key0, int nkeys, int tid) {
+  if (tid < kTileKeys && tile_key0 + tid < nkeys) {
+    float s = red[tid];
+#pragma unroll
+    for (int r = 1; r < RW; ++r) s += red[r * kTileKeys + tid];
+    out[tile_key0 + tid] = s;
+  }
+}
+
+// Entry contract of walk_tiles: tile t0 is in buffer t0 & 1 (landed and fenced) and the transfer of
+// tile t0+1 into the other buffer has been started.  On return every transfer has landed and tile t1
+// (the partial last tile, if the chunk has one) is in buffer t1 & 1, fenced.
+//
+// State of the pipelined walk.  Plain locals of the one function that owns the loop (walk_tiles), so
+// that all of it stays in registers; the macros below are that function's body, unit by unit.
+//
+//   kf[8]   fragments of the sub-block whose MFMAs run next
+//   prev    logits of the unit whose exponentials are being taken (cur: the unit being multiplied)
+//   e0,e1   exponentials issued in the previous slice, added in the next
+//   sa,sb   running sums of the unit being added up
+//   fa[8]   per-lane LDS byte address of fragment s of the wave's first sub-block (constant)
+//   acc[]   pass 1: zsum[2] row sums; pass 2: colp[NSUB] / colc[NSUB] column sums of the previous /
+//           current tile (the last two units of a tile finish during the next one)
+template <int RW, int PASS>
+__device__ __forceinline__ void walk_tiles(u32x4* lds, const uint16_t* kbase, int64_t stride_token, int nkeys,
+                                           int t0, int t1, const bf16x8 (&qf)[2][8], float c,
+                                           const float (&off)[2][16], float (&zsum)[2], float* red, float* out,
+                                           int tid, int kw, int rw, int n, int h) {
   constexpr int KW = 4 / RW, NSUB = 4 / KW, NUNIT = 2 * NSUB;
-  const float nref[2] = {-ref[0], -ref[1]};
+  constexpr int kRed = RW * kTileKeys;
+  constexpr int LAG = NUNIT == 2 ? 2 : 1;  // pass 2: tiles by which the store to S trails (see below)
+  const unsigned lds_base = (unsigned)(uintptr_t)(lds_vec_ptr)lds;
+  unsigned fa[8];
+#pragma unroll
+  for (int s = 0; s < 8; ++s)
+    fa[s] = lds_base + (unsigned)(n * 16 + ((2 * s + h) ^ (n & 15))) * 16u + (unsigned)(kw * kSubBytes);
   bf16x8 kf[8];
 #pragma unroll
-  for (int s = 0; s < 8; ++s) kf[s] = lds_frag(buf, kw, s, n, h);
-  f32x16 prev = {0};
+  for (int s = 0; s < 8; ++s) kf[s] = lds_read16(fa[s] + (t0 & 1) * kTileBytes, 0);
+  f32x16 prev;
 #pragma unroll
-  for (int s = 0; s < 8; ++s) prev = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[0][s], prev, 0, 0, 0);
-  float e0 = 0.0f, e1 = 0.0f;  // exponentials issued in the previous slice, added in this one
-  float sa = 0.0f, sb = 0.0f;  // running sums of the unit whose exponentials are being added
-  int lane_base = n * 16;
+  for (int v = 0; v < 16; ++v) prev[v] = -INFINITY;  // 2^(-inf) = 0: the first slices add nothing
+  float e0 = 0.0f, e1 = 0.0f, sa = 0.0f, sb = 0.0f;
+  float colp[NSUB], colc[NSUB];
 #pragma unroll
-  for (int u = 1; u < NUNIT; ++u) {
-    const int j = u >> 1, rb = u & 1, rbp = (u - 1) & 1;
-    const bool reload = rb == 1 && j + 1 < NSUB;
-    f32x16 cur = {0};
+  for (int j = 0; j < NSUB; ++j) colp[j] = colc[j] = 0.0f;
+  zsum[0] = zsum[1] = 0.0f;
+
+  for (int t = t0; t < t1; ++t) {
+    // two copies of the tile body so that the buffer offsets are instruction immediates
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[rb][s], cur, 0, 0, 0);
-      if (reload) kf[s] = lds_frag_at(buf, lane_base, kw + (j + 1) * KW, s, n, h);
-      const float x0 = fmaf(prev[2 * s], c, nref[rbp]);
-      const float x1 = fmaf(prev[2 * s + 1], c, nref[rbp]);
-      sa += e0;
-      sb += e1;
-      if (s == 0) {  // those were the last two logits of the unit before: close its sum
-        z[rbp ^ 1] += sa + sb;
-        sa = sb = 0.0f;
+    for (int par = 0; par < 2; ++par) {
+      if ((t & 1) != par) continue;
+      const int cur_base = par * kTileBytes, nxt_base = (par ^ 1) * kTileBytes;
+#pragma unroll
+      for (int u = 0; u < NUNIT; ++u) {
+        const int j = u >> 1, rb = u & 1, rbp = rb ^ 1;
+        if (u == NUNIT - 1) {
+          // before the last unit: its fragment reads reach into the next tile, whose transfer was
+          // started a tile ago and must have landed; every wave is past its reads of this tile's
+          // buffer, so the tile after next can start to overwrite it
+          tile_dma_wait<0>();
+          __syncthreads();  // also fences the column sums published since the previous barrier
+          tile_dma(lds + (t & 1) * kTileVec, kbase, stride_token, (t + 2) * kTileKeys, nkeys, tid);
+          if (PASS == 2 && t - t0 >= LAG)
+            store_columns<RW>(red + ((t - LAG) & 1) * kRed, out, (t - LAG) * kTileKeys, nkeys, tid);
+        }
+        f32x16 cur = {0};
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+          if (PASS == 1) cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[rb][s], cur, 0, 0, 0);
+          else cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][s], kf[s], cur, 0, 0, 0);
+          if (rb == 1) {  // last use of this fragment: fetch the next sub-block's into its place
+            if (j + 1 < NSUB) kf[s] = lds_read16(fa[s], cur_base + (j + 1) * KW * kSubBytes);
+            else kf[s] = lds_read16(fa[s], nxt_base);
+          }
+          const float x0 = fmaf(prev[2 * s], c, PASS == 1 ? off[rbp][0] : off[rbp][2 * s]);
+          const float x1 = fmaf(prev[2 * s + 1], c, PASS == 1 ? off[rbp][0] : off[rbp][2 * s + 1]);
+          sa += e0;
+          sb += e1;
+          if (s == 0) {  // those were the last two logits of unit u-2: bank its sum
+            const float total = sa + sb;
+            sa = sb = 0.0f;
+            if (PASS == 1) zsum[rb] += total;                  // unit u-2 has the row block of u
+            else if (u >= 2) colc[(u - 2) >> 1] += total;
+            else colp[NSUB - 1] += total;                      // the last two units of the previous tile
+          }
+          e0 = __builtin_amdgcn_exp2f(x0);
+          e1 = __builtin_amdgcn_exp2f(x1);
+          DAPQ_SLICE_END(cur, prev, e0, e1, sa, sb, fa[(s + 1) & 7]);
+          if (PASS == 2 && u == 1 && s == 0 && t > t0)  // the previous tile's column sums are complete
+            publish_columns<RW>(red + ((t - 1) & 1) * kRed, colp, kw, rw, n, h);
+        }
+        prev = cur;
       }
-      e0 = __builtin_amdgcn_exp2f(x0);
-      e1 = __builtin_amdgcn_exp2f(x1);
-      DAPQ_SLICE_END(cur, prev, e0, e1, sa, sb, lane_base);
+      if (PASS == 2) {
+#pragma unroll
+        for (int j = 0; j < NSUB; ++j) {
+          colp[j] = colc[j];
+          colc[j] = 0.0f;
+        }
+      }
     }
-    prev = cur;
   }
+
+  // drain: the exponentials of the last unit, with no MFMAs to hide behind
 #pragma unroll
   for (int s = 0; s < 8; ++s) {
-    const float x0 = fmaf(prev[2 * s], c, nref[1]);
-    const float x1 = fmaf(prev[2 * s + 1], c, nref[1]);
+    const float x0 = fmaf(prev[2 * s], c, PASS == 1 ? off[1][0] : off[1][2 * s]);
+    const float x1 = fmaf(prev[2 * s + 1], c, PASS == 1 ? off[1][0] : off[1][2 * s + 1]);
     sa += e0;
     sb += e1;
-    if (s == 0) {
-      z[0] += sa + sb;
+    if (s == 0) {  // closes unit NUNIT-2 of the last tile (row block 0, last sub-block)
+      if (PASS == 1) zsum[0] += sa + sb;
+      else colp[NSUB - 1] += sa + sb;
       sa = sb = 0.0f;
     }
     e0 = __builtin_amdgcn_exp2f(x0);
     e1 = __builtin_amdgcn_exp2f(x1);
   }
-  z[1] += (sa + e0) + (sb + e1);
+  const float total = (sa + e0) + (sb + e1);
+  tile_dma_wait<0>();  // the transfer started before the last unit (a tile nobody reads, if any)
+  if (PASS == 1) {
+    zsum[1] += total;
+    __syncthreads();
+  } else {
+    // The column sums of tile t are published after slice 0 of unit 1 of tile t+1; the barrier that
+    // follows is the one before the last unit, so the store trails by LAG tiles (2 when a tile has
+    // only two units and that barrier comes first).  Flush what is left.
+    colp[NSUB - 1] += total;
+    publish_columns<RW>(red + ((t1 - 1) & 1) * kRed, colp, kw, rw, n, h);
+    __syncthreads();
+    if (LAG == 2 && t1 - t0 >= 2)
+      store_columns<RW>(red + ((t1 - 2) & 1) * kRed, out, (t1 - 2) * kTileKeys, nkeys, tid);
+    store_columns<RW>(red + ((t1 - 1) & 1) * kRed, out, (t1 - 1) * kTileKeys, nkeys, tid);
+  }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Pass 1
+// ---------------------------------------------------------------------------------------------
 // One tile the plain way: handles partial tiles (keys >= nkeys are masked out), fixes the reference
 // logit on the wave's first sub-block (first), or tracks a running maximum (SAFE).
 template <int RW, bool SAFE>
@@ -268,37 +411,64 @@ __device__ __forceinline__ void pass1_tile_simple(const u32x4* buf, const bf16x8
   }
 }
 
+// The plain walk: every tile through pass1_tile_simple (the overflow redo, and chunks with fewer
+// than two full tiles).
 template <int RW, bool SAFE>
-__device__ __forceinline__ bool pass1_chunk(const ScoreParams& p, const Work& w, const uint16_t* kbase,
-                                            const bf16x8 (&qf)[2][8], u32x4* lds, float (&ref)[2], float (&z)[2]) {
-  constexpr int KW = 4 / RW;
+__device__ __forceinline__ void pass1_chunk_simple(const ScoreParams& p, const Work& w, const uint16_t* kbase,
+                                                   const bf16x8 (&qf)[2][8], u32x4* lds, float (&ref)[2], float (&z)[2]) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, h = lane >> 5;
   const int kw = wave / RW;
-  const float c = p.c;
   const int ntiles = (w.nkeys + kTileKeys - 1) / kTileKeys;
   bool first = !SAFE;
   ref[0] = ref[1] = -INFINITY;
   z[0] = z[1] = 0.0f;
-
   u32x4 st[8];
   tile_load(st, kbase, p.k_stride_token, 0, w.nkeys, tid);
   for (int t = 0; t < ntiles; ++t) {
-    u32x4* buf = lds + (t & 1) * (kTileBytes / 16);
+    u32x4* buf = lds + (t & 1) * kTileVec;
     tile_store(buf, st, tid);
     __syncthreads();
-    // unconditional prefetch: past the last tile the clamped addresses re-read its last key
     tile_load(st, kbase, p.k_stride_token, (t + 1) * kTileKeys, w.nkeys, tid);
-    const int tile_key0 = t * kTileKeys;
-    // the first tile fixes the reference logits; full tiles after it take the pipelined path
-    if (!SAFE && t > 0 && tile_key0 + kTileKeys <= w.nkeys)
-      pass1_tile_pipelined<RW>(buf, qf, c, ref, z, kw, n, h);
-    else
-      pass1_tile_simple<RW, SAFE>(buf, qf, c, ref, z, tile_key0, w.nkeys, first, kw, n, h);
+    pass1_tile_simple<RW, SAFE>(buf, qf, p.c, ref, z, t * kTileKeys, w.nkeys, first, kw, n, h);
   }
-  __syncthreads();  // every wave is done with the last tile before a caller reuses the buffers
-  // a sum that is not finite means a logit sat more than ~127 binades above the reference
-  const bool bad = !(z[0] < INFINITY) || !(z[1] < INFINITY);
-  return bad;
+  __syncthreads();  // every wave is done with the last tile before the buffers are reused
+}
+
+// The fast walk: tile 0 the plain way (it fixes the reference logits), full tiles 1.. pipelined,
+// a partial last tile the plain way again.  Needs at least two full tiles.
+template <int RW>
+__device__ __forceinline__ void pass1_chunk_pipelined(const ScoreParams& p, const Work& w, const uint16_t* kbase,
+                                                      const bf16x8 (&qf)[2][8], u32x4* lds, float (&ref)[2],
+                                                      float (&z)[2]) {
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, h = lane >> 5;
+  const int kw = wave / RW;
+  const int nfull = w.nkeys / kTileKeys;
+  const bool tail = (w.nkeys % kTileKeys) != 0;
+  bool first = true;
+  ref[0] = ref[1] = -INFINITY;
+  z[0] = z[1] = 0.0f;
+
+  tile_dma(lds, kbase, p.k_stride_token, 0, w.nkeys, tid);
+  tile_dma(lds + kTileVec, kbase, p.k_stride_token, kTileKeys, w.nkeys, tid);
+  tile_dma_wait<8>();  // tile 0 has landed, tile 1 may still be in flight
+  __syncthreads();
+  pass1_tile_simple<RW, false>(lds, qf, p.c, ref, z, 0, w.nkeys, first, kw, n, h);
+  tile_dma_wait<0>();
+  __syncthreads();  // tile 1 is in; every wave is done with tile 0's buffer
+  tile_dma(lds, kbase, p.k_stride_token, 2 * kTileKeys, w.nkeys, tid);
+
+  float off[2][16];
+  off[0][0] = -ref[0];
+  off[1][0] = -ref[1];
+  float zsum[2];
+  walk_tiles<RW, 1>(lds, kbase, p.k_stride_token, w.nkeys, 1, nfull, qf, p.c, off, zsum, nullptr, nullptr, tid, kw,
+                    0, n, h);
+  z[0] += zsum[0];
+  z[1] += zsum[1];
+  if (tail)  // already stored and fenced before the last unit of the last full tile
+    pass1_tile_simple<RW, false>(lds + (nfull & 1) * kTileVec, qf, p.c, ref, z, nfull * kTileKeys, w.nkeys, first, kw,
+                                 n, h);
+  __syncthreads();
 }
 
 template <int RW>
@@ -322,8 +492,11 @@ __global__ __launch_bounds__(kThreads, 2) void score_pass1_kernel(ScoreParams p)
   frag_from_q(qf[1], p, qbase, row0 + 32 + n, h);
 
   float ref[2], z[2];
-  bool bad = pass1_chunk<RW, false>(p, w, kbase, qf, lds, ref, z);
-  if (__syncthreads_or(bad ? 1 : 0)) pass1_chunk<RW, true>(p, w, kbase, qf, lds, ref, z);
+  if (w.nkeys >= 2 * kTileKeys) pass1_chunk_pipelined<RW>(p, w, kbase, qf, lds, ref, z);
+  else pass1_chunk_simple<RW, false>(p, w, kbase, qf, lds, ref, z);
+  // a sum that is not finite means a logit sat more than ~127 binades above the reference
+  const bool bad = !(z[0] < INFINITY) || !(z[1] < INFINITY);
+  if (__syncthreads_or(bad ? 1 : 0)) pass1_chunk_simple<RW, true>(p, w, kbase, qf, lds, ref, z);
 
   // the two lane halves hold different keys of the same query
   const float z0 = z[0] + xhalf(z[0]);
@@ -386,60 +559,6 @@ __global__ void score_combine_kernel(ScoreParams p, int key_waves) {
 // ---------------------------------------------------------------------------------------------
 // Pass 2
 // ---------------------------------------------------------------------------------------------
-// Column sums of one full tile, software pipelined like pass 1; nb holds -lse2 of the lane's rows.
-template <int RW>
-__device__ __forceinline__ void pass2_tile_pipelined(const u32x4* buf, const bf16x8 (&qf)[2][8], float c,
-                                                     const float (&nb)[2][16], float (&col)[4], int kw, int n, int h) {
-  constexpr int KW = 4 / RW, NSUB = 4 / KW, NUNIT = 2 * NSUB;
-  bf16x8 kf[8];
-#pragma unroll
-  for (int s = 0; s < 8; ++s) kf[s] = lds_frag(buf, kw, s, n, h);
-  f32x16 prev = {0};
-#pragma unroll
-  for (int s = 0; s < 8; ++s) prev = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[0][s], kf[s], prev, 0, 0, 0);
-  float e0 = 0.0f, e1 = 0.0f;  // exponentials issued in the previous slice, added in this one
-  float sa = 0.0f, sb = 0.0f;  // running sums of the unit whose exponentials are being added
-  int lane_base = n * 16;
-#pragma unroll
-  for (int u = 1; u < NUNIT; ++u) {
-    const int j = u >> 1, rb = u & 1, rbp = (u - 1) & 1;
-    const int jpp = u >= 2 ? (u - 2) >> 1 : 0;  // sub-block of the unit before the previous one
-    const bool reload = rb == 1 && j + 1 < NSUB;
-    f32x16 cur = {0};
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][s], kf[s], cur, 0, 0, 0);
-      if (reload) kf[s] = lds_frag_at(buf, lane_base, kw + (j + 1) * KW, s, n, h);
-      const float x0 = fmaf(prev[2 * s], c, nb[rbp][2 * s]);
-      const float x1 = fmaf(prev[2 * s + 1], c, nb[rbp][2 * s + 1]);
-      sa += e0;
-      sb += e1;
-      if (s == 0) {  // those were the last two logits of the unit before: close its sum
-        col[jpp] += sa + sb;
-        sa = sb = 0.0f;
-      }
-      e0 = __builtin_amdgcn_exp2f(x0);
-      e1 = __builtin_amdgcn_exp2f(x1);
-      DAPQ_SLICE_END(cur, prev, e0, e1, sa, sb, lane_base);
-    }
-    prev = cur;
-  }
-#pragma unroll
-  for (int s = 0; s < 8; ++s) {
-    const float x0 = fmaf(prev[2 * s], c, nb[1][2 * s]);
-    const float x1 = fmaf(prev[2 * s + 1], c, nb[1][2 * s + 1]);
-    sa += e0;
-    sb += e1;
-    if (s == 0) {
-      col[(NUNIT - 2) >> 1] += sa + sb;
-      sa = sb = 0.0f;
-    }
-    e0 = __builtin_amdgcn_exp2f(x0);
-    e1 = __builtin_amdgcn_exp2f(x1);
-  }
-  col[NSUB - 1] += (sa + e0) + (sb + e1);
-}
-
 // The plain way, for partial tiles and when the Q slab changes per super-group.
 template <int RW>
 __device__ __forceinline__ void pass2_tile_simple(const u32x4* buf, const bf16x8 (&qf)[2][8], float c,
@@ -468,9 +587,8 @@ __device__ __forceinline__ void pass2_tile_simple(const u32x4* buf, const bf16x8
 template <int RW, bool MULTI>
 __global__ __launch_bounds__(kThreads, 2) void score_pass2_kernel(ScoreParams p) {
   extern __shared__ u32x4 lds[];
-  constexpr int KW = 4 / RW;
-  constexpr int NSUB = 4 / KW;  // sub-blocks of a tile per wave
-  float* red = reinterpret_cast<float*>(lds + kLdsScore / 16);  // [RW][128] partial column sums
+  float* red = reinterpret_cast<float*>(lds + kLdsScore / 16);  // [2][RW][128] partial column sums
+  constexpr int kRed = RW * kTileKeys;
   const Work w = locate(p, blockIdx.x);
   if (w.nkeys == 0) return;
   const int layer = blockIdx.z / p.n_kv_heads, kv = blockIdx.z - layer * p.n_kv_heads;
@@ -505,40 +623,49 @@ __global__ __launch_bounds__(kThreads, 2) void score_pass2_kernel(ScoreParams p)
   if (!MULTI) load_slab(0);
 
   const int ntiles = (w.nkeys + kTileKeys - 1) / kTileKeys;
+  const int nfull = w.nkeys / kTileKeys;
+
+  if (!MULTI && nfull >= 1) {
+    // ---- pipelined: all full tiles in one stream, the partial last tile (if any) the plain way
+    tile_dma(lds, kbase, p.k_stride_token, 0, w.nkeys, tid);
+    tile_dma(lds + kTileVec, kbase, p.k_stride_token, kTileKeys, w.nkeys, tid);
+    if (kTileKeys < w.nkeys) tile_dma_wait<8>();  // tile 0 has landed, tile 1 may still be in flight
+    else tile_dma_wait<0>();
+    __syncthreads();
+    float zsum[2];
+    walk_tiles<RW, 2>(lds, kbase, p.k_stride_token, w.nkeys, 0, nfull, qf, c, nb, zsum, red, out, tid, kw, rw, n, h);
+    if (nfull < ntiles) {  // the partial tile is in its buffer already (stored and fenced in the walk)
+      float col[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+      pass2_tile_simple<RW>(lds + (nfull & 1) * kTileVec, qf, c, nb, col, nfull * kTileKeys, w.nkeys, kw, n, h);
+      __syncthreads();  // the stores above have read red before it is overwritten
+      publish_columns<RW>(red + (nfull & 1) * kRed, col, kw, rw, n, h);
+      __syncthreads();
+      store_columns<RW>(red + (nfull & 1) * kRed, out, nfull * kTileKeys, w.nkeys, tid);
+    }
+    return;
+  }
+
+  // ---- plain: one tile at a time, staged through registers
   u32x4 st[8];
   tile_load(st, kbase, p.k_stride_token, 0, w.nkeys, tid);
   for (int t = 0; t < ntiles; ++t) {
-    u32x4* buf = lds + (t & 1) * (kTileBytes / 16);
+    u32x4* buf = lds + (t & 1) * kTileVec;
     tile_store(buf, st, tid);
     __syncthreads();
-    // unconditional prefetch: past the last tile the clamped addresses re-read its last key
     tile_load(st, kbase, p.k_stride_token, (t + 1) * kTileKeys, w.nkeys, tid);
     const int tile_key0 = t * kTileKeys;
-
     float col[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     if (MULTI) {
       for (int sg = 0; sg < p.n_super; ++sg) {
         load_slab(sg);
         pass2_tile_simple<RW>(buf, qf, c, nb, col, tile_key0, w.nkeys, kw, n, h);
       }
-    } else if (tile_key0 + kTileKeys <= w.nkeys) {
-      pass2_tile_pipelined<RW>(buf, qf, c, nb, col, kw, n, h);
     } else {
       pass2_tile_simple<RW>(buf, qf, c, nb, col, tile_key0, w.nkeys, kw, n, h);
     }
-    // lane halves hold different query rows of the same key; then add the RW slabs through LDS
-#pragma unroll
-    for (int j = 0; j < NSUB; ++j) {
-      const float v = col[j] + xhalf(col[j]);
-      if (h == 0) red[rw * kTileKeys + (kw + j * KW) * 32 + n] = v;
-    }
+    publish_columns<RW>(red + (t & 1) * kRed, col, kw, rw, n, h);
     __syncthreads();
-    if (tid < kTileKeys && tile_key0 + tid < w.nkeys) {
-      float s = red[tid];
-#pragma unroll
-      for (int r = 1; r < RW; ++r) s += red[r * kTileKeys + tid];
-      out[tile_key0 + tid] = s;
-    }
+    store_columns<RW>(red + (t & 1) * kRed, out, tile_key0, w.nkeys, tid);
   }
 }
 
@@ -609,7 +736,7 @@ int launch_accumulate(const dapq_shape* s, const ScorePlan& plan, ScoreParams p,
     DAPQ_HIP_LAUNCH_CHECK("score_chunk_prefix_kernel");
   }
   const dim3 grid((unsigned)plan.max_chunks, 1, (unsigned)(s->n_layers * s->n_kv_heads));
-  const int lds_bytes = kLdsScore + 4 * kTileKeys * (int)sizeof(float);
+  const int lds_bytes = kLdsScore + 2 * 4 * kTileKeys * (int)sizeof(float);
   int rc = DAPQ_OK;
 #define DAPQ_LAUNCH_P2(RWV, MULTIV)                                                                       \
   do {                                                                                                    \
@@ -630,12 +757,7 @@ int launch_accumulate(const dapq_shape* s, const ScorePlan& plan, ScoreParams p,
   return DAPQ_OK;
 }
 
-}  // namespace
-}  // namespace dapq
-
-using namespace dapq;
-
-static int check_workspace(void* workspace, size_t workspace_bytes, const ScorePlan& plan) {
+int check_workspace(void* workspace, size_t workspace_bytes, const ScorePlan& plan) {
   DAPQ_REQUIRE(workspace != nullptr, DAPQ_ERR_INVALID_ARG, "workspace is NULL");
   DAPQ_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 255) == 0, DAPQ_ERR_UNSUPPORTED,
                "workspace is not 256-byte aligned");
@@ -644,8 +766,13 @@ static int check_workspace(void* workspace, size_t workspace_bytes, const ScoreP
   return DAPQ_OK;
 }
 
-extern "C" DAPQ_API int dapq_score_stats(const dapq_shape* shape, const void* q, const void* k, float* lse2, void* workspace,
-                                size_t workspace_bytes, void* stream) {
+}  // namespace
+}  // namespace dapq
+
+using namespace dapq;
+
+extern "C" DAPQ_API int dapq_score_stats(const dapq_shape* shape, const void* q, const void* k, float* lse2,
+                                         void* workspace, size_t workspace_bytes, void* stream) {
   int rc = check_shape(shape, true, true, false);
   if (rc != DAPQ_OK) return rc;
   ScorePlan plan;
@@ -666,8 +793,9 @@ extern "C" DAPQ_API int dapq_score_stats(const dapq_shape* shape, const void* q,
   return launch_stats(shape, plan, p, static_cast<hipStream_t>(stream));
 }
 
-extern "C" DAPQ_API int dapq_score_accumulate(const dapq_shape* shape, const void* q, const void* k, const float* lse2,
-                                     float* scores, void* workspace, size_t workspace_bytes, void* stream) {
+extern "C" DAPQ_API int dapq_score_accumulate(const dapq_shape* shape, const void* q, const void* k,
+                                              const float* lse2, float* scores, void* workspace,
+                                              size_t workspace_bytes, void* stream) {
   int rc = check_shape(shape, true, true, false);
   if (rc != DAPQ_OK) return rc;
   ScorePlan plan;
@@ -688,8 +816,8 @@ extern "C" DAPQ_API int dapq_score_accumulate(const dapq_shape* shape, const voi
   return launch_accumulate(shape, plan, p, static_cast<hipStream_t>(stream));
 }
 
-extern "C" DAPQ_API int dapq_score(const dapq_shape* shape, const void* q, const void* k, float* scores, void* workspace,
-                          size_t workspace_bytes, void* stream) {
+extern "C" DAPQ_API int dapq_score(const dapq_shape* shape, const void* q, const void* k, float* scores,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
   int rc = check_shape(shape, true, true, false);
   if (rc != DAPQ_OK) return rc;
   ScorePlan plan;
