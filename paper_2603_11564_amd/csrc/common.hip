@@ -69,21 +69,29 @@ int make_score_plan(const dapq_shape* s, ScorePlan* p) {
   DAPQ_REQUIRE(rows64 <= (1 << 20), DAPQ_ERR_UNSUPPORTED, "group * n_pseudo = %lld rows per KV head is too large",
                (long long)rows64);
   p->rows = (int)rows64;
-  const int slabs = (p->rows + 63) / 64;  // 64-row slabs
-  p->row_waves = slabs >= 4 ? 4 : (slabs >= 2 ? 2 : 1);
-  p->key_waves = 4 / p->row_waves;
-  p->n_super = (slabs + p->row_waves - 1) / p->row_waves;
-  p->rows_pad = p->n_super * p->row_waves * 64;
-  DAPQ_REQUIRE(p->n_super <= 65535, DAPQ_ERR_UNSUPPORTED, "too many query rows per KV head");
-
-  // Chunk of keys per workgroup: as long as possible (the Q slab is reloaded per chunk) while the
-  // launch still has >= 8 workgroups per compute unit to balance the tail.
   const int64_t heads = (int64_t)s->n_layers * s->n_kv_heads;
+  p->wave_path = p->rows <= 256;
   int chunk = kMaxChunkKeys;
-  while (chunk > kTileKeys) {
-    const int64_t wgs = heads * ((s->total_tokens + chunk - 1) / chunk);
-    if (wgs >= 2048) break;
-    chunk /= 2;
+  if (p->wave_path) {
+    // one wave per chunk: all rows in its registers
+    p->row_blocks = p->rows <= 64 ? 2 : (p->rows <= 128 ? 4 : 8);
+    p->row_waves = 1;
+    p->key_waves = 1;
+    p->n_super = 1;
+    p->rows_pad = p->row_blocks * 32;
+    // as long as possible (Q is reloaded per chunk) while there are >= 4 chunks per SIMD (1024 SIMDs)
+    while (chunk > kTileKeys && heads * ((s->total_tokens + chunk - 1) / chunk) < 4096) chunk /= 2;
+  } else {
+    const int slabs = (p->rows + 63) / 64;  // 64-row slabs
+    p->row_blocks = 0;
+    p->row_waves = 4;
+    p->key_waves = 1;
+    p->n_super = (slabs + p->row_waves - 1) / p->row_waves;
+    p->rows_pad = p->n_super * p->row_waves * 64;
+    DAPQ_REQUIRE(p->n_super <= 65535, DAPQ_ERR_UNSUPPORTED, "too many query rows per KV head");
+    // Chunk of keys per workgroup: as long as possible (the Q slab is reloaded per chunk) while the
+    // launch still has >= 8 workgroups per compute unit to balance the tail.
+    while (chunk > kTileKeys && heads * ((s->total_tokens + chunk - 1) / chunk) < 2048) chunk /= 2;
   }
   p->chunk_keys = chunk;
   if (s->cu_seqlens == nullptr) {

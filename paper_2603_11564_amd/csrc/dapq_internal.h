@@ -34,6 +34,8 @@ constexpr int kMaxChunkKeys = 2048; // most keys one workgroup of a score pass w
 // dapq_workspace_bytes() and the launchers agree.
 struct ScorePlan {
   int rows;        // R = (H_q/H_kv) * N query rows scored against every key of a KV head
+  bool wave_path;  // R <= 256: every wave holds all rows and walks its own chunk (no workgroup sharing)
+  int row_blocks;  // wave path: 32-row blocks per wave (2, 4 or 8)
   int row_waves;   // RW in {1,2,4}: waves of a workgroup that hold different 64-row slabs of Q
   int key_waves;   // 4 / RW: waves that share a slab and split the keys of a tile
   int n_super;     // row super-groups of RW*64 rows

@@ -32,6 +32,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));  // 16 bytes; native vector, stays in registers
 
 struct ScoreParams {
@@ -669,6 +670,365 @@ __global__ __launch_bounds__(kThreads, 2) void score_pass2_kernel(ScoreParams p)
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Wave-private kernels (R <= 256 rows per KV head): one wave = all query rows x its own key stream.
+//
+// A workgroup is a single wave that keeps ALL the Q rows of the KV head in registers (up to eight
+// 32-row blocks = 256 registers of MFMA operands; the launch bound of one wave per SIMD gives it the
+// whole 512-register file) and walks its own chunk of keys.  Nothing is shared between waves, so
+// there is no barrier anywhere and no cross-wave reduction: in pass 2 the lane that owns a key
+// column sees every query row.  Keys arrive through a per-wave ring of 32-key sub-blocks in LDS
+// (global_load_lds_dwordx4, five slots of 8 KB in pass 1: four sub-blocks = 32 KB in flight per
+// wave, 128 KB per compute unit), and each fragment is read from LDS exactly once per wave.
+//
+// The instruction stream is the software pipeline described above, per (sub-block, row block)
+// unit, with the exponentials trailing the MFMAs by one unit plus one slice so that the first
+// result of a unit is not touched until a slice after its last MFMA issued.
+// ---------------------------------------------------------------------------------------------
+constexpr int kWaveStages1 = 5;           // pass 1: ring slots (40 KB per wave, 160 KB per compute unit)
+constexpr int kWaveStages2 = 4;           // pass 2: one slot less, a 1 KB table of row offsets instead
+constexpr int kSubVec = kSubBytes / 16;   // 512 16-byte chunks per sub-block
+constexpr int kWaveLds1 = kWaveStages1 * kSubBytes;
+constexpr int kWaveLds2 = kWaveStages2 * kSubBytes + 256 * (int)sizeof(float);
+
+// One wave moves one 32-key sub-block into an LDS slot: 8 transfers of 1 KB (4 key rows each).
+__device__ __forceinline__ void sub_dma(u32x4* slot, const uint16_t* kbase, int64_t stride_token, int key0, int nkeys,
+                                        int lane) {
+  const int row0 = lane >> 4, pos = lane & 15;
+  if (key0 + 32 <= nkeys) {
+    const char* base = reinterpret_cast<const char*>(kbase + (int64_t)key0 * stride_token);
+    const unsigned row_off = (unsigned)row0 * (unsigned)stride_token * 2u;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const unsigned ch = (unsigned)(pos ^ ((4 * i + row0) & 15));
+      const char* src = base + (int64_t)(4 * i) * stride_token * 2 + (row_off + ch * 16u);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                       (__attribute__((address_space(3))) void*)(slot + i * 64), 16, 0, 0);
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int row = 4 * i + row0;
+      int gk = key0 + row;
+      gk = gk < nkeys ? gk : nkeys - 1;  // rows past the end repeat the last key
+      const uint16_t* src = kbase + (int64_t)gk * stride_token + (pos ^ (row & 15)) * 8;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                       (__attribute__((address_space(3))) void*)(slot + i * 64), 16, 0, 0);
+    }
+  }
+}
+
+// Waits until at most `newer` sub-block transfers (8 operations each) of this wave are in flight.
+__device__ __forceinline__ void wait_subblocks(int newer) {
+  if (newer <= 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  else if (newer == 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+  else if (newer == 2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+  else if (newer == 3) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+  else asm volatile("s_waitcnt vmcnt(32)" ::: "memory");
+}
+
+#define DAPQ_WAVE_SLICE_END(cur, prev, e0, e1, sa, sb, la, lb, addr) \
+  asm volatile("" : "+v"(cur), "+v"(prev), "+v"(e0), "+v"(e1), "+v"(sa), "+v"(sb), "+v"(la), "+v"(lb), "+v"(addr))
+#define DAPQ_WAVE_SLICE_END2(cur, prev, e0, e1, sa, sb, la, lb, addr, addr2)                                          \
+  asm volatile("" : "+v"(cur), "+v"(prev), "+v"(e0), "+v"(e1), "+v"(sa), "+v"(sb), "+v"(la), "+v"(lb), "+v"(addr), \
+               "+v"(addr2))
+
+// exponentials of two logits: x = a*c + o; the pair issued in the previous step is added now
+#define DAPQ_VALU_STEP(a0, a1, o0, o1)              \
+  do {                                              \
+    const float x0_ = fmaf((a0), c, (o0));          \
+    const float x1_ = fmaf((a1), c, (o1));          \
+    sa += e0;                                       \
+    sb += e1;                                       \
+    e0 = __builtin_amdgcn_exp2f(x0_);               \
+    e1 = __builtin_amdgcn_exp2f(x1_);               \
+  } while (0)
+
+// Pipelined walk of one wave over sub-blocks [sb0, sb1) of its chunk.
+//   on entry  kf = fragments of sub-block sb0; transfers of all sub-blocks < issued are under way
+//   on exit   kf = fragments of sub-block sb1 if sb1 < nsubs
+// PASS 1: off1[rb] = -(reference logit * c) of row block rb; acc[rb] receives the row sums.
+// PASS 2: the LDS table at byte address nbt holds -lse2 of every row (-inf for padding rows); the
+//         16 values a lane needs for a row block (its accumulator rows) are fetched one unit ahead.
+//         S of every key is written to out.
+// NST = slots of the sub-block ring.
+template <int NRB, int PASS, int NST>
+__device__ __forceinline__ void wave_walk(u32x4* ring, const uint16_t* kbase, int64_t stride_token, int nkeys,
+                                          int nsubs, int sb0, int sb1, int& issued, bf16x8 (&kf)[8],
+                                          const bf16x8 (&qf)[NRB][8], float c, const float (&off1)[NRB], unsigned nbt,
+                                          float (&acc)[NRB], float* out, int lane, int n, int h) {
+  const unsigned ring_base = (unsigned)(uintptr_t)(lds_vec_ptr)ring;
+  unsigned fa[8];
+#pragma unroll
+  for (int s = 0; s < 8; ++s) fa[s] = ring_base + (unsigned)(n * 16 + ((2 * s + h) ^ (n & 15))) * 16u;
+  unsigned nba = nbt + (unsigned)h * 16u;  // pass 2: this lane's first table entry (row 4h)
+  f32x16 prev;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) prev[v] = -INFINITY;  // 2^(-inf) = 0: the first steps add nothing
+  float la = -INFINITY, lb = -INFINITY;              // last two logits of the unit before prev
+  float e0 = 0.0f, e1 = 0.0f, sa = 0.0f, sb = 0.0f;
+  f32x4 oc[4], on[4];                                // pass 2: offsets of prev's rows / of cur's rows
+  float oa = 0.0f, ob = 0.0f;                        // pass 2: offsets that go with la, lb
+#pragma unroll
+  for (int b = 0; b < 4; ++b) oc[b] = on[b] = (f32x4){0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb) acc[rb] = 0.0f;
+
+  for (int sub = sb0; sub < sb1; ++sub) {
+    const unsigned next_slot = (unsigned)((sub + 1) % NST) * (unsigned)kSubBytes;
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+      constexpr int kLast = NRB - 1;
+      const int rb1 = (rb + NRB - 1) % NRB;  // row block of the previous unit (prev)
+      const int rb2 = (rb + NRB - 2) % NRB;  // row block of the unit before it (la, lb)
+      if (rb == 1) {
+        // the slot of this sub-block is free (its fragments are in registers and have been used)
+        if (issued < nsubs) {
+          sub_dma(ring + (issued % NST) * kSubVec, kbase, stride_token, issued * 32, nkeys, lane);
+          ++issued;
+        }
+      }
+      if (rb == kLast && sub + 1 < nsubs) wait_subblocks(issued - (sub + 2));  // sub-block sub+1 has landed
+      f32x16 cur = {0};
+#pragma unroll
+      for (int s = 0; s < 8; ++s) {
+        if (PASS == 1) cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[rb][s], cur, 0, 0, 0);
+        else cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][s], kf[s], cur, 0, 0, 0);
+        if (rb == kLast) kf[s] = lds_read16(fa[s] + next_slot, 0);  // last use: fetch the next sub-block's
+        if (PASS == 2 && s >= 2 && s < 6)  // offsets of this unit's rows, needed from the next unit on
+          on[s - 2] = *(const f32x4 __attribute__((address_space(3)))*)(uintptr_t)(nba + (rb * 32 + 8 * (s - 2)) * 4);
+        if (s == 0) {
+          DAPQ_VALU_STEP(la, lb, PASS == 1 ? off1[rb2] : oa, PASS == 1 ? off1[rb2] : ob);
+        } else {
+          DAPQ_VALU_STEP(prev[2 * s - 2], prev[2 * s - 1], PASS == 1 ? off1[rb1] : oc[(2 * s - 2) >> 2][(2 * s - 2) & 3],
+                         PASS == 1 ? off1[rb1] : oc[(2 * s - 1) >> 2][(2 * s - 1) & 3]);
+        }
+        if (s == 1) {
+          // the add above took in the last two logits of the unit two back: that unit is complete
+          if (PASS == 1) {
+            acc[rb2] += sa + sb;
+            sa = sb = 0.0f;
+          } else if (rb == 1) {
+            // ... and it closed a sub-block: the column sum of a key is complete
+            if (sub > sb0) {
+              const float total = sa + sb;
+              const float both = total + xhalf(total);
+              const int key = (sub - 1) * 32 + n;
+              if (h == 0 && key < nkeys) out[key] = both;
+            }
+            sa = sb = 0.0f;
+          }
+        }
+        if (PASS == 1) DAPQ_WAVE_SLICE_END(cur, prev, e0, e1, sa, sb, la, lb, fa[(s + 1) & 7]);
+        else DAPQ_WAVE_SLICE_END2(cur, prev, e0, e1, sa, sb, la, lb, fa[(s + 1) & 7], nba);
+      }
+      la = prev[14];
+      lb = prev[15];
+      prev = cur;
+      if (PASS == 2) {
+        oa = oc[3][2];
+        ob = oc[3][3];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) oc[b] = on[b];
+      }
+    }
+  }
+
+  // drain: prev = last unit (row block NRB-1), la/lb = tail of the unit before it
+  {
+    constexpr int rbl = NRB - 1, rbl1 = NRB - 2;
+    DAPQ_VALU_STEP(la, lb, PASS == 1 ? off1[rbl1] : oa, PASS == 1 ? off1[rbl1] : ob);
+#pragma unroll
+    for (int s = 1; s <= 8; ++s) {
+      DAPQ_VALU_STEP(prev[2 * s - 2], prev[2 * s - 1], PASS == 1 ? off1[rbl] : oc[(2 * s - 2) >> 2][(2 * s - 2) & 3],
+                     PASS == 1 ? off1[rbl] : oc[(2 * s - 1) >> 2][(2 * s - 1) & 3]);
+      if (s == 1 && PASS == 1) {
+        acc[rbl1] += sa + sb;
+        sa = sb = 0.0f;
+      }
+    }
+    const float total = (sa + e0) + (sb + e1);
+    if (PASS == 1) {
+      acc[rbl] += total;
+    } else if (sb1 > sb0) {
+      const float both = total + xhalf(total);
+      const int key = (sb1 - 1) * 32 + n;
+      if (h == 0 && key < nkeys) out[key] = both;
+    }
+  }
+}
+
+// One sub-block the plain way (pass 1): masks keys >= nkeys, fixes the reference logits (FIRST) or
+// tracks a running maximum (SAFE).
+template <int NRB, bool SAFE, bool FIRST>
+__device__ __forceinline__ void wave_sub_simple(const bf16x8 (&kf)[8], const bf16x8 (&qf)[NRB][8], float c,
+                                                float (&ref)[NRB], float (&z)[NRB], int key0, int nkeys, int h) {
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb) {
+    f32x16 a = {0};
+#pragma unroll
+    for (int s = 0; s < 8; ++s) a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[rb][s], a, 0, 0, 0);
+    if (key0 + 32 > nkeys) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        if (key0 + acc_row(v, h) >= nkeys) a[v] = -INFINITY;
+    }
+    if (SAFE || FIRST) {
+      float m = a[0];
+#pragma unroll
+      for (int v = 1; v < 16; ++v) m = fmaxf(m, a[v]);
+      m = fmaxf(m, xhalf(m)) * c;
+      if (SAFE) {
+        const float mnew = fmaxf(ref[rb], m);
+        z[rb] *= __builtin_amdgcn_exp2f(ref[rb] - mnew);
+        ref[rb] = mnew;
+      } else {
+        ref[rb] = m;
+      }
+    }
+    const float nref = -ref[rb];
+    float sum = 0.0f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) sum += __builtin_amdgcn_exp2f(fmaf(a[v], c, nref));
+    z[rb] += sum;
+  }
+}
+
+// The Q fragments only ever feed MFMAs, which can read their A/B operands from the accumulation
+// half of the register file: pin them there so that the vector half stays free for everything the
+// vector ALU touches (accumulators, exponentials, offsets).
+template <int NRB>
+__device__ __forceinline__ void pin_q_in_agprs(bf16x8 (&qf)[NRB][8]) {
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+    for (int s = 0; s < 8; ++s) asm volatile("" : "+a"(qf[rb][s]));
+}
+
+template <int NRB>
+__device__ __forceinline__ void wave_load_frags(bf16x8 (&kf)[8], const u32x4* slot, int n, int h) {
+#pragma unroll
+  for (int s = 0; s < 8; ++s) kf[s] = __builtin_bit_cast(bf16x8, slot[lds_chunk_index(n, 2 * s + h)]);
+}
+
+template <int NRB>
+__global__ __launch_bounds__(64, 1) void score_wave_pass1_kernel(ScoreParams p) {
+  extern __shared__ u32x4 ring[];
+  const Work w = locate(p, blockIdx.x);
+  if (w.nkeys == 0) return;
+  const int layer = blockIdx.z / p.n_kv_heads, kv = blockIdx.z - layer * p.n_kv_heads;
+  const int lane = threadIdx.x, n = lane & 31, h = lane >> 5;
+  const uint16_t* qbase = p.q + (int64_t)layer * p.q_stride_layer + (int64_t)w.seq * p.q_stride_seq +
+                          (int64_t)kv * p.group * p.q_stride_head;
+  const uint16_t* kbase = p.k + (int64_t)layer * p.k_stride_layer + (int64_t)w.seq * p.k_stride_seq +
+                          (int64_t)kv * p.k_stride_head + w.tok0 * p.k_stride_token;
+  const int nsubs = (w.nkeys + 31) / 32, nfull = w.nkeys / 32;
+  int issued = 0;
+  for (; issued < kWaveStages1 && issued < nsubs; ++issued)
+    sub_dma(ring + issued * kSubVec, kbase, p.k_stride_token, issued * 32, w.nkeys, lane);
+  bf16x8 qf[NRB][8];
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb) frag_from_q(qf[rb], p, qbase, rb * 32 + n, h);
+  if (NRB == 8) pin_q_in_agprs<NRB>(qf);
+
+  float ref[NRB], z[NRB];
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb) {
+    ref[rb] = -INFINITY;
+    z[rb] = 0.0f;
+  }
+  bf16x8 kf[8];
+  wait_subblocks(issued - 1);
+  wave_load_frags<NRB>(kf, ring, n, h);
+  // sub-block 0 the plain way: it fixes the reference logits
+  wave_sub_simple<NRB, false, true>(kf, qf, p.c, ref, z, 0, w.nkeys, h);
+  if (nsubs > 1) {
+    wait_subblocks(issued - 2);
+    wave_load_frags<NRB>(kf, ring + kSubVec, n, h);
+    if (issued < nsubs) {  // slot 0 is free
+      sub_dma(ring + (issued % kWaveStages1) * kSubVec, kbase, p.k_stride_token, issued * 32, w.nkeys, lane);
+      ++issued;
+    }
+    if (nfull > 1) {
+      float off[NRB], zs[NRB];
+#pragma unroll
+      for (int rb = 0; rb < NRB; ++rb) off[rb] = -ref[rb];
+      wave_walk<NRB, 1, kWaveStages1>(ring, kbase, p.k_stride_token, w.nkeys, nsubs, 1, nfull, issued, kf, qf, p.c, off,
+                                      0u, zs, nullptr, lane, n, h);
+#pragma unroll
+      for (int rb = 0; rb < NRB; ++rb) z[rb] += zs[rb];
+    }
+    if (nfull < nsubs && nfull >= 1)  // the partial last sub-block; its fragments are in kf
+      wave_sub_simple<NRB, false, false>(kf, qf, p.c, ref, z, nfull * 32, w.nkeys, h);
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
+  // a sum that is not finite means a logit sat more than ~127 binades above the reference: redo
+  // the chunk with a running maximum, one sub-block at a time
+  bool bad = false;
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb) bad = bad || !(z[rb] < INFINITY);
+  if (__any(bad ? 1 : 0)) {
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+      ref[rb] = -INFINITY;
+      z[rb] = 0.0f;
+    }
+    for (int sub = 0; sub < nsubs; ++sub) {
+      sub_dma(ring, kbase, p.k_stride_token, sub * 32, w.nkeys, lane);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      wave_load_frags<NRB>(kf, ring, n, h);
+      wave_sub_simple<NRB, true, false>(kf, qf, p.c, ref, z, sub * 32, w.nkeys, h);
+    }
+  }
+
+  // the two lane halves hold different keys of the same query
+  float2* outp = p.parts + ((int64_t)blockIdx.z * p.max_chunks + blockIdx.x) * p.rows_pad;
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb) {
+    const float zz = z[rb] + xhalf(z[rb]);
+    if (h == 0) outp[rb * 32 + n] = make_float2(ref[rb], zz);
+  }
+}
+
+template <int NRB>
+__global__ __launch_bounds__(64, 1) void score_wave_pass2_kernel(ScoreParams p) {
+  extern __shared__ u32x4 ring[];
+  const Work w = locate(p, blockIdx.x);
+  if (w.nkeys == 0) return;
+  const int layer = blockIdx.z / p.n_kv_heads, kv = blockIdx.z - layer * p.n_kv_heads;
+  const int lane = threadIdx.x, n = lane & 31, h = lane >> 5;
+  const uint16_t* qbase = p.q + (int64_t)layer * p.q_stride_layer + (int64_t)w.seq * p.q_stride_seq +
+                          (int64_t)kv * p.group * p.q_stride_head;
+  const uint16_t* kbase = p.k + (int64_t)layer * p.k_stride_layer + (int64_t)w.seq * p.k_stride_seq +
+                          (int64_t)kv * p.k_stride_head + w.tok0 * p.k_stride_token;
+  const float* lse = p.lse2 + (((int64_t)layer * p.batch + w.seq) * p.n_q_heads + (int64_t)kv * p.group) * p.n_pseudo;
+  float* out = p.scores + ((int64_t)layer * p.n_kv_heads + kv) * p.total_tokens + w.tok0;
+  const int nsubs = (w.nkeys + 31) / 32;
+  int issued = 0;
+  for (; issued < kWaveStages2 && issued < nsubs; ++issued)
+    sub_dma(ring + issued * kSubVec, kbase, p.k_stride_token, issued * 32, w.nkeys, lane);
+  // table of -lse2 per row behind the ring; -inf for padding rows, which then add 0
+  float* nbt = reinterpret_cast<float*>(ring + kWaveStages2 * kSubVec);
+#pragma unroll
+  for (int r = lane; r < NRB * 32; r += 64) nbt[r] = r < p.rows ? -lse[r] : -INFINITY;
+  bf16x8 qf[NRB][8];
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb) frag_from_q(qf[rb], p, qbase, rb * 32 + n, h);
+  if (NRB == 8) pin_q_in_agprs<NRB>(qf);
+  __syncthreads();  // one wave: orders the table writes before the reads below
+  bf16x8 kf[8];
+  wait_subblocks(issued - 1);
+  wave_load_frags<NRB>(kf, ring, n, h);
+  float unused_off[NRB], unused_acc[NRB];
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb) unused_off[rb] = 0.0f;
+  wave_walk<NRB, 2, kWaveStages2>(ring, kbase, p.k_stride_token, w.nkeys, nsubs, 0, nsubs, issued, kf, qf, p.c,
+                                  unused_off, (unsigned)(uintptr_t)(lds_vec_ptr)(ring + kWaveStages2 * kSubVec),
+                                  unused_acc, out, lane, n, h);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
 template <typename F>
 int set_lds(F kernel, int bytes) {
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
@@ -704,21 +1064,22 @@ int launch_stats(const dapq_shape* s, const ScorePlan& plan, ScoreParams p, hipS
                        plan.chunk_keys);
     DAPQ_HIP_LAUNCH_CHECK("score_chunk_prefix_kernel");
   }
-  const dim3 grid((unsigned)plan.max_chunks, (unsigned)plan.n_super, (unsigned)(s->n_layers * s->n_kv_heads));
   int rc = DAPQ_OK;
-  switch (plan.row_waves) {
-    case 1:
-      if ((rc = set_lds(score_pass1_kernel<1>, kLdsScore)) != DAPQ_OK) return rc;
-      hipLaunchKernelGGL(score_pass1_kernel<1>, grid, dim3(kThreads), kLdsScore, stream, p);
-      break;
-    case 2:
-      if ((rc = set_lds(score_pass1_kernel<2>, kLdsScore)) != DAPQ_OK) return rc;
-      hipLaunchKernelGGL(score_pass1_kernel<2>, grid, dim3(kThreads), kLdsScore, stream, p);
-      break;
-    default:
-      if ((rc = set_lds(score_pass1_kernel<4>, kLdsScore)) != DAPQ_OK) return rc;
-      hipLaunchKernelGGL(score_pass1_kernel<4>, grid, dim3(kThreads), kLdsScore, stream, p);
-      break;
+  if (plan.wave_path) {
+    const dim3 grid((unsigned)plan.max_chunks, 1, (unsigned)(s->n_layers * s->n_kv_heads));
+#define DAPQ_LAUNCH_W1(NRBV)                                                                        \
+  do {                                                                                              \
+    if ((rc = set_lds(score_wave_pass1_kernel<NRBV>, kWaveLds1)) != DAPQ_OK) return rc;              \
+    hipLaunchKernelGGL(score_wave_pass1_kernel<NRBV>, grid, dim3(64), kWaveLds1, stream, p);        \
+  } while (0)
+    if (plan.row_blocks == 2) DAPQ_LAUNCH_W1(2);
+    else if (plan.row_blocks == 4) DAPQ_LAUNCH_W1(4);
+    else DAPQ_LAUNCH_W1(8);
+#undef DAPQ_LAUNCH_W1
+  } else {
+    const dim3 grid((unsigned)plan.max_chunks, (unsigned)plan.n_super, (unsigned)(s->n_layers * s->n_kv_heads));
+    if ((rc = set_lds(score_pass1_kernel<4>, kLdsScore)) != DAPQ_OK) return rc;
+    hipLaunchKernelGGL(score_pass1_kernel<4>, grid, dim3(kThreads), kLdsScore, stream, p);
   }
   DAPQ_HIP_LAUNCH_CHECK("score_pass1_kernel");
   const int64_t rows_total = (int64_t)s->n_layers * s->batch * s->n_q_heads * s->n_pseudo;
@@ -736,23 +1097,23 @@ int launch_accumulate(const dapq_shape* s, const ScorePlan& plan, ScoreParams p,
     DAPQ_HIP_LAUNCH_CHECK("score_chunk_prefix_kernel");
   }
   const dim3 grid((unsigned)plan.max_chunks, 1, (unsigned)(s->n_layers * s->n_kv_heads));
-  const int lds_bytes = kLdsScore + 2 * 4 * kTileKeys * (int)sizeof(float);
   int rc = DAPQ_OK;
-#define DAPQ_LAUNCH_P2(RWV, MULTIV)                                                                       \
-  do {                                                                                                    \
-    if ((rc = set_lds(score_pass2_kernel<RWV, MULTIV>, lds_bytes)) != DAPQ_OK) return rc;                 \
-    hipLaunchKernelGGL((score_pass2_kernel<RWV, MULTIV>), grid, dim3(kThreads), lds_bytes, stream, p);    \
+  if (plan.wave_path) {
+#define DAPQ_LAUNCH_W2(NRBV)                                                                        \
+  do {                                                                                              \
+    if ((rc = set_lds(score_wave_pass2_kernel<NRBV>, kWaveLds2)) != DAPQ_OK) return rc;              \
+    hipLaunchKernelGGL(score_wave_pass2_kernel<NRBV>, grid, dim3(64), kWaveLds2, stream, p);        \
   } while (0)
-  if (plan.n_super > 1) {
-    DAPQ_LAUNCH_P2(4, true);  // more than 256 rows always uses four row waves
-  } else if (plan.row_waves == 1) {
-    DAPQ_LAUNCH_P2(1, false);
-  } else if (plan.row_waves == 2) {
-    DAPQ_LAUNCH_P2(2, false);
+    if (plan.row_blocks == 2) DAPQ_LAUNCH_W2(2);
+    else if (plan.row_blocks == 4) DAPQ_LAUNCH_W2(4);
+    else DAPQ_LAUNCH_W2(8);
+#undef DAPQ_LAUNCH_W2
   } else {
-    DAPQ_LAUNCH_P2(4, false);
+    // more than 256 rows: four row waves, the Q slab changes per super-group
+    const int lds_bytes = kLdsScore + 2 * 4 * kTileKeys * (int)sizeof(float);
+    if ((rc = set_lds(score_pass2_kernel<4, true>, lds_bytes)) != DAPQ_OK) return rc;
+    hipLaunchKernelGGL((score_pass2_kernel<4, true>), grid, dim3(kThreads), lds_bytes, stream, p);
   }
-#undef DAPQ_LAUNCH_P2
   DAPQ_HIP_LAUNCH_CHECK("score_pass2_kernel");
   return DAPQ_OK;
 }
