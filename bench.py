@@ -79,6 +79,90 @@ def cpu_baseline(w, seed, n_layers):
     }
 
 
+class Context:
+    """Everything one benchmark step needs, resident in HBM: inputs, outputs, workspace, and step()."""
+
+    def __init__(self, w, seed, dev, overrides=None):
+        """overrides: optional {(layer_index, sequence, kv_head): (k_bits [L, d], v_bits [L, d])} of post-RoPE
+        host slices written over the device-generated ones; the parity tests use it to give the oracle and
+        the GPU the same bits for the heads they compare."""
+        import numpy as np
+        import torch
+        import paper_2603_11564_amd as D
+        import workloads as W
+
+        self.w, self.dev, self.D = w, dev, D
+        data = W.device_fill(w, seed, dev)
+        self.lens = lens = data["lens"]
+        self.cu = data["cu_seqlens"] if w.ragged is not None else None
+        self.cu_host = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+        self.tokens = tokens = int(sum(lens))
+        self.k, self.v = k, v = data["k"], data["v"]
+        d, Hq, Hkv, N, nl, B = w.head_dim, w.n_q_heads, w.n_kv_heads, w.n_pseudo, w.n_layers, w.batch
+        if w.layout == "hnd":
+            kstr = (Hkv * tokens * d, 0, tokens * d, d)
+            rope_k = (d, tokens * d)
+        else:
+            kstr = (tokens * Hkv * d, 0, d, Hkv * d)
+            rope_k = (Hkv * d, d)
+        for li in range(nl):       # keys are cached already rotated; done once, outside the timed region
+            D.dapq_rope_apply(k[li], k[li], data["k_pos"], tokens, Hkv, d, rope_k[0], rope_k[1], w.theta, 0)
+        if overrides:
+            for (li, b, kv), (kb, vb) in overrides.items():
+                kt = torch.from_numpy(kb.view(np.int16)).to(dev).view(torch.bfloat16)
+                vt = torch.from_numpy(vb.view(np.int16)).to(dev).view(torch.bfloat16)
+                s0, s1 = int(self.cu_host[b]), int(self.cu_host[b + 1])
+                assert kt.shape[0] == s1 - s0
+                if w.layout == "hnd":
+                    k[li, kv, s0:s1].copy_(kt)
+                    v[li, kv, s0:s1].copy_(vt)
+                else:
+                    k[li, s0:s1, kv].copy_(kt)
+                    v[li, s0:s1, kv].copy_(vt)
+        # pseudo queries laid out [batch][layer][Hq][N][d] so that one rope call covers a sequence
+        self.q_pre = data["q"].permute(1, 0, 2, 3, 4).contiguous()
+        self.q = torch.empty_like(self.q_pre)
+        qstr = (Hq * N * d, nl * Hq * N * d, N * d, d)
+        self.shape = D.make_shape(n_layers=nl, batch=B, n_q_heads=Hq, n_kv_heads=Hkv, n_pseudo=N,
+                                  total_tokens=tokens, cu_seqlens=self.cu, k_strides=kstr, v_strides=kstr,
+                                  q_strides=qstr, scale=w.scale)
+        self.ws = torch.empty(D.workspace_bytes(self.shape), dtype=torch.uint8, device=dev)
+        self.lse2 = torch.empty((nl, B, Hq, N), dtype=torch.float32, device=dev)
+        self.S = torch.empty((nl, Hkv, tokens), dtype=torch.float32, device=dev)
+        self.P = torch.empty_like(self.S)
+        self.idx = torch.zeros((nl, B, Hkv, w.budget), dtype=torch.int32, device=dev)
+        self.count = torch.zeros((nl, B, Hkv), dtype=torch.int32, device=dev)
+        self.k_out = torch.zeros((nl, B, Hkv, w.budget, d), dtype=torch.bfloat16, device=dev)
+        self.v_out = torch.zeros_like(self.k_out)
+        self.q_pos = data["q_pos"]
+        self.stream = torch.cuda.current_stream()
+        self.key_units = nl * Hkv * tokens
+
+    names = ["rope", "score_pass1", "score_pass2", "pool", "topk", "gather"]
+
+    def step(self, events=None):
+        D, w, stream = self.D, self.w, self.stream
+        d, Hq, N, nl = w.head_dim, w.n_q_heads, w.n_pseudo, w.n_layers
+
+        def mark(i):
+            if events is not None:
+                events[i].record(stream)
+        mark(0)
+        for b in range(w.batch):
+            D.dapq_rope_apply(self.q_pre[b], self.q[b], self.q_pos[b], N, nl * Hq, d, d, N * d, w.theta, 0, stream)
+        mark(1)
+        D.dapq_score_stats(self.shape, self.q, self.k, self.lse2, self.ws, stream)
+        mark(2)
+        D.dapq_score_accumulate(self.shape, self.q, self.k, self.lse2, self.S, self.ws, stream)
+        mark(3)
+        D.dapq_pool(self.shape, self.S, self.P, w.pool_width, stream)
+        mark(4)
+        D.dapq_topk(self.shape, self.P, w.budget, None, self.idx, self.count, None, stream)
+        mark(5)
+        D.dapq_gather(self.shape, self.k, self.v, self.idx, self.count, w.budget, self.k_out, self.v_out, stream)
+        mark(6)
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -99,76 +183,26 @@ def main():
     w = W.workload(args.workload, args.n_pseudo)
     if args.layers is not None:
         w = replace(w, n_layers=args.layers)
-
-    # ---------------------------------------------------------------- inputs (resident in HBM)
-    data = W.device_fill(w, args.seed, dev)
-    lens = data["lens"]
-    cu = data["cu_seqlens"] if w.ragged is not None else None
-    tokens = int(sum(lens))
-    k, v = data["k"], data["v"]
+    ctx = Context(w, args.seed, dev)
+    lens, tokens = ctx.lens, ctx.tokens
     d, Hq, Hkv, N, nl, B = w.head_dim, w.n_q_heads, w.n_kv_heads, w.n_pseudo, w.n_layers, w.batch
-    if w.layout == "hnd":
-        kstr = (Hkv * tokens * d, 0, tokens * d, d)
-        rope_k = dict(stride_row=d, stride_head=tokens * d)
-    else:
-        kstr = (tokens * Hkv * d, 0, d, Hkv * d)
-        rope_k = dict(stride_row=Hkv * d, stride_head=d)
-    for li in range(nl):           # keys are cached already rotated; done once, outside the timed region
-        D.dapq_rope_apply(k[li], k[li], data["k_pos"], tokens, Hkv, d, rope_k["stride_row"],
-                          rope_k["stride_head"], w.theta, 0)
-    # pseudo queries laid out [batch][layer][Hq][N][d] so that one rope call covers a sequence
-    q_pre = data["q"].permute(1, 0, 2, 3, 4).contiguous()
-    q = torch.empty_like(q_pre)
-    qstr = (Hq * N * d, nl * Hq * N * d, N * d, d)
-    shape = D.make_shape(n_layers=nl, batch=B, n_q_heads=Hq, n_kv_heads=Hkv, n_pseudo=N, total_tokens=tokens,
-                         cu_seqlens=cu, k_strides=kstr, v_strides=kstr, q_strides=qstr, scale=w.scale)
-    ws = torch.empty(D.workspace_bytes(shape), dtype=torch.uint8, device=dev)
-    lse2 = torch.empty((nl, B, Hq, N), dtype=torch.float32, device=dev)
-    S = torch.empty((nl, Hkv, tokens), dtype=torch.float32, device=dev)
-    P = torch.empty_like(S)
-    idx = torch.zeros((nl, B, Hkv, w.budget), dtype=torch.int32, device=dev)
-    count = torch.zeros((nl, B, Hkv), dtype=torch.int32, device=dev)
-    k_out = torch.zeros((nl, B, Hkv, w.budget, d), dtype=torch.bfloat16, device=dev)
-    v_out = torch.zeros_like(k_out)
-    q_pos = data["q_pos"]
-    stream = torch.cuda.current_stream()
-
-    names = ["rope", "score_pass1", "score_pass2", "pool", "topk", "gather"]
-
-    def step(events=None):
-        def mark(i):
-            if events is not None:
-                events[i].record(stream)
-        mark(0)
-        for b in range(B):
-            D.dapq_rope_apply(q_pre[b], q[b], q_pos[b], N, nl * Hq, d, d, N * d, w.theta, 0, stream)
-        mark(1)
-        D.dapq_score_stats(shape, q, k, lse2, ws, stream)
-        mark(2)
-        D.dapq_score_accumulate(shape, q, k, lse2, S, ws, stream)
-        mark(3)
-        D.dapq_pool(shape, S, P, w.pool_width, stream)
-        mark(4)
-        D.dapq_topk(shape, P, w.budget, None, idx, count, None, stream)
-        mark(5)
-        D.dapq_gather(shape, k, v, idx, count, w.budget, k_out, v_out, stream)
-        mark(6)
+    names = Context.names
 
     for _ in range(args.warmup):
-        step()
+        ctx.step()
     torch.cuda.synchronize()
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(7)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):
-        step(evs[s])
+        ctx.step(evs[s])
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt * 1e3 / args.steps
     per = {n: float(np.mean([evs[s][i].elapsed_time(evs[s][i + 1]) for s in range(args.steps)]))
            for i, n in enumerate(names)}
 
-    key_units = nl * Hkv * tokens
+    key_units = ctx.key_units
     value = key_units / (ms_per_step * 1e-3)
 
     # ---------------------------------------------------------------- roofline of the dominant kernel

@@ -1,0 +1,140 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The whole workload is built in HBM exactly as bench.py builds it (bench.Context).  A few (layer, KV
+head) slices are overwritten with host-generated bits (workloads.k_pre + the oracle's RoPE), so the
+float64 oracle can compute those heads one by one on the same inputs; every other head is checked
+through properties that hold at any size (mass conservation, ordering, bit-exact gathers, planted
+needles retained)."""
+import os
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from oracle import dapq_oracle as O
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+pytestmark = pytest.mark.gpu
+
+
+def announce(msg):
+    print(f"[gpu-case] {msg}", file=sys.__stderr__, flush=True)
+
+
+@pytest.fixture(scope="module")
+def env():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    sys.path.insert(0, ROOT)
+    import bench
+    import dapq_harness
+    return bench, dapq_harness
+
+
+def host_slice(w, seed, layer, seq, kv, L):
+    """Post-RoPE bits of one (layer, sequence, KV head) the way the oracle sees them."""
+    qp = W.q_pre(w, seed, layer, seq)
+    k = O.rope_apply(W.k_pre(w, seed, layer, seq, kv, L, qp)[:, None, :], W.k_positions(L), w.theta)[:, 0]
+    v = W.v_rows(w, seed, layer, seq, kv, L)
+    q = O.rope_apply(qp.transpose(1, 0, 2), W.q_positions(L, w.n_pseudo), w.theta).transpose(1, 0, 2)
+    return q, k, v
+
+
+def check_all_heads(ctx, w):
+    """Size-independent properties over every head, evaluated on the device."""
+    g, N, nl, Hkv = w.group, w.n_pseudo, w.n_layers, w.n_kv_heads
+    cu = ctx.cu_host
+    S, P, idx, count = ctx.S, ctx.P, ctx.idx, ctx.count
+    assert torch.isfinite(S).all() and (S > 0).all()
+    assert (P >= S).all()
+    for b, L in enumerate(ctx.lens):
+        s, e = int(cu[b]), int(cu[b + 1])
+        mass = S[:, :, s:e].double().sum(dim=2)
+        assert (mass - g * N).abs().max().item() < 1e-3 * g * N, "softmax mass is not conserved"
+        n = min(w.budget, L)
+        assert (count[:, b] == n).all()
+        ids = idx[:, b, :, :n].long()
+        assert (ids[..., 1:] > ids[..., :-1]).all() and ids.min() >= 0 and ids.max() < L
+        # every kept key scores at least as high as every dropped key of its head
+        Pb = P[:, :, s:e]
+        kept = torch.zeros_like(Pb, dtype=torch.bool)
+        kept.scatter_(2, ids, True)
+        lowest_kept = torch.where(kept, Pb, torch.full_like(Pb, float("inf"))).amin(dim=2)
+        highest_dropped = torch.where(kept, torch.full_like(Pb, -1.0), Pb).amax(dim=2)
+        assert (lowest_kept >= highest_dropped).all()
+        # gathers are bit copies of the rows the indices name
+        for name, src, dst in (("k", ctx.k, ctx.k_out), ("v", ctx.v, ctx.v_out)):
+            rows = src[:, :, s:e] if w.layout == "hnd" else src[:, s:e].permute(0, 2, 1, 3)
+            want = torch.gather(rows.view(torch.int16), 2, ids[..., None].expand(-1, -1, -1, w.head_dim))
+            assert torch.equal(dst[:, b, :, :n].view(torch.int16), want), name
+
+
+@pytest.mark.parametrize("name,samples", [("C2", [(0, 0), (17, 5), (31, 7)])])
+def test_full_size_dense_workload(env, name, samples):
+    bench, H = env
+    w = W.workload(name)
+    seed = 0
+    L = w.seq_len
+    announce(f"full size {name}: building the workload")
+    host = {(li, kv): host_slice(w, seed, li, 0, kv, L) for (li, kv) in samples}
+    ctx = bench.Context(w, seed, torch.device("cuda:0"),
+                        {(li, 0, kv): (k, v) for (li, kv), (q, k, v) in host.items()})
+    announce(f"full size {name}: one step")
+    ctx.step()
+    torch.cuda.synchronize()
+    check_all_heads(ctx, w)
+    # planted needles survive in every head (the device generator plants the same rows as the host one)
+    idx = ctx.idx.cpu().numpy()
+    for li in range(w.n_layers):
+        for kv in range(w.n_kv_heads):
+            pos, _, _ = W.needle_plan(w, seed, li, 0, kv, L)
+            assert set(pos.tolist()) <= set(idx[li, 0, kv].tolist()), (li, kv)
+    classes = {"exact": 0, "margin": 0}
+    for (li, kv), (q, k, v) in host.items():
+        announce(f"full size {name}: oracle for layer {li} head {kv}")
+        g = w.group
+        q_gpu = H.host_bits(ctx.q[0, li, kv * g:(kv + 1) * g])
+        assert np.array_equal(q_gpu, q[kv * g:(kv + 1) * g]), "rotated pseudo queries differ from the oracle's"
+        S_ref = O.score_head(O.bf16_bits_to_f64(q[kv * g:(kv + 1) * g]), O.bf16_bits_to_f64(k), w.scale)
+        P_ref = O.pool(S_ref, w.pool_width)
+        worst = H.assert_scores_close(ctx.S[li, kv].cpu().numpy(), S_ref, f"S[{li},{kv}]")
+        H.assert_scores_close(ctx.P[li, kv].cpu().numpy(), P_ref, f"P[{li},{kv}]")
+        classes[H.check_retained(P_ref, idx[li, 0, kv], w.budget)] += 1
+        keep = idx[li, 0, kv]
+        assert np.array_equal(H.host_bits(ctx.k_out[li, 0, kv]), k[keep])
+        assert np.array_equal(H.host_bits(ctx.v_out[li, 0, kv]), v[keep])
+        announce(f"full size {name}: layer {li} head {kv}: max rel err {worst:.2e}")
+    announce(f"full size {name}: sampled heads {classes}")
+
+
+def test_full_size_ragged_batch(env):
+    """The ragged heavy-hitter batch at its full shape but 4 of the 32 layers (the oracle side of a
+    sampled head is then ~1 s); N = 128 and g = 4 give 512 rows per KV head, the multi-slab path."""
+    bench, H = env
+    from dataclasses import replace
+    w = replace(W.workload("C3"), n_layers=4)
+    seed = 3
+    lens = W.seq_lens(w, seed)
+    announce(f"full size C3 (4 layers): lens {lens}")
+    samples = [(0, 0, 0), (3, 7, 5), (2, 3, 2)]
+    host = {(li, b, kv): host_slice(w, seed, li, b, kv, lens[b]) for (li, b, kv) in samples}
+    ctx = bench.Context(w, seed, torch.device("cuda:0"), {key: (k, v) for key, (q, k, v) in host.items()})
+    ctx.step()
+    torch.cuda.synchronize()
+    check_all_heads(ctx, w)
+    cu = ctx.cu_host
+    idx = ctx.idx.cpu().numpy()
+    for (li, b, kv), (q, k, v) in host.items():
+        s, e = int(cu[b]), int(cu[b + 1])
+        g = w.group
+        assert np.array_equal(H.host_bits(ctx.q[b, li, kv * g:(kv + 1) * g]), q[kv * g:(kv + 1) * g])
+        S_ref = O.score_head(O.bf16_bits_to_f64(q[kv * g:(kv + 1) * g]), O.bf16_bits_to_f64(k), w.scale)
+        P_ref = O.pool(S_ref, w.pool_width)
+        worst = H.assert_scores_close(ctx.S[li, kv, s:e].cpu().numpy(), S_ref, f"S[{li},{b},{kv}]")
+        cls = H.check_retained(P_ref, idx[li, b, kv], w.budget)
+        keep = idx[li, b, kv]
+        assert np.array_equal(H.host_bits(ctx.k_out[li, b, kv]), k[keep])
+        assert np.array_equal(H.host_bits(ctx.v_out[li, b, kv]), v[keep])
+        announce(f"full size C3: layer {li} seq {b} head {kv}: max rel err {worst:.2e}, set {cls}")
