@@ -23,9 +23,13 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE,
-# scaled by a copy kernel of known size); see profiles/.  None until measured for that workload.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch), each scaled
+# by what the same counter reads for a copy kernel of known size in the same run (the fp32 -> bf16 conversion
+# of the input generator: 128 MiB read, 64 MiB written); profiles/score_pass2_c2_hbm_traffic.md.
+MEASURED_TRAFFIC_BYTES = {
+    ("C2", "score_pass2"): 2.319e9,   # 2.285 GB fetched (1.064 x the key bytes: Q is re-read per chunk) + 32 MiB written
+    ("C2", "score_pass1"): 2.300e9,
+}
 
 
 def parse():
