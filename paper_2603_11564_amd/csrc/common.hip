@@ -79,8 +79,10 @@ int make_score_plan(const dapq_shape* s, ScorePlan* p) {
     p->key_waves = 1;
     p->n_super = 1;
     p->rows_pad = p->row_blocks * 32;
-    // as long as possible (Q is reloaded per chunk) while there are >= 4 chunks per SIMD (1024 SIMDs)
-    while (chunk > kTileKeys && heads * ((s->total_tokens + chunk - 1) / chunk) < 4096) chunk /= 2;
+    // one wave per chunk and, if the work allows, one chunk per SIMD (1024 of them): every wave is
+    // launched once, loads Q once and streams for the whole kernel
+    chunk = 1 << 16;
+    while (chunk > kTileKeys && heads * ((s->total_tokens + chunk - 1) / chunk) < 1024) chunk /= 2;
   } else {
     const int slabs = (p->rows + 63) / 64;  // 64-row slabs
     p->row_blocks = 0;

@@ -727,11 +727,19 @@ __device__ __forceinline__ void wait_subblocks(int newer) {
   else asm volatile("s_waitcnt vmcnt(32)" ::: "memory");
 }
 
+template <int NST>
+__device__ __forceinline__ void wait_ring_full() {
+  static_assert(NST >= 2 && NST <= 5, "ring sizes the kernels use");
+  if (NST == 5) asm volatile("s_waitcnt vmcnt(32)" ::: "memory");
+  else if (NST == 4) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+  else if (NST == 3) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+  else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+}
+
 #define DAPQ_WAVE_SLICE_END(cur, prev, e0, e1, sa, sb, la, lb, addr) \
-  asm volatile("" : "+v"(cur), "+v"(prev), "+v"(e0), "+v"(e1), "+v"(sa), "+v"(sb), "+v"(la), "+v"(lb), "+v"(addr))
+  asm volatile("" : "+v"(prev), "+v"(e0), "+v"(e1), "+v"(sa), "+v"(sb), "+v"(la), "+v"(lb), "+v"(addr))
 #define DAPQ_WAVE_SLICE_END2(cur, prev, e0, e1, sa, sb, la, lb, addr, addr2)                                          \
-  asm volatile("" : "+v"(cur), "+v"(prev), "+v"(e0), "+v"(e1), "+v"(sa), "+v"(sb), "+v"(la), "+v"(lb), "+v"(addr), \
-               "+v"(addr2))
+  asm volatile("" : "+v"(prev), "+v"(e0), "+v"(e1), "+v"(sa), "+v"(sb), "+v"(la), "+v"(lb), "+v"(addr), "+v"(addr2))
 
 // exponentials of two logits: x = a*c + o; the pair issued in the previous step is added now
 #define DAPQ_VALU_STEP(a0, a1, o0, o1)              \
@@ -774,8 +782,11 @@ __device__ __forceinline__ void wave_walk(u32x4* ring, const uint16_t* kbase, in
 #pragma unroll
   for (int rb = 0; rb < NRB; ++rb) acc[rb] = 0.0f;
 
+  int issue_slot = issued % NST;       // ring slot the next transfer goes to
+  int read_slot = (sb0 + 1) % NST;     // ring slot of the sub-block after the current one
   for (int sub = sb0; sub < sb1; ++sub) {
-    const unsigned next_slot = (unsigned)((sub + 1) % NST) * (unsigned)kSubBytes;
+    const unsigned next_slot = (unsigned)read_slot * (unsigned)kSubBytes;
+    read_slot = read_slot + 1 == NST ? 0 : read_slot + 1;
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) {
       constexpr int kLast = NRB - 1;
@@ -784,11 +795,15 @@ __device__ __forceinline__ void wave_walk(u32x4* ring, const uint16_t* kbase, in
       if (rb == 1) {
         // the slot of this sub-block is free (its fragments are in registers and have been used)
         if (issued < nsubs) {
-          sub_dma(ring + (issued % NST) * kSubVec, kbase, stride_token, issued * 32, nkeys, lane);
+          sub_dma(ring + issue_slot * kSubVec, kbase, stride_token, issued * 32, nkeys, lane);
           ++issued;
+          issue_slot = issue_slot + 1 == NST ? 0 : issue_slot + 1;
         }
       }
-      if (rb == kLast && sub + 1 < nsubs) wait_subblocks(issued - (sub + 2));  // sub-block sub+1 has landed
+      if (rb == kLast && sub + 1 < nsubs) {  // sub-block sub+1 must have landed
+        if (issued - (sub + 2) == NST - 1) wait_ring_full<NST>();  // the common case: a full ring in flight
+        else wait_subblocks(issued - (sub + 2));
+      }
       f32x16 cur = {0};
 #pragma unroll
       for (int s = 0; s < 8; ++s) {
