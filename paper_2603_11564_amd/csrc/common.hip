@@ -70,19 +70,22 @@ int make_score_plan(const dapq_shape* s, ScorePlan* p) {
                (long long)rows64);
   p->rows = (int)rows64;
   const int64_t heads = (int64_t)s->n_layers * s->n_kv_heads;
-  p->wave_path = p->rows <= 256;
+  p->wave_path = true;
+  p->n_groups = 1;
   int chunk = kMaxChunkKeys;
   if (p->wave_path) {
-    // one wave per chunk: all rows in its registers
+    // one wave per (chunk, row group): a group is up to 256 rows, all in the wave's registers
+    p->n_groups = (p->rows + 255) / 256;
+    DAPQ_REQUIRE(p->n_groups <= 65535, DAPQ_ERR_UNSUPPORTED, "too many query rows per KV head");
     p->row_blocks = p->rows <= 64 ? 2 : (p->rows <= 128 ? 4 : 8);
     p->row_waves = 1;
     p->key_waves = 1;
     p->n_super = 1;
-    p->rows_pad = p->row_blocks * 32;
-    // one wave per chunk and, if the work allows, one chunk per SIMD (1024 of them): every wave is
-    // launched once, loads Q once and streams for the whole kernel
+    p->rows_pad = p->n_groups * p->row_blocks * 32;
+    // if the work allows, one wave per SIMD (1024 of them): every wave is launched once, loads Q
+    // once and streams for the whole kernel
     chunk = 1 << 16;
-    while (chunk > kTileKeys && heads * ((s->total_tokens + chunk - 1) / chunk) < 1024) chunk /= 2;
+    while (chunk > kTileKeys && heads * p->n_groups * ((s->total_tokens + chunk - 1) / chunk) < 1024) chunk /= 2;
   } else {
     const int slabs = (p->rows + 63) / 64;  // 64-row slabs
     p->row_blocks = 0;
@@ -112,6 +115,8 @@ int make_score_plan(const dapq_shape* s, ScorePlan* p) {
   off = align_up(off + sizeof(float) * 2 * (size_t)heads * (size_t)p->max_chunks * p->key_waves * p->rows_pad, 256);
   p->off_lse2 = off;
   off = align_up(off + sizeof(float) * (size_t)s->n_layers * s->batch * s->n_q_heads * s->n_pseudo, 256);
+  p->off_partial = off;
+  if (p->n_groups > 1) off = align_up(off + sizeof(float) * (size_t)p->n_groups * (size_t)heads * (size_t)s->total_tokens, 256);
   p->total_bytes = off;
   return DAPQ_OK;
 }

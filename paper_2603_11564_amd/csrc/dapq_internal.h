@@ -35,6 +35,7 @@ constexpr int kMaxChunkKeys = 2048; // most keys one workgroup of a score pass w
 struct ScorePlan {
   int rows;        // R = (H_q/H_kv) * N query rows scored against every key of a KV head
   bool wave_path;  // R <= 256: every wave holds all rows and walks its own chunk (no workgroup sharing)
+  int n_groups;    // wave path: row groups of row_blocks * 32 rows, one wave each per chunk
   int row_blocks;  // wave path: 32-row blocks per wave (2, 4 or 8)
   int row_waves;   // RW in {1,2,4}: waves of a workgroup that hold different 64-row slabs of Q
   int key_waves;   // 4 / RW: waves that share a slab and split the keys of a tile
@@ -43,7 +44,7 @@ struct ScorePlan {
   int chunk_keys;  // keys per workgroup (multiple of kTileKeys)
   int64_t max_chunks;  // grid size along the key axis: upper bound on sum_b ceil(L_b / chunk_keys)
   // workspace carving (byte offsets)
-  size_t off_cu_chunks, off_parts, off_lse2, total_bytes;
+  size_t off_cu_chunks, off_parts, off_lse2, off_partial, total_bytes;
 };
 
 // Validates the fields every entry point relies on.  need_q / need_k / need_v say which stride

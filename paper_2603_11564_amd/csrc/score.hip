@@ -43,11 +43,12 @@ struct ScoreParams {
   float2* parts;              // [layer*Hkv][max_chunks][KW][rows_pad] (reference, sum) in the log2 domain
   float* lse2;                // [layer][batch][Hq][N]
   float* scores;              // [layer][Hkv][total_tokens]
+  float* partial;             // [n_groups][layer][Hkv][total_tokens] per-row-group column sums (n_groups > 1)
   int64_t k_stride_layer, k_stride_seq, k_stride_head, k_stride_token;
   int64_t q_stride_layer, q_stride_seq, q_stride_head, q_stride_row;
   int64_t total_tokens;
   int32_t n_layers, batch, n_q_heads, n_kv_heads, group, n_pseudo;
-  int32_t rows, rows_pad, n_super, chunk_keys, max_chunks;
+  int32_t rows, rows_pad, n_super, n_groups, chunk_keys, max_chunks;
   float c;  // scale * log2(e)
 };
 
@@ -691,31 +692,36 @@ constexpr int kSubVec = kSubBytes / 16;   // 512 16-byte chunks per sub-block
 constexpr int kWaveLds1 = kWaveStages1 * kSubBytes;
 constexpr int kWaveLds2 = kWaveStages2 * kSubBytes + 256 * (int)sizeof(float);
 
-// One wave moves one 32-key sub-block into an LDS slot: 8 transfers of 1 KB (4 key rows each).
+// Per-lane byte offsets of the four distinct 16-byte chunks a lane fetches in sub_dma: transfer i
+// moves key rows 4i..4i+3, lane (row0 = lane / 16, pos = lane % 16) fills LDS position pos of row
+// 4i + row0 with the logical chunk pos ^ ((4i + row0) & 15) = (pos ^ row0) ^ (4 * (i & 3)).
+__device__ __forceinline__ void sub_dma_lane_offsets(unsigned (&voff)[4], int64_t stride_token, int lane) {
+  const unsigned row0 = (unsigned)lane >> 4, pos = (unsigned)lane & 15u;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) voff[j] = row0 * (unsigned)stride_token * 2u + ((pos ^ row0) ^ (4u * j)) * 16u;
+}
+
+// One wave moves the 32-key sub-block that starts at key0 into an LDS slot: 8 transfers of 1 KB
+// (buffer_load_dwordx4 ... lds).  The buffer descriptor spans from the first row of the sub-block to
+// the end of the last key row of the chunk, so rows past the end of the chunk read as zeros; the
+// uniform part of every address lives in scalar registers (descriptor base, scalar offset per
+// transfer) and the lane part is one of the four precomputed offsets.  A sub-block that starts at or
+// past the end of the chunk gets an empty descriptor: the eight transfers still count as vector
+// memory operations (the waits rely on a fixed number per sub-block) but fetch nothing and fill the
+// slot with zeros.
 __device__ __forceinline__ void sub_dma(u32x4* slot, const uint16_t* kbase, int64_t stride_token, int key0, int nkeys,
-                                        int lane) {
-  const int row0 = lane >> 4, pos = lane & 15;
-  if (key0 + 32 <= nkeys) {
-    const char* base = reinterpret_cast<const char*>(kbase + (int64_t)key0 * stride_token);
-    const unsigned row_off = (unsigned)row0 * (unsigned)stride_token * 2u;
+                                        const unsigned (&voff)[4]) {
+  const int64_t stride_b = stride_token * 2;
+  const bool live = key0 < nkeys;
+  const char* base = reinterpret_cast<const char*>(kbase) + (live ? (int64_t)key0 * stride_b : (int64_t)0);
+  const int64_t span = (int64_t)(nkeys - key0 - 1) * stride_b + kHeadDim * 2;
+  const unsigned records = !live ? 0u : (span > (int64_t)0xFFFFFFFFll ? 0xFFFFFFFFu : (unsigned)span);
+  const __amdgpu_buffer_rsrc_t rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(base), 0, (int)records, 0x00020000);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const unsigned ch = (unsigned)(pos ^ ((4 * i + row0) & 15));
-      const char* src = base + (int64_t)(4 * i) * stride_token * 2 + (row_off + ch * 16u);
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                       (__attribute__((address_space(3))) void*)(slot + i * 64), 16, 0, 0);
-    }
-  } else {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int row = 4 * i + row0;
-      int gk = key0 + row;
-      gk = gk < nkeys ? gk : nkeys - 1;  // rows past the end repeat the last key
-      const uint16_t* src = kbase + (int64_t)gk * stride_token + (pos ^ (row & 15)) * 8;
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                       (__attribute__((address_space(3))) void*)(slot + i * 64), 16, 0, 0);
-    }
-  }
+  for (int i = 0; i < 8; ++i)
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)(slot + i * 64), 16,
+                                             (int)voff[i & 3], (int)((unsigned)(4 * i) * (unsigned)stride_b), 0, 0);
 }
 
 // Waits until at most `newer` sub-block transfers (8 operations each) of this wave are in flight.
@@ -736,53 +742,75 @@ __device__ __forceinline__ void wait_ring_full() {
   else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
 }
 
-#define DAPQ_WAVE_SLICE_END(cur, prev, e0, e1, sa, sb, la, lb, addr) \
-  asm volatile("" : "+v"(prev), "+v"(e0), "+v"(e1), "+v"(sa), "+v"(sb), "+v"(la), "+v"(lb), "+v"(addr))
-#define DAPQ_WAVE_SLICE_END2(cur, prev, e0, e1, sa, sb, la, lb, addr, addr2)                                          \
-  asm volatile("" : "+v"(prev), "+v"(e0), "+v"(e1), "+v"(sa), "+v"(sb), "+v"(la), "+v"(lb), "+v"(addr), "+v"(addr2))
+// The instruction order is pinned with empty asm statements that take values as read-write operands:
+// what produces an operand must come before the statement, what uses it after.  One sits right
+// after the MFMA of a slice (it "redefines" the K fragment the MFMA read and the two pending
+// exponents, so the MFMA leads the slice and the vector work follows), one at the end of the slice.
+// Neither names a transcendental's result or the accumulator in flight: both would cost wait states.
+#define DAPQ_WAVE_SLICE_MID(kfrag, x0, x1) asm volatile("" : "+v"(kfrag), "+v"(x0), "+v"(x1))
+#define DAPQ_WAVE_SLICE_END(prev, x0, x1, t0, t1, addr) \
+  asm volatile("" : "+v"(prev), "+v"(x0), "+v"(x1), "+v"(t0), "+v"(t1), "+v"(addr))
 
-// exponentials of two logits: x = a*c + o; the pair issued in the previous step is added now
-#define DAPQ_VALU_STEP(a0, a1, o0, o1)              \
-  do {                                              \
-    const float x0_ = fmaf((a0), c, (o0));          \
-    const float x1_ = fmaf((a1), c, (o1));          \
-    sa += e0;                                       \
-    sb += e1;                                       \
-    e0 = __builtin_amdgcn_exp2f(x0_);               \
-    e1 = __builtin_amdgcn_exp2f(x1_);               \
+// One step of the four-stage vector pipeline over pairs of logits: the exponentials started two
+// steps ago (p0, p1: two sets of registers take turns) are added to the sums they belong to (t0,
+// t1), the exponents formed in the previous step are exponentiated into the registers just freed,
+// and the exponents of a new pair are formed (x = a*c + o).  Every result is first read a full step
+// after the instruction that produces it, whatever order the compiler picks inside a step.
+#define DAPQ_VALU_STEP(a0, a1, o0, o1, t0, t1, p0, p1) \
+  do {                                                 \
+    t0 += p0;                                          \
+    t1 += p1;                                          \
+    p0 = __builtin_amdgcn_exp2f(x0);                   \
+    p1 = __builtin_amdgcn_exp2f(x1);                   \
+    x0 = fmaf((a0), c, (o0));                          \
+    x1 = fmaf((a1), c, (o1));                          \
+  } while (0)
+// step k of a unit: even steps use the first set of pending exponentials, odd steps the second
+#define DAPQ_VALU_STEP_K(k, a0, a1, o0, o1, t0, t1)                     \
+  do {                                                                  \
+    if ((k) % 2 == 0) DAPQ_VALU_STEP(a0, a1, o0, o1, t0, t1, ea0, ea1); \
+    else DAPQ_VALU_STEP(a0, a1, o0, o1, t0, t1, eb0, eb1);              \
   } while (0)
 
 // Pipelined walk of one wave over sub-blocks [sb0, sb1) of its chunk.
-//   on entry  kf = fragments of sub-block sb0; transfers of all sub-blocks < issued are under way
-//   on exit   kf = fragments of sub-block sb1 if sb1 < nsubs
+//   on entry  kf = fragments of sub-block sb0; the transfers of sub-blocks sb0+1 .. sb0+NST-1 are
+//             under way (sub-block i lives in ring slot i % NST)
+//   on exit   kf = fragments of sub-block sb1 (zeros if it does not exist)
+// Every iteration issues the transfer of sub-block sub+NST into the slot of the current sub-block
+// once its fragments are in registers, and waits for sub-block sub+1 before its last unit; as every
+// sub-block is 8 operations, existing or not, that wait is a fixed count.
+// A unit is one sub-block against one 32-row block of Q: 8 MFMAs, one per slice.  While the MFMAs
+// of a unit issue, the 16 logits per lane of the unit before it enter the vector pipeline in 8
+// steps: none in slice 0 (the transfer issue, the ring wait and the loop bookkeeping sit there, and
+// the first logits are then more than a slice old), one in each of slices 1..6, two in slice 7.
+// The sum a step adds to belongs to the pair three steps back: steps 0..2 of a unit still feed the
+// unit two back.
 // PASS 1: off1[rb] = -(reference logit * c) of row block rb; acc[rb] receives the row sums.
 // PASS 2: the LDS table at byte address nbt holds -lse2 of every row (-inf for padding rows); the
 //         16 values a lane needs for a row block (its accumulator rows) are fetched one unit ahead.
-//         S of every key is written to out.
+//         S of every key goes to out.
 // NST = slots of the sub-block ring.
 template <int NRB, int PASS, int NST>
 __device__ __forceinline__ void wave_walk(u32x4* ring, const uint16_t* kbase, int64_t stride_token, int nkeys,
-                                          int nsubs, int sb0, int sb1, int& issued, bf16x8 (&kf)[8],
-                                          const bf16x8 (&qf)[NRB][8], float c, const float (&off1)[NRB], unsigned nbt,
-                                          float (&acc)[NRB], float* out, int lane, int n, int h) {
+                                          int sb0, int sb1, bf16x8 (&kf)[8], const bf16x8 (&qf)[NRB][8], float c,
+                                          const float (&off1)[NRB], unsigned nbt, float (&acc)[NRB], float* out,
+                                          const unsigned (&voff)[4], int n, int h) {
   const unsigned ring_base = (unsigned)(uintptr_t)(lds_vec_ptr)ring;
   unsigned fa[8];
 #pragma unroll
   for (int s = 0; s < 8; ++s) fa[s] = ring_base + (unsigned)(n * 16 + ((2 * s + h) ^ (n & 15))) * 16u;
-  unsigned nba = nbt + (unsigned)h * 16u;  // pass 2: this lane's first table entry (row 4h)
+  const unsigned nba = nbt + (unsigned)h * 16u;  // pass 2: this lane's first table entry (row 4h)
   f32x16 prev;
 #pragma unroll
   for (int v = 0; v < 16; ++v) prev[v] = -INFINITY;  // 2^(-inf) = 0: the first steps add nothing
-  float la = -INFINITY, lb = -INFINITY;              // last two logits of the unit before prev
-  float e0 = 0.0f, e1 = 0.0f, sa = 0.0f, sb = 0.0f;
-  f32x4 oc[4], on[4];                                // pass 2: offsets of prev's rows / of cur's rows
-  float oa = 0.0f, ob = 0.0f;                        // pass 2: offsets that go with la, lb
+  float x0 = -INFINITY, x1 = -INFINITY, ea0 = 0.0f, ea1 = 0.0f, eb0 = 0.0f, eb1 = 0.0f, sa = 0.0f, sb = 0.0f;
+  f32x4 oc[4], on[4];  // pass 2: offsets of prev's rows / of cur's rows
 #pragma unroll
   for (int b = 0; b < 4; ++b) oc[b] = on[b] = (f32x4){0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
   for (int rb = 0; rb < NRB; ++rb) acc[rb] = 0.0f;
 
-  int issue_slot = issued % NST;       // ring slot the next transfer goes to
+  int issue_slot = sb0 % NST;          // ring slot of the current sub-block: the next transfer goes there
   int read_slot = (sb0 + 1) % NST;     // ring slot of the sub-block after the current one
   for (int sub = sb0; sub < sb1; ++sub) {
     const unsigned next_slot = (unsigned)read_slot * (unsigned)kSubBytes;
@@ -791,81 +819,77 @@ __device__ __forceinline__ void wave_walk(u32x4* ring, const uint16_t* kbase, in
     for (int rb = 0; rb < NRB; ++rb) {
       constexpr int kLast = NRB - 1;
       const int rb1 = (rb + NRB - 1) % NRB;  // row block of the previous unit (prev)
-      const int rb2 = (rb + NRB - 2) % NRB;  // row block of the unit before it (la, lb)
+      const int rb2 = (rb + NRB - 2) % NRB;  // row block of the unit before it
       if (rb == 1) {
         // the slot of this sub-block is free (its fragments are in registers and have been used)
-        if (issued < nsubs) {
-          sub_dma(ring + issue_slot * kSubVec, kbase, stride_token, issued * 32, nkeys, lane);
-          ++issued;
-          issue_slot = issue_slot + 1 == NST ? 0 : issue_slot + 1;
-        }
+        sub_dma(ring + issue_slot * kSubVec, kbase, stride_token, (sub + NST) * 32, nkeys, voff);
+        issue_slot = issue_slot + 1 == NST ? 0 : issue_slot + 1;
       }
-      if (rb == kLast && sub + 1 < nsubs) {  // sub-block sub+1 must have landed
-        if (issued - (sub + 2) == NST - 1) wait_ring_full<NST>();  // the common case: a full ring in flight
-        else wait_subblocks(issued - (sub + 2));
-      }
+      if (rb == kLast) wait_ring_full<NST>();  // sub-block sub+1 has landed: NST-1 newer ones are in flight
       f32x16 cur = {0};
 #pragma unroll
       for (int s = 0; s < 8; ++s) {
         if (PASS == 1) cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[rb][s], cur, 0, 0, 0);
         else cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][s], kf[s], cur, 0, 0, 0);
+        DAPQ_WAVE_SLICE_MID(kf[s], x0, x1);
         if (rb == kLast) kf[s] = lds_read16(fa[s] + next_slot, 0);  // last use: fetch the next sub-block's
-        if (PASS == 2 && s >= 2 && s < 6)  // offsets of this unit's rows, needed from the next unit on
-          on[s - 2] = *(const f32x4 __attribute__((address_space(3)))*)(uintptr_t)(nba + (rb * 32 + 8 * (s - 2)) * 4);
-        if (s == 0) {
-          DAPQ_VALU_STEP(la, lb, PASS == 1 ? off1[rb2] : oa, PASS == 1 ? off1[rb2] : ob);
-        } else {
-          DAPQ_VALU_STEP(prev[2 * s - 2], prev[2 * s - 1], PASS == 1 ? off1[rb1] : oc[(2 * s - 2) >> 2][(2 * s - 2) & 3],
-                         PASS == 1 ? off1[rb1] : oc[(2 * s - 1) >> 2][(2 * s - 1) & 3]);
-        }
-        if (s == 1) {
-          // the add above took in the last two logits of the unit two back: that unit is complete
-          if (PASS == 1) {
-            acc[rb2] += sa + sb;
-            sa = sb = 0.0f;
-          } else if (rb == 1) {
-            // ... and it closed a sub-block: the column sum of a key is complete
-            if (sub > sb0) {
-              const float total = sa + sb;
-              const float both = total + xhalf(total);
-              const int key = (sub - 1) * 32 + n;
-              if (h == 0 && key < nkeys) out[key] = both;
+        if (PASS == 2) {
+          if (s >= 1 && s <= 4)  // offsets of this unit's rows, needed from the next unit on
+            on[s - 1] = *(const f32x4 __attribute__((address_space(3)))*)(uintptr_t)(nba + (rb * 32 + 8 * (s - 1)) * 4);
+          if (s == 7) {
+            DAPQ_VALU_STEP_K(6, prev[12], prev[13], oc[3][0], oc[3][1], sa, sb);
+            DAPQ_VALU_STEP_K(7, prev[14], prev[15], oc[3][2], oc[3][3], sa, sb);
+          } else if (s >= 1) {
+            DAPQ_VALU_STEP_K(s - 1, prev[2 * s - 2], prev[2 * s - 1], oc[(2 * s - 2) >> 2][(2 * s - 2) & 3],
+                             oc[(2 * s - 1) >> 2][(2 * s - 1) & 3], sa, sb);
+            if (s == 3 && rb == 1) {
+              // the adds above took in the last logits of the previous sub-block: its column sums are complete
+              if (sub > sb0) {
+                const float total = sa + sb;
+                const float both = total + xhalf(total);
+                const int key = (sub - 1) * 32 + n;
+                if (h == 0 && key < nkeys) out[key] = both;
+              }
+              sa = sb = 0.0f;
             }
-            sa = sb = 0.0f;
           }
+          DAPQ_WAVE_SLICE_END(prev, x0, x1, sa, sb, fa[(s + 1) & 7]);
+        } else {
+          if (s == 7) {
+            DAPQ_VALU_STEP_K(6, prev[12], prev[13], off1[rb1], off1[rb1], acc[rb1], acc[rb1]);
+            DAPQ_VALU_STEP_K(7, prev[14], prev[15], off1[rb1], off1[rb1], acc[rb1], acc[rb1]);
+          } else if (s >= 1 && s <= 3) {
+            DAPQ_VALU_STEP_K(s - 1, prev[2 * s - 2], prev[2 * s - 1], off1[rb1], off1[rb1], acc[rb2], acc[rb2]);
+          } else if (s >= 4) {
+            DAPQ_VALU_STEP_K(s - 1, prev[2 * s - 2], prev[2 * s - 1], off1[rb1], off1[rb1], acc[rb1], acc[rb1]);
+          }
+          DAPQ_WAVE_SLICE_END(prev, x0, x1, acc[rb1], acc[rb2], fa[(s + 1) & 7]);
         }
-        if (PASS == 1) DAPQ_WAVE_SLICE_END(cur, prev, e0, e1, sa, sb, la, lb, fa[(s + 1) & 7]);
-        else DAPQ_WAVE_SLICE_END2(cur, prev, e0, e1, sa, sb, la, lb, fa[(s + 1) & 7], nba);
       }
-      la = prev[14];
-      lb = prev[15];
       prev = cur;
       if (PASS == 2) {
-        oa = oc[3][2];
-        ob = oc[3][3];
 #pragma unroll
         for (int b = 0; b < 4; ++b) oc[b] = on[b];
       }
     }
   }
 
-  // drain: prev = last unit (row block NRB-1), la/lb = tail of the unit before it
+  // drain: prev = last unit (row block NRB-1); three more steps on -inf flush the pipeline
   {
     constexpr int rbl = NRB - 1, rbl1 = NRB - 2;
-    DAPQ_VALU_STEP(la, lb, PASS == 1 ? off1[rbl1] : oa, PASS == 1 ? off1[rbl1] : ob);
 #pragma unroll
-    for (int s = 1; s <= 8; ++s) {
-      DAPQ_VALU_STEP(prev[2 * s - 2], prev[2 * s - 1], PASS == 1 ? off1[rbl] : oc[(2 * s - 2) >> 2][(2 * s - 2) & 3],
-                     PASS == 1 ? off1[rbl] : oc[(2 * s - 1) >> 2][(2 * s - 1) & 3]);
-      if (s == 1 && PASS == 1) {
-        acc[rbl1] += sa + sb;
-        sa = sb = 0.0f;
+    for (int k = 0; k < 11; ++k) {
+      const float a0 = k < 8 ? prev[(2 * k) & 15] : -INFINITY, a1 = k < 8 ? prev[(2 * k + 1) & 15] : -INFINITY;
+      if (PASS == 1) {
+        if (k < 3) DAPQ_VALU_STEP_K(k, a0, a1, off1[rbl], off1[rbl], acc[rbl1], acc[rbl1]);
+        else DAPQ_VALU_STEP_K(k, a0, a1, off1[rbl], off1[rbl], acc[rbl], acc[rbl]);
+      } else {
+        DAPQ_VALU_STEP_K(k, a0, a1, oc[((2 * k) & 15) >> 2][(2 * k) & 3], oc[((2 * k + 1) & 15) >> 2][(2 * k + 1) & 3], sa,
+                         sb);
       }
     }
-    const float total = (sa + e0) + (sb + e1);
-    if (PASS == 1) {
-      acc[rbl] += total;
-    } else if (sb1 > sb0) {
+    if (PASS == 2 && sb1 > sb0) {
+      const float total = sa + sb;
       const float both = total + xhalf(total);
       const int key = (sb1 - 1) * 32 + n;
       if (h == 0 && key < nkeys) out[key] = both;
@@ -937,13 +961,16 @@ __global__ __launch_bounds__(64, 1) void score_wave_pass1_kernel(ScoreParams p) 
                           (int64_t)kv * p.group * p.q_stride_head;
   const uint16_t* kbase = p.k + (int64_t)layer * p.k_stride_layer + (int64_t)w.seq * p.k_stride_seq +
                           (int64_t)kv * p.k_stride_head + w.tok0 * p.k_stride_token;
+  const int gbase = blockIdx.y * (NRB * 32);  // first row of this wave's row group
   const int nsubs = (w.nkeys + 31) / 32, nfull = w.nkeys / 32;
-  int issued = 0;
-  for (; issued < kWaveStages1 && issued < nsubs; ++issued)
-    sub_dma(ring + issued * kSubVec, kbase, p.k_stride_token, issued * 32, w.nkeys, lane);
+  unsigned voff[4];
+  sub_dma_lane_offsets(voff, p.k_stride_token, lane);
+  // the ring is filled whether the sub-blocks exist or not (sub_dma): the waits count operations
+#pragma unroll
+  for (int i = 0; i < kWaveStages1; ++i) sub_dma(ring + i * kSubVec, kbase, p.k_stride_token, i * 32, w.nkeys, voff);
   bf16x8 qf[NRB][8];
 #pragma unroll
-  for (int rb = 0; rb < NRB; ++rb) frag_from_q(qf[rb], p, qbase, rb * 32 + n, h);
+  for (int rb = 0; rb < NRB; ++rb) frag_from_q(qf[rb], p, qbase, gbase + rb * 32 + n, h);
   if (NRB == 8) pin_q_in_agprs<NRB>(qf);
 
   float ref[NRB], z[NRB];
@@ -953,23 +980,20 @@ __global__ __launch_bounds__(64, 1) void score_wave_pass1_kernel(ScoreParams p) 
     z[rb] = 0.0f;
   }
   bf16x8 kf[8];
-  wait_subblocks(issued - 1);
+  wait_subblocks(kWaveStages1 - 1);
   wave_load_frags<NRB>(kf, ring, n, h);
   // sub-block 0 the plain way: it fixes the reference logits
   wave_sub_simple<NRB, false, true>(kf, qf, p.c, ref, z, 0, w.nkeys, h);
   if (nsubs > 1) {
-    wait_subblocks(issued - 2);
+    wait_subblocks(kWaveStages1 - 2);
     wave_load_frags<NRB>(kf, ring + kSubVec, n, h);
-    if (issued < nsubs) {  // slot 0 is free
-      sub_dma(ring + (issued % kWaveStages1) * kSubVec, kbase, p.k_stride_token, issued * 32, w.nkeys, lane);
-      ++issued;
-    }
+    sub_dma(ring, kbase, p.k_stride_token, kWaveStages1 * 32, w.nkeys, voff);  // slot 0 is free
     if (nfull > 1) {
       float off[NRB], zs[NRB];
 #pragma unroll
       for (int rb = 0; rb < NRB; ++rb) off[rb] = -ref[rb];
-      wave_walk<NRB, 1, kWaveStages1>(ring, kbase, p.k_stride_token, w.nkeys, nsubs, 1, nfull, issued, kf, qf, p.c, off,
-                                      0u, zs, nullptr, lane, n, h);
+      wave_walk<NRB, 1, kWaveStages1>(ring, kbase, p.k_stride_token, w.nkeys, 1, nfull, kf, qf, p.c, off, 0u, zs, nullptr,
+                                      voff, n, h);
 #pragma unroll
       for (int rb = 0; rb < NRB; ++rb) z[rb] += zs[rb];
     }
@@ -990,7 +1014,7 @@ __global__ __launch_bounds__(64, 1) void score_wave_pass1_kernel(ScoreParams p) 
       z[rb] = 0.0f;
     }
     for (int sub = 0; sub < nsubs; ++sub) {
-      sub_dma(ring, kbase, p.k_stride_token, sub * 32, w.nkeys, lane);
+      sub_dma(ring, kbase, p.k_stride_token, sub * 32, w.nkeys, voff);
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       wave_load_frags<NRB>(kf, ring, n, h);
       wave_sub_simple<NRB, true, false>(kf, qf, p.c, ref, z, sub * 32, w.nkeys, h);
@@ -998,7 +1022,7 @@ __global__ __launch_bounds__(64, 1) void score_wave_pass1_kernel(ScoreParams p) 
   }
 
   // the two lane halves hold different keys of the same query
-  float2* outp = p.parts + ((int64_t)blockIdx.z * p.max_chunks + blockIdx.x) * p.rows_pad;
+  float2* outp = p.parts + ((int64_t)blockIdx.z * p.max_chunks + blockIdx.x) * p.rows_pad + gbase;
 #pragma unroll
   for (int rb = 0; rb < NRB; ++rb) {
     const float zz = z[rb] + xhalf(z[rb]);
@@ -1018,30 +1042,44 @@ __global__ __launch_bounds__(64, 1) void score_wave_pass2_kernel(ScoreParams p) 
   const uint16_t* kbase = p.k + (int64_t)layer * p.k_stride_layer + (int64_t)w.seq * p.k_stride_seq +
                           (int64_t)kv * p.k_stride_head + w.tok0 * p.k_stride_token;
   const float* lse = p.lse2 + (((int64_t)layer * p.batch + w.seq) * p.n_q_heads + (int64_t)kv * p.group) * p.n_pseudo;
-  float* out = p.scores + ((int64_t)layer * p.n_kv_heads + kv) * p.total_tokens + w.tok0;
+  const int gbase = blockIdx.y * (NRB * 32);  // first row of this wave's row group
+  // with several row groups each writes its own plane of column sums; a small kernel adds them up
+  float* plane = p.n_groups > 1 ? p.partial + (int64_t)blockIdx.y * p.n_layers * p.n_kv_heads * p.total_tokens : p.scores;
+  float* out = plane + ((int64_t)layer * p.n_kv_heads + kv) * p.total_tokens + w.tok0;
   const int nsubs = (w.nkeys + 31) / 32;
-  int issued = 0;
-  for (; issued < kWaveStages2 && issued < nsubs; ++issued)
-    sub_dma(ring + issued * kSubVec, kbase, p.k_stride_token, issued * 32, w.nkeys, lane);
+  unsigned voff[4];
+  sub_dma_lane_offsets(voff, p.k_stride_token, lane);
+#pragma unroll
+  for (int i = 0; i < kWaveStages2; ++i) sub_dma(ring + i * kSubVec, kbase, p.k_stride_token, i * 32, w.nkeys, voff);
   // table of -lse2 per row behind the ring; -inf for padding rows, which then add 0
   float* nbt = reinterpret_cast<float*>(ring + kWaveStages2 * kSubVec);
 #pragma unroll
-  for (int r = lane; r < NRB * 32; r += 64) nbt[r] = r < p.rows ? -lse[r] : -INFINITY;
+  for (int r = lane; r < NRB * 32; r += 64) nbt[r] = gbase + r < p.rows ? -lse[gbase + r] : -INFINITY;
   bf16x8 qf[NRB][8];
 #pragma unroll
-  for (int rb = 0; rb < NRB; ++rb) frag_from_q(qf[rb], p, qbase, rb * 32 + n, h);
+  for (int rb = 0; rb < NRB; ++rb) frag_from_q(qf[rb], p, qbase, gbase + rb * 32 + n, h);
   if (NRB == 8) pin_q_in_agprs<NRB>(qf);
   __syncthreads();  // one wave: orders the table writes before the reads below
   bf16x8 kf[8];
-  wait_subblocks(issued - 1);
+  wait_subblocks(kWaveStages2 - 1);
   wave_load_frags<NRB>(kf, ring, n, h);
   float unused_off[NRB], unused_acc[NRB];
 #pragma unroll
   for (int rb = 0; rb < NRB; ++rb) unused_off[rb] = 0.0f;
-  wave_walk<NRB, 2, kWaveStages2>(ring, kbase, p.k_stride_token, w.nkeys, nsubs, 0, nsubs, issued, kf, qf, p.c,
+  wave_walk<NRB, 2, kWaveStages2>(ring, kbase, p.k_stride_token, w.nkeys, 0, nsubs, kf, qf, p.c,
                                   unused_off, (unsigned)(uintptr_t)(lds_vec_ptr)(ring + kWaveStages2 * kSubVec),
-                                  unused_acc, out, lane, n, h);
+                                  unused_acc, out, voff, n, h);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
+// S = sum over row groups of their planes of column sums, in group order.
+__global__ void score_group_sum_kernel(const float* partial, float* scores, int64_t count, int n_groups) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < count; e += stride) {
+    float s = partial[e];
+    for (int g = 1; g < n_groups; ++g) s += partial[(int64_t)g * count + e];
+    scores[e] = s;
+  }
 }
 
 template <typename F>
@@ -1061,7 +1099,7 @@ int fill_params(const dapq_shape* s, const ScorePlan& plan, ScoreParams* p) {
   p->total_tokens = s->total_tokens;
   p->n_layers = s->n_layers; p->batch = s->batch; p->n_q_heads = s->n_q_heads; p->n_kv_heads = s->n_kv_heads;
   p->group = s->n_q_heads / s->n_kv_heads; p->n_pseudo = s->n_pseudo;
-  p->rows = plan.rows; p->rows_pad = plan.rows_pad; p->n_super = plan.n_super;
+  p->rows = plan.rows; p->rows_pad = plan.rows_pad; p->n_super = plan.n_super; p->n_groups = plan.n_groups;
   p->chunk_keys = plan.chunk_keys; p->max_chunks = (int32_t)plan.max_chunks;
   p->c = s->scale * 1.4426950408889634f;
   return DAPQ_OK;
@@ -1081,7 +1119,7 @@ int launch_stats(const dapq_shape* s, const ScorePlan& plan, ScoreParams p, hipS
   }
   int rc = DAPQ_OK;
   if (plan.wave_path) {
-    const dim3 grid((unsigned)plan.max_chunks, 1, (unsigned)(s->n_layers * s->n_kv_heads));
+    const dim3 grid((unsigned)plan.max_chunks, (unsigned)plan.n_groups, (unsigned)(s->n_layers * s->n_kv_heads));
 #define DAPQ_LAUNCH_W1(NRBV)                                                                        \
   do {                                                                                              \
     if ((rc = set_lds(score_wave_pass1_kernel<NRBV>, kWaveLds1)) != DAPQ_OK) return rc;              \
@@ -1114,15 +1152,23 @@ int launch_accumulate(const dapq_shape* s, const ScorePlan& plan, ScoreParams p,
   const dim3 grid((unsigned)plan.max_chunks, 1, (unsigned)(s->n_layers * s->n_kv_heads));
   int rc = DAPQ_OK;
   if (plan.wave_path) {
+    const dim3 wgrid((unsigned)plan.max_chunks, (unsigned)plan.n_groups, (unsigned)(s->n_layers * s->n_kv_heads));
 #define DAPQ_LAUNCH_W2(NRBV)                                                                        \
   do {                                                                                              \
     if ((rc = set_lds(score_wave_pass2_kernel<NRBV>, kWaveLds2)) != DAPQ_OK) return rc;              \
-    hipLaunchKernelGGL(score_wave_pass2_kernel<NRBV>, grid, dim3(64), kWaveLds2, stream, p);        \
+    hipLaunchKernelGGL(score_wave_pass2_kernel<NRBV>, wgrid, dim3(64), kWaveLds2, stream, p);       \
   } while (0)
     if (plan.row_blocks == 2) DAPQ_LAUNCH_W2(2);
     else if (plan.row_blocks == 4) DAPQ_LAUNCH_W2(4);
     else DAPQ_LAUNCH_W2(8);
 #undef DAPQ_LAUNCH_W2
+    if (plan.n_groups > 1) {
+      DAPQ_HIP_LAUNCH_CHECK("score_wave_pass2_kernel");
+      const int64_t count = (int64_t)s->n_layers * s->n_kv_heads * s->total_tokens;
+      const unsigned blocks = (unsigned)(count + 255) / 256 < 16384u ? (unsigned)((count + 255) / 256) : 16384u;
+      hipLaunchKernelGGL(score_group_sum_kernel, dim3(blocks > 0 ? blocks : 1), dim3(256), 0, stream, p.partial,
+                         p.scores, count, plan.n_groups);
+    }
   } else {
     // more than 256 rows: four row waves, the Q slab changes per super-group
     const int lds_bytes = kLdsScore + 2 * 4 * kTileKeys * (int)sizeof(float);
@@ -1166,6 +1212,7 @@ extern "C" DAPQ_API int dapq_score_stats(const dapq_shape* shape, const void* q,
   p.parts = reinterpret_cast<float2*>(ws + plan.off_parts);
   p.lse2 = lse2;
   p.scores = nullptr;
+  p.partial = nullptr;
   return launch_stats(shape, plan, p, static_cast<hipStream_t>(stream));
 }
 
@@ -1187,6 +1234,7 @@ extern "C" DAPQ_API int dapq_score_accumulate(const dapq_shape* shape, const voi
   p.k = static_cast<const uint16_t*>(k);
   p.cu_chunks = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + plan.off_cu_chunks);
   p.parts = nullptr;
+  p.partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + plan.off_partial);
   p.lse2 = const_cast<float*>(lse2);
   p.scores = scores;
   return launch_accumulate(shape, plan, p, static_cast<hipStream_t>(stream));
