@@ -70,33 +70,36 @@ int make_score_plan(const dapq_shape* s, ScorePlan* p) {
                (long long)rows64);
   p->rows = (int)rows64;
   const int64_t heads = (int64_t)s->n_layers * s->n_kv_heads;
-  p->wave_path = true;
-  p->n_groups = 1;
-  int chunk = kMaxChunkKeys;
-  if (p->wave_path) {
-    // one wave per (chunk, row group): a group is up to 256 rows, all in the wave's registers
-    p->n_groups = (p->rows + 255) / 256;
-    DAPQ_REQUIRE(p->n_groups <= 65535, DAPQ_ERR_UNSUPPORTED, "too many query rows per KV head");
-    p->row_blocks = p->rows <= 64 ? 2 : (p->rows <= 128 ? 4 : 8);
-    p->row_waves = 1;
-    p->key_waves = 1;
-    p->n_super = 1;
-    p->rows_pad = p->n_groups * p->row_blocks * 32;
-    // if the work allows, one wave per SIMD (1024 of them): every wave is launched once, loads Q
-    // once and streams for the whole kernel
-    chunk = 1 << 16;
-    while (chunk > kTileKeys && heads * p->n_groups * ((s->total_tokens + chunk - 1) / chunk) < 1024) chunk /= 2;
-  } else {
-    const int slabs = (p->rows + 63) / 64;  // 64-row slabs
-    p->row_blocks = 0;
-    p->row_waves = 4;
-    p->key_waves = 1;
-    p->n_super = (slabs + p->row_waves - 1) / p->row_waves;
-    p->rows_pad = p->n_super * p->row_waves * 64;
-    DAPQ_REQUIRE(p->n_super <= 65535, DAPQ_ERR_UNSUPPORTED, "too many query rows per KV head");
-    // Chunk of keys per workgroup: as long as possible (the Q slab is reloaded per chunk) while the
-    // launch still has >= 8 workgroups per compute unit to balance the tail.
-    while (chunk > kTileKeys && heads * ((s->total_tokens + chunk - 1) / chunk) < 2048) chunk /= 2;
+  // one wave per (chunk, row group): a group is up to 256 rows, all in the wave's registers
+  p->n_groups = (p->rows + 255) / 256;
+  p->row_blocks = p->rows <= 64 ? 2 : (p->rows <= 128 ? 4 : 8);
+  p->rows_pad = p->n_groups * p->row_blocks * 32;
+
+  // Keys per wave.  The machine runs kWaveSlots waves at a time, each for as long as its chunk; a
+  // wave pays a fixed start-up (Q fragments, ring fill) worth about kStartKeys keys.  Dense batches
+  // run in whole rounds of equal chunks: pick the chunk with the shortest rounds x (chunk +
+  // start-up).  Ragged batches (lengths unknown on the host) are dispatched as waves drain, so
+  // the cost is the work per slot plus one chunk of tail imbalance.
+  constexpr int64_t kWaveSlots = 1024, kStartKeys = 160;
+  const int64_t units_per_chunk_row = heads * p->n_groups;
+  int chunk = kMinChunkKeys;
+  int64_t best = INT64_MAX;
+  for (int c = kMaxChunkKeys; c >= kMinChunkKeys; c /= 2) {
+    int64_t cost;
+    if (s->cu_seqlens == nullptr) {
+      const int64_t L = s->total_tokens / s->batch;
+      const int64_t units = units_per_chunk_row * s->batch * ((L + c - 1) / c);
+      const int64_t rounds = (units + kWaveSlots - 1) / kWaveSlots;
+      cost = rounds * ((L < c ? L : c) + kStartKeys);
+    } else {
+      const int64_t chunks = (s->total_tokens + c - 1) / c + s->batch / 2;
+      const int64_t units = units_per_chunk_row * chunks;
+      cost = (units_per_chunk_row * s->total_tokens + units * kStartKeys) / kWaveSlots + c;
+    }
+    if (cost < best) {
+      best = cost;
+      chunk = c;
+    }
   }
   p->chunk_keys = chunk;
   if (s->cu_seqlens == nullptr) {
@@ -107,12 +110,13 @@ int make_score_plan(const dapq_shape* s, ScorePlan* p) {
   }
   if (p->max_chunks < 1) p->max_chunks = 1;
   DAPQ_REQUIRE(p->max_chunks < ((int64_t)1 << 31), DAPQ_ERR_UNSUPPORTED, "too many key chunks");
+  DAPQ_REQUIRE(p->n_groups <= 65535, DAPQ_ERR_UNSUPPORTED, "too many query rows per KV head");
 
   size_t off = 0;
   p->off_cu_chunks = off;
   off = align_up(off + sizeof(int32_t) * ((size_t)s->batch + 1), 256);
   p->off_parts = off;
-  off = align_up(off + sizeof(float) * 2 * (size_t)heads * (size_t)p->max_chunks * p->key_waves * p->rows_pad, 256);
+  off = align_up(off + sizeof(float) * 2 * (size_t)heads * (size_t)p->max_chunks * p->rows_pad, 256);
   p->off_lse2 = off;
   off = align_up(off + sizeof(float) * (size_t)s->n_layers * s->batch * s->n_q_heads * s->n_pseudo, 256);
   p->off_partial = off;

@@ -27,21 +27,17 @@ int fail(int code, const char* fmt, ...);
   } while (0)
 
 constexpr int kHeadDim = 128;
-constexpr int kTileKeys = 128;      // keys per LDS tile of the score kernels
-constexpr int kMaxChunkKeys = 2048; // most keys one workgroup of a score pass walks over
+constexpr int kMinChunkKeys = 128;      // fewest keys one wave of a score pass walks over
+constexpr int kMaxChunkKeys = 1 << 16;  // most
 
 // How the score passes split the work; a pure function of the shape so that
 // dapq_workspace_bytes() and the launchers agree.
 struct ScorePlan {
   int rows;        // R = (H_q/H_kv) * N query rows scored against every key of a KV head
-  bool wave_path;  // R <= 256: every wave holds all rows and walks its own chunk (no workgroup sharing)
-  int n_groups;    // wave path: row groups of row_blocks * 32 rows, one wave each per chunk
-  int row_blocks;  // wave path: 32-row blocks per wave (2, 4 or 8)
-  int row_waves;   // RW in {1,2,4}: waves of a workgroup that hold different 64-row slabs of Q
-  int key_waves;   // 4 / RW: waves that share a slab and split the keys of a tile
-  int n_super;     // row super-groups of RW*64 rows
-  int rows_pad;    // n_super * RW * 64
-  int chunk_keys;  // keys per workgroup (multiple of kTileKeys)
+  int n_groups;    // row groups of row_blocks * 32 rows, one wave each per chunk
+  int row_blocks;  // 32-row blocks per wave (2, 4 or 8)
+  int rows_pad;    // n_groups * row_blocks * 32
+  int chunk_keys;  // keys per wave (a power of two)
   int64_t max_chunks;  // grid size along the key axis: upper bound on sum_b ceil(L_b / chunk_keys)
   // workspace carving (byte offsets)
   size_t off_cu_chunks, off_parts, off_lse2, off_partial, total_bytes;

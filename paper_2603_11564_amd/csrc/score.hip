@@ -1,28 +1,37 @@
 // Importance scoring (Sec. 4.2, S(j) = sum_i Attention(q_i, k_j); Attention = softmax over the
 // prompt keys, App. C.1) as two streaming passes over K for gfx950.
 //
-//   pass 1  (score_pass1_kernel + score_combine_kernel): lse2[row] = log2 sum_j 2^(c * q_row.k_j)
-//   pass 2  (score_pass2_kernel):  S(j) = sum_rows 2^(c * q_row.k_j - lse2[row])
+//   pass 1  (score_wave_pass1_kernel + score_combine_kernel): lse2[row] = log2 sum_j 2^(c * q_row.k_j)
+//   pass 2  (score_wave_pass2_kernel [+ score_group_sum_kernel]): S(j) = sum_rows 2^(c * q_row.k_j - lse2[row])
 // with c = scale * log2(e).  "rows" are the R = g*N pseudo-query rows of the g query heads that
 // share one KV head.  Nothing of size N x L_p is ever stored.
 //
-// Work split.  One workgroup = 4 waves walks a chunk of keys of one (layer, sequence, KV head).
-// Keys stream through LDS in tiles of 128 rows (32 KB, double buffered, 16-byte chunks XOR-swizzled
-// so that the MFMA operand reads are bank-conflict free); each wave keeps a 64-row slab of Q in
-// registers for the whole chunk as MFMA operand fragments and runs v_mfma_f32_32x32x16_bf16 against
-// every 32-key sub-block.  RW waves hold different slabs; the other 4/RW waves split the keys.
+// Work split.  A workgroup is ONE wave.  It keeps a group of up to 256 Q rows of one KV head in
+// registers as MFMA operand fragments (eight 32-row blocks = 256 registers, pinned to the
+// accumulation half of the register file; one wave per SIMD owns the whole 512-register file) and
+// walks its own chunk of keys of one (layer, sequence, KV head).  Nothing is shared between waves:
+// no barrier anywhere, no cross-wave reduction.  Heads with more than 256 rows are split into row
+// groups (grid.y): pass 1 needs nothing more (its sums are per row), pass 2 writes one plane of
+// column sums per group and a small kernel adds the planes in group order.
+// Keys arrive through a per-wave ring of 32-key sub-blocks in LDS (buffer_load_dwordx4 ... lds, five
+// slots of 8 KB: four sub-blocks = 32 KB in flight per wave, 128 KB per compute unit; 16-byte
+// chunks XOR-swizzled so that the MFMA operand reads are bank-conflict free), and every fragment is
+// read from LDS exactly once per wave.  v_mfma_f32_32x32x16_bf16 runs on every (sub-block, row
+// block) unit:
 //   pass 1 uses D[key][query] (K as the A operand): a lane owns one query column, the reduction
 //           over keys stays inside the lane;
 //   pass 2 uses D[query][key] (Q as the A operand): a lane owns one key column, the reduction over
-//           query rows stays inside the lane, and lse2 of the lane's 16 rows sits in registers.
+//           query rows stays inside the lane, and -lse2 of the lane's 16 rows per row block sits in
+//           registers (128 of them).
 // Pass 1 does not track a running maximum: it exponentiates against a per-row reference logit taken
 // from the first sub-block (2^x has 127 binades of headroom above it) and only if a sum overflows
 // redoes the chunk with a conventional online maximum.
 //
-// The vector ALU is the busiest unit of this kernel (one FMA, one exponential, one add per logit),
-// the matrix pipe second, so the full tiles run software pipelined from a single wave: while the
-// MFMAs of one (sub-block, row block) unit execute, the lane exponentiates the logits of the unit
-// before it, across tile boundaries, with one barrier per tile.
+// With one wave per SIMD every instruction costs issue time, so the kernels are built around the
+// instruction count per MFMA ("slice"): one MFMA, and for two logits of the previous unit one FMA,
+// one exponential and one add each; the rest (transfer issue, ring wait, fragment reads, loop
+// control) is about one more instruction per slice.
+
 #include <math.h>
 
 #include "dapq_internal.h"
@@ -40,7 +49,7 @@ struct ScoreParams {
   const uint16_t* k;
   const int32_t* cu_seqlens;  // NULL = dense
   int32_t* cu_chunks;         // [batch+1] prefix of per-sequence chunk counts (ragged only)
-  float2* parts;              // [layer*Hkv][max_chunks][KW][rows_pad] (reference, sum) in the log2 domain
+  float2* parts;              // [layer*Hkv][max_chunks][rows_pad] (reference, sum) in the log2 domain
   float* lse2;                // [layer][batch][Hq][N]
   float* scores;              // [layer][Hkv][total_tokens]
   float* partial;             // [n_groups][layer][Hkv][total_tokens] per-row-group column sums (n_groups > 1)
@@ -48,14 +57,10 @@ struct ScoreParams {
   int64_t q_stride_layer, q_stride_seq, q_stride_head, q_stride_row;
   int64_t total_tokens;
   int32_t n_layers, batch, n_q_heads, n_kv_heads, group, n_pseudo;
-  int32_t rows, rows_pad, n_super, n_groups, chunk_keys, max_chunks;
+  int32_t rows, rows_pad, n_groups, chunk_keys, max_chunks;
   float c;  // scale * log2(e)
 };
 
-constexpr int kThreads = 256;
-constexpr int kTileBytes = kTileKeys * kHeadDim * 2;  // 32 KB
-constexpr int kTileVec = kTileBytes / 16;             // 16-byte chunks per tile
-constexpr int kLdsScore = 2 * kTileBytes;
 constexpr int kSubBytes = 32 * kHeadDim * 2;          // one 32-key sub-block
 
 // Which (sequence, chunk) a workgroup works on.
@@ -66,6 +71,29 @@ struct Work {
   int nkeys;     // keys in the chunk (<= chunk_keys), 0 = nothing to do
   int seq_len;
 };
+
+// The same for a wave-uniform chunk index, with the result pinned to scalar registers: everything
+// derived from it (key base pointer, buffer descriptors, trip counts) then stays scalar too.
+__device__ __forceinline__ int uniform_i32(int v) { return __builtin_amdgcn_readfirstlane(v); }
+template <typename T>
+__device__ __forceinline__ const T* uniform_ptr(const T* ptr) {
+  const unsigned long long v = (unsigned long long)(uintptr_t)ptr;
+  const unsigned lo = (unsigned)uniform_i32((int)(unsigned)(v & 0xFFFFFFFFull));
+  const unsigned hi = (unsigned)uniform_i32((int)(unsigned)(v >> 32));
+  return reinterpret_cast<const T*>((uintptr_t)(((unsigned long long)hi << 32) | lo));
+}
+__device__ __forceinline__ Work locate(const ScoreParams& p, int gchunk);
+__device__ __forceinline__ Work locate_uniform(const ScoreParams& p, int gchunk) {
+  Work w = locate(p, gchunk);
+  w.seq = uniform_i32(w.seq);
+  w.key0 = uniform_i32(w.key0);
+  w.nkeys = uniform_i32(w.nkeys);
+  w.seq_len = uniform_i32(w.seq_len);
+  const unsigned lo = (unsigned)uniform_i32((int)(unsigned)(w.tok0 & 0xFFFFFFFFll));
+  const unsigned hi = (unsigned)uniform_i32((int)(unsigned)((unsigned long long)w.tok0 >> 32));
+  w.tok0 = (int64_t)(((unsigned long long)hi << 32) | lo);
+  return w;
+}
 
 __device__ __forceinline__ Work locate(const ScoreParams& p, int gchunk) {
   Work w;
@@ -98,85 +126,12 @@ __device__ __forceinline__ Work locate(const ScoreParams& p, int gchunk) {
   return w;
 }
 
-// Coalesced 16-byte loads of one 128-key tile: thread t takes chunk (t & 15) of keys (t >> 4) + 16*i.
-// Branch-free: nkeys >= 1 and out-of-range rows are clamped to the last key of the chunk.
-__device__ __forceinline__ void tile_load(u32x4 (&st)[8], const uint16_t* kbase, int64_t stride_token,
-                                          int tile_key0, int nkeys, int tid) {
-  const int ch = tid & 15;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int key = (tid >> 4) + 16 * i;
-    int gk = tile_key0 + key;
-    gk = gk < nkeys ? gk : nkeys - 1;  // rows past the end repeat the last key; callers mask or drop them
-    st[i] = *reinterpret_cast<const u32x4*>(kbase + (int64_t)gk * stride_token + ch * 8);
-  }
-}
-
 // LDS position of 16-byte chunk `ch` of tile row `key`: rows are 256 B apart, chunks XOR-swizzled by
 // the row so that 16 consecutive rows reading the same logical chunk hit 16 different bank groups.
 __device__ __forceinline__ int lds_chunk_index(int key, int ch) { return key * 16 + (ch ^ (key & 15)); }
 
-__device__ __forceinline__ void tile_store(u32x4* buf, const u32x4 (&st)[8], int tid) {
-  const int ch = tid & 15;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int key = (tid >> 4) + 16 * i;
-    buf[lds_chunk_index(key, ch)] = st[i];
-  }
-}
-
-// The same tile moved straight from global memory into LDS (global_load_lds_dwordx4): no staging
-// registers, no LDS store instructions.  Each wave instruction fills 1 KB = 4 tile rows; the lane
-// that owns LDS slot (row, pos) fetches the logical chunk pos ^ (row & 15), which is the swizzle of
-// lds_chunk_index.  Nothing is issued for a tile that starts past the end of the chunk.  The data
-// is in LDS once the issuing wave's vmcnt has drained (tile_dma_wait) and a barrier has passed.
-__device__ __forceinline__ void tile_dma(u32x4* buf, const uint16_t* kbase, int64_t stride_token, int tile_key0,
-                                         int nkeys, int tid) {
-  if (tile_key0 >= nkeys) return;
-  const int wave = tid >> 6, lane = tid & 63;
-  const int row0 = wave * 4 + (lane >> 4);  // tile rows of this lane: row0 + 16*i
-  const int ch = (lane & 15) ^ (row0 & 15);
-  if (tile_key0 + kTileKeys <= nkeys) {
-    // full tile: one per-lane byte offset for all eight transfers, the rest is a uniform base
-    const unsigned lane_off = (unsigned)row0 * (unsigned)stride_token * 2u + (unsigned)ch * 16u;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const char* base = reinterpret_cast<const char*>(kbase + (int64_t)(tile_key0 + 16 * i) * stride_token);
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(base + lane_off),
-                                       (__attribute__((address_space(3))) void*)(buf + (i * 4 + wave) * 64), 16, 0, 0);
-    }
-  } else {
-    // partial tile: rows past the end repeat the last key; callers mask or drop them
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      int gk = tile_key0 + row0 + 16 * i;
-      gk = gk < nkeys ? gk : nkeys - 1;
-      const uint16_t* src = kbase + (int64_t)gk * stride_token + ch * 8;
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                       (__attribute__((address_space(3))) void*)(buf + (i * 4 + wave) * 64), 16, 0, 0);
-    }
-  }
-}
-
-// Waits until at most `pending` of this wave's vector memory operations are still in flight.
-template <int pending>
-__device__ __forceinline__ void tile_dma_wait() {
-  static_assert(pending == 0 || pending == 8, "only the two counts the kernels use");
-  if (pending == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-}
-
-// MFMA operand fragments of one 32-row sub-block held in LDS: fragment s of lane (n, h) is the
-// 8 channels [(2s+h)*8, +8) of row n.
-__device__ __forceinline__ void frag_from_lds(bf16x8 (&f)[8], const u32x4* buf, int sub, int n, int h) {
-#pragma unroll
-  for (int s = 0; s < 8; ++s) {
-    const u32x4 v = buf[lds_chunk_index(sub * 32 + n, 2 * s + h)];
-    f[s] = __builtin_bit_cast(bf16x8, v);
-  }
-}
-
-// The same fragments for a 32-row block of Q read straight from global memory.
+// Fragment s of lane (n, h) of an MFMA operand is the 8 channels [(2s+h)*8, +8) of row n: the same
+// for a 32-row block of Q read straight from global memory.
 __device__ __forceinline__ void frag_from_q(bf16x8 (&f)[8], const ScoreParams& p, const uint16_t* qbase, int row,
                                             int h) {
   const int rc = row < p.rows ? row : p.rows - 1;  // padding rows repeat the last row; their results are dropped
@@ -191,19 +146,6 @@ __device__ __forceinline__ float xhalf(float v) { return __shfl_xor(v, 32, 64); 
 // Row of the 32x32 MFMA result held in accumulator register v of a lane in half h.
 __device__ __forceinline__ int acc_row(int v, int h) { return 8 * (v >> 2) + 4 * h + (v & 3); }
 
-// ---------------------------------------------------------------------------------------------
-// Software-pipelined walk over the full tiles of a chunk (both passes).
-//
-// A unit is one 32-key sub-block against one 32-row block of Q: 8 MFMAs, 16 logits per lane.  A
-// slice is one MFMA of the current unit plus the exponentials of two logits of the previous unit
-// (2 FMAs, the 2 adds of the exponentials issued one slice earlier, 2 transcendentals) and, in the
-// second row block of a sub-block, one LDS fragment read for the next sub-block.  The slice order
-// is pinned with an empty asm statement after each slice that takes the slice's results and the
-// next slice's inputs as read-write operands: what produces them must come before it, what
-// consumes them after it.  It emits no instruction.
-// ---------------------------------------------------------------------------------------------
-#define DAPQ_SLICE_END(cur, prev, e0, e1, sa, sb, addr) \
-  asm volatile("" : "+v"(cur), "+v"(prev), "+v"(e0), "+v"(e1), "+v"(sa), "+v"(sb), "+v"(addr))
 
 typedef const u32x4 __attribute__((address_space(3))) * lds_vec_ptr;
 
@@ -214,302 +156,6 @@ __device__ __forceinline__ bf16x8 lds_read16(unsigned lane_addr, int const_off) 
 
 // Column sums of a tile -> S (pass 2): lane halves hold different query rows of the same key (one
 // shuffle), the RW slabs of a workgroup are added through LDS by the first 128 threads after a barrier.
-template <int RW>
-__device__ __forceinline__ void publish_columns(float* red, const float* col, int kw, int rw, int n, int h) {
-  constexpr int KW = 4 / RW, NSUB = 4 / KW;
-#pragma unroll
-  for (int j = 0; j < NSUB; ++j) {
-    const float v = col[j] + xhalf(col[j]);
-    if (h == 0) red[rw * kTileKeys + (kw + j * KW) * 32 + n] = v;
-  }
-}
-
-template <int RW>
-__device__ __forceinline__ void store_columns(const float* red, float* out, int tile_key0, int nkeys, int tid) {
-  if (tid < kTileKeys && tile_key0 + tid < nkeys) {
-    float s = red[tid];
-#pragma unroll
-    for (int r = 1; r < RW; ++r) s += red[r * kTileKeys + tid];
-    out[tile_key0 + tid] = s;
-  }
-}
-
-// Entry contract of walk_tiles: tile t0 is in buffer t0 & 1 (landed and fenced) and the transfer of
-// tile t0+1 into the other buffer has been started.  On return every transfer has landed and tile t1
-// (the partial last tile, if the chunk has one) is in buffer t1 & 1, fenced.
-//
-// State of the pipelined walk.  Plain locals of the one function that owns the loop (walk_tiles), so
-// that all of it stays in registers; the macros below are that function's body, unit by unit.
-//
-//   kf[8]   fragments of the sub-block whose MFMAs run next
-//   prev    logits of the unit whose exponentials are being taken (cur: the unit being multiplied)
-//   e0,e1   exponentials issued in the previous slice, added in the next
-//   sa,sb   running sums of the unit being added up
-//   fa[8]   per-lane LDS byte address of fragment s of the wave's first sub-block (constant)
-//   acc[]   pass 1: zsum[2] row sums; pass 2: colp[NSUB] / colc[NSUB] column sums of the previous /
-//           current tile (the last two units of a tile finish during the next one)
-template <int RW, int PASS>
-__device__ __forceinline__ void walk_tiles(u32x4* lds, const uint16_t* kbase, int64_t stride_token, int nkeys,
-                                           int t0, int t1, const bf16x8 (&qf)[2][8], float c,
-                                           const float (&off)[2][16], float (&zsum)[2], float* red, float* out,
-                                           int tid, int kw, int rw, int n, int h) {
-  constexpr int KW = 4 / RW, NSUB = 4 / KW, NUNIT = 2 * NSUB;
-  constexpr int kRed = RW * kTileKeys;
-  constexpr int LAG = NUNIT == 2 ? 2 : 1;  // pass 2: tiles by which the store to S trails (see below)
-  const unsigned lds_base = (unsigned)(uintptr_t)(lds_vec_ptr)lds;
-  unsigned fa[8];
-#pragma unroll
-  for (int s = 0; s < 8; ++s)
-    fa[s] = lds_base + (unsigned)(n * 16 + ((2 * s + h) ^ (n & 15))) * 16u + (unsigned)(kw * kSubBytes);
-  bf16x8 kf[8];
-#pragma unroll
-  for (int s = 0; s < 8; ++s) kf[s] = lds_read16(fa[s] + (t0 & 1) * kTileBytes, 0);
-  f32x16 prev;
-#pragma unroll
-  for (int v = 0; v < 16; ++v) prev[v] = -INFINITY;  // 2^(-inf) = 0: the first slices add nothing
-  float e0 = 0.0f, e1 = 0.0f, sa = 0.0f, sb = 0.0f;
-  float colp[NSUB], colc[NSUB];
-#pragma unroll
-  for (int j = 0; j < NSUB; ++j) colp[j] = colc[j] = 0.0f;
-  zsum[0] = zsum[1] = 0.0f;
-
-  for (int t = t0; t < t1; ++t) {
-    // two copies of the tile body so that the buffer offsets are instruction immediates
-#pragma unroll
-    for (int par = 0; par < 2; ++par) {
-      if ((t & 1) != par) continue;
-      const int cur_base = par * kTileBytes, nxt_base = (par ^ 1) * kTileBytes;
-#pragma unroll
-      for (int u = 0; u < NUNIT; ++u) {
-        const int j = u >> 1, rb = u & 1, rbp = rb ^ 1;
-        if (u == NUNIT - 1) {
-          // before the last unit: its fragment reads reach into the next tile, whose transfer was
-          // started a tile ago and must have landed; every wave is past its reads of this tile's
-          // buffer, so the tile after next can start to overwrite it
-          tile_dma_wait<0>();
-          __syncthreads();  // also fences the column sums published since the previous barrier
-          tile_dma(lds + (t & 1) * kTileVec, kbase, stride_token, (t + 2) * kTileKeys, nkeys, tid);
-          if (PASS == 2 && t - t0 >= LAG)
-            store_columns<RW>(red + ((t - LAG) & 1) * kRed, out, (t - LAG) * kTileKeys, nkeys, tid);
-        }
-        f32x16 cur = {0};
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-          if (PASS == 1) cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[rb][s], cur, 0, 0, 0);
-          else cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][s], kf[s], cur, 0, 0, 0);
-          if (rb == 1) {  // last use of this fragment: fetch the next sub-block's into its place
-            if (j + 1 < NSUB) kf[s] = lds_read16(fa[s], cur_base + (j + 1) * KW * kSubBytes);
-            else kf[s] = lds_read16(fa[s], nxt_base);
-          }
-          const float x0 = fmaf(prev[2 * s], c, PASS == 1 ? off[rbp][0] : off[rbp][2 * s]);
-          const float x1 = fmaf(prev[2 * s + 1], c, PASS == 1 ? off[rbp][0] : off[rbp][2 * s + 1]);
-          sa += e0;
-          sb += e1;
-          if (s == 0) {  // those were the last two logits of unit u-2: bank its sum
-            const float total = sa + sb;
-            sa = sb = 0.0f;
-            if (PASS == 1) zsum[rb] += total;                  // unit u-2 has the row block of u
-            else if (u >= 2) colc[(u - 2) >> 1] += total;
-            else colp[NSUB - 1] += total;                      // the last two units of the previous tile
-          }
-          e0 = __builtin_amdgcn_exp2f(x0);
-          e1 = __builtin_amdgcn_exp2f(x1);
-          DAPQ_SLICE_END(cur, prev, e0, e1, sa, sb, fa[(s + 1) & 7]);
-          if (PASS == 2 && u == 1 && s == 0 && t > t0)  // the previous tile's column sums are complete
-            publish_columns<RW>(red + ((t - 1) & 1) * kRed, colp, kw, rw, n, h);
-        }
-        prev = cur;
-      }
-      if (PASS == 2) {
-#pragma unroll
-        for (int j = 0; j < NSUB; ++j) {
-          colp[j] = colc[j];
-          colc[j] = 0.0f;
-        }
-      }
-    }
-  }
-
-  // drain: the exponentials of the last unit, with no MFMAs to hide behind
-#pragma unroll
-  for (int s = 0; s < 8; ++s) {
-    const float x0 = fmaf(prev[2 * s], c, PASS == 1 ? off[1][0] : off[1][2 * s]);
-    const float x1 = fmaf(prev[2 * s + 1], c, PASS == 1 ? off[1][0] : off[1][2 * s + 1]);
-    sa += e0;
-    sb += e1;
-    if (s == 0) {  // closes unit NUNIT-2 of the last tile (row block 0, last sub-block)
-      if (PASS == 1) zsum[0] += sa + sb;
-      else colp[NSUB - 1] += sa + sb;
-      sa = sb = 0.0f;
-    }
-    e0 = __builtin_amdgcn_exp2f(x0);
-    e1 = __builtin_amdgcn_exp2f(x1);
-  }
-  const float total = (sa + e0) + (sb + e1);
-  tile_dma_wait<0>();  // the transfer started before the last unit (a tile nobody reads, if any)
-  if (PASS == 1) {
-    zsum[1] += total;
-    __syncthreads();
-  } else {
-    // The column sums of tile t are published after slice 0 of unit 1 of tile t+1; the barrier that
-    // follows is the one before the last unit, so the store trails by LAG tiles (2 when a tile has
-    // only two units and that barrier comes first).  Flush what is left.
-    colp[NSUB - 1] += total;
-    publish_columns<RW>(red + ((t1 - 1) & 1) * kRed, colp, kw, rw, n, h);
-    __syncthreads();
-    if (LAG == 2 && t1 - t0 >= 2)
-      store_columns<RW>(red + ((t1 - 2) & 1) * kRed, out, (t1 - 2) * kTileKeys, nkeys, tid);
-    store_columns<RW>(red + ((t1 - 1) & 1) * kRed, out, (t1 - 1) * kTileKeys, nkeys, tid);
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Pass 1
-// ---------------------------------------------------------------------------------------------
-// One tile the plain way: handles partial tiles (keys >= nkeys are masked out), fixes the reference
-// logit on the wave's first sub-block (first), or tracks a running maximum (SAFE).
-template <int RW, bool SAFE>
-__device__ __forceinline__ void pass1_tile_simple(const u32x4* buf, const bf16x8 (&qf)[2][8], float c,
-                                                  float (&ref)[2], float (&z)[2], int tile_key0, int nkeys, bool& first,
-                                                  int kw, int n, int h) {
-  constexpr int KW = 4 / RW;
-  const bool full = tile_key0 + kTileKeys <= nkeys;
-#pragma unroll 1
-  for (int sub = kw; sub < 4; sub += KW) {
-    const int sub_key0 = tile_key0 + sub * 32;
-    if (sub_key0 >= nkeys) break;
-    bf16x8 kf[8];
-    frag_from_lds(kf, buf, sub, n, h);
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-      f32x16 acc = {0};
-#pragma unroll
-      for (int s = 0; s < 8; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[rb][s], acc, 0, 0, 0);
-      if (!full) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v)
-          if (sub_key0 + acc_row(v, h) >= nkeys) acc[v] = -INFINITY;
-      }
-      if (SAFE || first) {
-        float m = acc[0];
-#pragma unroll
-        for (int v = 1; v < 16; ++v) m = fmaxf(m, acc[v]);
-        m = fmaxf(m, xhalf(m)) * c;
-        if (SAFE) {
-          const float mnew = fmaxf(ref[rb], m);
-          z[rb] *= __builtin_amdgcn_exp2f(ref[rb] - mnew);
-          ref[rb] = mnew;
-        } else {
-          ref[rb] = m;
-        }
-      }
-      const float nref = -ref[rb];
-      float sum = 0.0f;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) sum += __builtin_amdgcn_exp2f(fmaf(acc[v], c, nref));
-      z[rb] += sum;
-    }
-    first = false;
-  }
-}
-
-// The plain walk: every tile through pass1_tile_simple (the overflow redo, and chunks with fewer
-// than two full tiles).
-template <int RW, bool SAFE>
-__device__ __forceinline__ void pass1_chunk_simple(const ScoreParams& p, const Work& w, const uint16_t* kbase,
-                                                   const bf16x8 (&qf)[2][8], u32x4* lds, float (&ref)[2], float (&z)[2]) {
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, h = lane >> 5;
-  const int kw = wave / RW;
-  const int ntiles = (w.nkeys + kTileKeys - 1) / kTileKeys;
-  bool first = !SAFE;
-  ref[0] = ref[1] = -INFINITY;
-  z[0] = z[1] = 0.0f;
-  u32x4 st[8];
-  tile_load(st, kbase, p.k_stride_token, 0, w.nkeys, tid);
-  for (int t = 0; t < ntiles; ++t) {
-    u32x4* buf = lds + (t & 1) * kTileVec;
-    tile_store(buf, st, tid);
-    __syncthreads();
-    tile_load(st, kbase, p.k_stride_token, (t + 1) * kTileKeys, w.nkeys, tid);
-    pass1_tile_simple<RW, SAFE>(buf, qf, p.c, ref, z, t * kTileKeys, w.nkeys, first, kw, n, h);
-  }
-  __syncthreads();  // every wave is done with the last tile before the buffers are reused
-}
-
-// The fast walk: tile 0 the plain way (it fixes the reference logits), full tiles 1.. pipelined,
-// a partial last tile the plain way again.  Needs at least two full tiles.
-template <int RW>
-__device__ __forceinline__ void pass1_chunk_pipelined(const ScoreParams& p, const Work& w, const uint16_t* kbase,
-                                                      const bf16x8 (&qf)[2][8], u32x4* lds, float (&ref)[2],
-                                                      float (&z)[2]) {
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, h = lane >> 5;
-  const int kw = wave / RW;
-  const int nfull = w.nkeys / kTileKeys;
-  const bool tail = (w.nkeys % kTileKeys) != 0;
-  bool first = true;
-  ref[0] = ref[1] = -INFINITY;
-  z[0] = z[1] = 0.0f;
-
-  tile_dma(lds, kbase, p.k_stride_token, 0, w.nkeys, tid);
-  tile_dma(lds + kTileVec, kbase, p.k_stride_token, kTileKeys, w.nkeys, tid);
-  tile_dma_wait<8>();  // tile 0 has landed, tile 1 may still be in flight
-  __syncthreads();
-  pass1_tile_simple<RW, false>(lds, qf, p.c, ref, z, 0, w.nkeys, first, kw, n, h);
-  tile_dma_wait<0>();
-  __syncthreads();  // tile 1 is in; every wave is done with tile 0's buffer
-  tile_dma(lds, kbase, p.k_stride_token, 2 * kTileKeys, w.nkeys, tid);
-
-  float off[2][16];
-  off[0][0] = -ref[0];
-  off[1][0] = -ref[1];
-  float zsum[2];
-  walk_tiles<RW, 1>(lds, kbase, p.k_stride_token, w.nkeys, 1, nfull, qf, p.c, off, zsum, nullptr, nullptr, tid, kw,
-                    0, n, h);
-  z[0] += zsum[0];
-  z[1] += zsum[1];
-  if (tail)  // already stored and fenced before the last unit of the last full tile
-    pass1_tile_simple<RW, false>(lds + (nfull & 1) * kTileVec, qf, p.c, ref, z, nfull * kTileKeys, w.nkeys, first, kw,
-                                 n, h);
-  __syncthreads();
-}
-
-template <int RW>
-__global__ __launch_bounds__(kThreads, 2) void score_pass1_kernel(ScoreParams p) {
-  extern __shared__ u32x4 lds[];
-  constexpr int KW = 4 / RW;
-  const Work w = locate(p, blockIdx.x);
-  if (w.nkeys == 0) return;
-  const int layer = blockIdx.z / p.n_kv_heads, kv = blockIdx.z - layer * p.n_kv_heads;
-  const int sg = blockIdx.y;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, h = lane >> 5;
-  const int rw = wave % RW, kw = wave / RW;
-  const int row0 = (sg * RW + rw) * 64;
-
-  const uint16_t* qbase = p.q + (int64_t)layer * p.q_stride_layer + (int64_t)w.seq * p.q_stride_seq +
-                          (int64_t)kv * p.group * p.q_stride_head;
-  const uint16_t* kbase = p.k + (int64_t)layer * p.k_stride_layer + (int64_t)w.seq * p.k_stride_seq +
-                          (int64_t)kv * p.k_stride_head + w.tok0 * p.k_stride_token;
-  bf16x8 qf[2][8];
-  frag_from_q(qf[0], p, qbase, row0 + n, h);
-  frag_from_q(qf[1], p, qbase, row0 + 32 + n, h);
-
-  float ref[2], z[2];
-  if (w.nkeys >= 2 * kTileKeys) pass1_chunk_pipelined<RW>(p, w, kbase, qf, lds, ref, z);
-  else pass1_chunk_simple<RW, false>(p, w, kbase, qf, lds, ref, z);
-  // a sum that is not finite means a logit sat more than ~127 binades above the reference
-  const bool bad = !(z[0] < INFINITY) || !(z[1] < INFINITY);
-  if (__syncthreads_or(bad ? 1 : 0)) pass1_chunk_simple<RW, true>(p, w, kbase, qf, lds, ref, z);
-
-  // the two lane halves hold different keys of the same query
-  const float z0 = z[0] + xhalf(z[0]);
-  const float z1 = z[1] + xhalf(z[1]);
-  if (h == 0) {
-    float2* out = p.parts + (((int64_t)blockIdx.z * p.max_chunks + blockIdx.x) * KW + kw) * p.rows_pad + row0;
-    out[n] = make_float2(ref[0], z0);
-    out[32 + n] = make_float2(ref[1], z1);
-  }
-}
-
 // Per-sequence prefix of chunk counts for ragged batches (tiny, one block).
 __global__ void score_chunk_prefix_kernel(const int32_t* cu_seqlens, int32_t* cu_chunks, int batch, int chunk_keys) {
   if (threadIdx.x == 0 && blockIdx.x == 0) {
@@ -524,7 +170,7 @@ __global__ void score_chunk_prefix_kernel(const int32_t* cu_seqlens, int32_t* cu
 }
 
 // Merge the per-chunk (reference, sum) pairs of a row: lse2 = log2 sum_c z_c 2^(ref_c).
-__global__ void score_combine_kernel(ScoreParams p, int key_waves) {
+__global__ void score_combine_kernel(ScoreParams p) {
   const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t total = (int64_t)p.n_layers * p.batch * p.n_q_heads * p.n_pseudo;
   if (gid >= total) return;
@@ -544,14 +190,14 @@ __global__ void score_combine_kernel(ScoreParams p, int key_waves) {
     c0 = p.cu_chunks[b];
     c1 = p.cu_chunks[b + 1];
   }
-  const float2* src = p.parts + ((int64_t)(layer * p.n_kv_heads + kv) * p.max_chunks) * key_waves * p.rows_pad + row;
+  const float2* src = p.parts + ((int64_t)(layer * p.n_kv_heads + kv) * p.max_chunks) * p.rows_pad + row;
   float m = -INFINITY;
-  for (int64_t e = (int64_t)c0 * key_waves; e < (int64_t)c1 * key_waves; ++e) {
+  for (int64_t e = c0; e < c1; ++e) {
     const float2 v = src[e * p.rows_pad];
     if (v.y > 0.0f) m = fmaxf(m, v.x + log2f(v.y));
   }
   float s = 0.0f;
-  for (int64_t e = (int64_t)c0 * key_waves; e < (int64_t)c1 * key_waves; ++e) {
+  for (int64_t e = c0; e < c1; ++e) {
     const float2 v = src[e * p.rows_pad];
     if (v.y > 0.0f) s += exp2f(v.x + log2f(v.y) - m);
   }
@@ -559,138 +205,13 @@ __global__ void score_combine_kernel(ScoreParams p, int key_waves) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Pass 2
-// ---------------------------------------------------------------------------------------------
-// The plain way, for partial tiles and when the Q slab changes per super-group.
-template <int RW>
-__device__ __forceinline__ void pass2_tile_simple(const u32x4* buf, const bf16x8 (&qf)[2][8], float c,
-                                                  const float (&nb)[2][16], float (&col)[4], int tile_key0, int nkeys,
-                                                  int kw, int n, int h) {
-  constexpr int KW = 4 / RW, NSUB = 4 / KW;
-#pragma unroll
-  for (int j = 0; j < NSUB; ++j) {
-    const int sub = kw + j * KW;
-    if (tile_key0 + sub * 32 >= nkeys) continue;
-    bf16x8 kf[8];
-    frag_from_lds(kf, buf, sub, n, h);
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-      f32x16 acc = {0};
-#pragma unroll
-      for (int s = 0; s < 8; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][s], kf[s], acc, 0, 0, 0);
-      float sum = 0.0f;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) sum += __builtin_amdgcn_exp2f(fmaf(acc[v], c, nb[rb][v]));
-      col[j] += sum;
-    }
-  }
-}
-
-template <int RW, bool MULTI>
-__global__ __launch_bounds__(kThreads, 2) void score_pass2_kernel(ScoreParams p) {
-  extern __shared__ u32x4 lds[];
-  float* red = reinterpret_cast<float*>(lds + kLdsScore / 16);  // [2][RW][128] partial column sums
-  constexpr int kRed = RW * kTileKeys;
-  const Work w = locate(p, blockIdx.x);
-  if (w.nkeys == 0) return;
-  const int layer = blockIdx.z / p.n_kv_heads, kv = blockIdx.z - layer * p.n_kv_heads;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, h = lane >> 5;
-  const int rw = wave % RW, kw = wave / RW;
-  const float c = p.c;
-
-  const uint16_t* qbase = p.q + (int64_t)layer * p.q_stride_layer + (int64_t)w.seq * p.q_stride_seq +
-                          (int64_t)kv * p.group * p.q_stride_head;
-  const uint16_t* kbase = p.k + (int64_t)layer * p.k_stride_layer + (int64_t)w.seq * p.k_stride_seq +
-                          (int64_t)kv * p.k_stride_head + w.tok0 * p.k_stride_token;
-  const float* lse = p.lse2 + (((int64_t)layer * p.batch + w.seq) * p.n_q_heads + (int64_t)kv * p.group) * p.n_pseudo;
-  float* out = p.scores + ((int64_t)layer * p.n_kv_heads + kv) * p.total_tokens + w.tok0;
-
-  // Q slab and the normalisers of its rows; reloaded per super-group when R > RW*64 (MULTI).
-  bf16x8 qf[2][8];
-  float nb[2][16];  // -lse2 of the lane's accumulator rows; -inf for padding rows, which then add 0
-  auto load_slab = [&](int sg) {
-    const int row0 = (sg * RW + rw) * 64;
-    frag_from_q(qf[0], p, qbase, row0 + n, h);
-    frag_from_q(qf[1], p, qbase, row0 + 32 + n, h);
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = row0 + rb * 32 + acc_row(v, h);
-        const int rc = row < p.rows ? row : p.rows - 1;
-        const float l = lse[rc];  // rows are laid out head-major: row = head*N + i
-        nb[rb][v] = row < p.rows ? -l : -INFINITY;
-      }
-  };
-  if (!MULTI) load_slab(0);
-
-  const int ntiles = (w.nkeys + kTileKeys - 1) / kTileKeys;
-  const int nfull = w.nkeys / kTileKeys;
-
-  if (!MULTI && nfull >= 1) {
-    // ---- pipelined: all full tiles in one stream, the partial last tile (if any) the plain way
-    tile_dma(lds, kbase, p.k_stride_token, 0, w.nkeys, tid);
-    tile_dma(lds + kTileVec, kbase, p.k_stride_token, kTileKeys, w.nkeys, tid);
-    if (kTileKeys < w.nkeys) tile_dma_wait<8>();  // tile 0 has landed, tile 1 may still be in flight
-    else tile_dma_wait<0>();
-    __syncthreads();
-    float zsum[2];
-    walk_tiles<RW, 2>(lds, kbase, p.k_stride_token, w.nkeys, 0, nfull, qf, c, nb, zsum, red, out, tid, kw, rw, n, h);
-    if (nfull < ntiles) {  // the partial tile is in its buffer already (stored and fenced in the walk)
-      float col[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-      pass2_tile_simple<RW>(lds + (nfull & 1) * kTileVec, qf, c, nb, col, nfull * kTileKeys, w.nkeys, kw, n, h);
-      __syncthreads();  // the stores above have read red before it is overwritten
-      publish_columns<RW>(red + (nfull & 1) * kRed, col, kw, rw, n, h);
-      __syncthreads();
-      store_columns<RW>(red + (nfull & 1) * kRed, out, nfull * kTileKeys, w.nkeys, tid);
-    }
-    return;
-  }
-
-  // ---- plain: one tile at a time, staged through registers
-  u32x4 st[8];
-  tile_load(st, kbase, p.k_stride_token, 0, w.nkeys, tid);
-  for (int t = 0; t < ntiles; ++t) {
-    u32x4* buf = lds + (t & 1) * kTileVec;
-    tile_store(buf, st, tid);
-    __syncthreads();
-    tile_load(st, kbase, p.k_stride_token, (t + 1) * kTileKeys, w.nkeys, tid);
-    const int tile_key0 = t * kTileKeys;
-    float col[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-    if (MULTI) {
-      for (int sg = 0; sg < p.n_super; ++sg) {
-        load_slab(sg);
-        pass2_tile_simple<RW>(buf, qf, c, nb, col, tile_key0, w.nkeys, kw, n, h);
-      }
-    } else {
-      pass2_tile_simple<RW>(buf, qf, c, nb, col, tile_key0, w.nkeys, kw, n, h);
-    }
-    publish_columns<RW>(red + (t & 1) * kRed, col, kw, rw, n, h);
-    __syncthreads();
-    store_columns<RW>(red + (t & 1) * kRed, out, tile_key0, w.nkeys, tid);
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Wave-private kernels (R <= 256 rows per KV head): one wave = all query rows x its own key stream.
-//
-// A workgroup is a single wave that keeps ALL the Q rows of the KV head in registers (up to eight
-// 32-row blocks = 256 registers of MFMA operands; the launch bound of one wave per SIMD gives it the
-// whole 512-register file) and walks its own chunk of keys.  Nothing is shared between waves, so
-// there is no barrier anywhere and no cross-wave reduction: in pass 2 the lane that owns a key
-// column sees every query row.  Keys arrive through a per-wave ring of 32-key sub-blocks in LDS
-// (global_load_lds_dwordx4, five slots of 8 KB in pass 1: four sub-blocks = 32 KB in flight per
-// wave, 128 KB per compute unit), and each fragment is read from LDS exactly once per wave.
-//
-// The instruction stream is the software pipeline described above, per (sub-block, row block)
-// unit, with the exponentials trailing the MFMAs by one unit plus one slice so that the first
-// result of a unit is not touched until a slice after its last MFMA issued.
+// The score kernels: one wave = a group of query rows x its own key stream.
 // ---------------------------------------------------------------------------------------------
 constexpr int kWaveStages1 = 5;           // pass 1: ring slots (40 KB per wave, 160 KB per compute unit)
-constexpr int kWaveStages2 = 4;           // pass 2: one slot less, a 1 KB table of row offsets instead
+constexpr int kWaveStages2 = 5;           // pass 2: the same
 constexpr int kSubVec = kSubBytes / 16;   // 512 16-byte chunks per sub-block
 constexpr int kWaveLds1 = kWaveStages1 * kSubBytes;
-constexpr int kWaveLds2 = kWaveStages2 * kSubBytes + 256 * (int)sizeof(float);
+constexpr int kWaveLds2 = kWaveStages2 * kSubBytes;
 
 // Per-lane byte offsets of the four distinct 16-byte chunks a lane fetches in sub_dma: transfer i
 // moves key rows 4i..4i+3, lane (row0 = lane / 16, pos = lane % 16) fills LDS position pos of row
@@ -745,10 +266,14 @@ __device__ __forceinline__ void wait_ring_full() {
 // The instruction order is pinned with empty asm statements that take values as read-write operands:
 // what produces an operand must come before the statement, what uses it after.  One sits right
 // after the MFMA of a slice (it "redefines" the K fragment the MFMA read and the two pending
-// exponents, so the MFMA leads the slice and the vector work follows), one at the end of the slice.
+// exponents, so the MFMA leads the slice and the vector work follows), one at the end of the slice
+// (it also names the K fragment of the next MFMA, which therefore cannot start early).
 // Neither names a transcendental's result or the accumulator in flight: both would cost wait states.
 #define DAPQ_WAVE_SLICE_MID(kfrag, x0, x1) asm volatile("" : "+v"(kfrag), "+v"(x0), "+v"(x1))
-#define DAPQ_WAVE_SLICE_END(prev, x0, x1, t0, t1, addr) \
+#define DAPQ_WAVE_SLICE_END(prev, x0, x1, t0, t1, addr, knext) \
+  asm volatile("" : "+v"(prev), "+v"(x0), "+v"(x1), "+v"(t0), "+v"(t1), "+v"(addr), "+v"(knext))
+// pass 1 keeps its cadence without naming the next K fragment, and measures 2-3% faster that way
+#define DAPQ_WAVE_SLICE_END1(prev, x0, x1, t0, t1, addr) \
   asm volatile("" : "+v"(prev), "+v"(x0), "+v"(x1), "+v"(t0), "+v"(t1), "+v"(addr))
 
 // One step of the four-stage vector pipeline over pairs of logits: the exponentials started two
@@ -780,33 +305,27 @@ __device__ __forceinline__ void wait_ring_full() {
 // once its fragments are in registers, and waits for sub-block sub+1 before its last unit; as every
 // sub-block is 8 operations, existing or not, that wait is a fixed count.
 // A unit is one sub-block against one 32-row block of Q: 8 MFMAs, one per slice.  While the MFMAs
-// of a unit issue, the 16 logits per lane of the unit before it enter the vector pipeline in 8
-// steps: none in slice 0 (the transfer issue, the ring wait and the loop bookkeeping sit there, and
-// the first logits are then more than a slice old), one in each of slices 1..6, two in slice 7.
-// The sum a step adds to belongs to the pair three steps back: steps 0..2 of a unit still feed the
-// unit two back.
+// of a unit issue, the 16 logits per lane of the unit before it enter the vector pipeline, one pair
+// per slice (the MFMA leads its slice, so the last MFMA of a unit is a full slice old when its
+// first result is read).  The sum a step adds to belongs to the pair three steps back: steps 0..2
+// of a unit still feed the unit two back.
 // PASS 1: off1[rb] = -(reference logit * c) of row block rb; acc[rb] receives the row sums.
-// PASS 2: the LDS table at byte address nbt holds -lse2 of every row (-inf for padding rows); the
-//         16 values a lane needs for a row block (its accumulator rows) are fetched one unit ahead.
-//         S of every key goes to out.
+// PASS 2: off2[rb][v] = -lse2 of the row that accumulator register v of this lane holds in row
+//         block rb (-inf for padding rows, which then add 0).  S of every key goes to out.
 // NST = slots of the sub-block ring.
 template <int NRB, int PASS, int NST>
 __device__ __forceinline__ void wave_walk(u32x4* ring, const uint16_t* kbase, int64_t stride_token, int nkeys,
                                           int sb0, int sb1, bf16x8 (&kf)[8], const bf16x8 (&qf)[NRB][8], float c,
-                                          const float (&off1)[NRB], unsigned nbt, float (&acc)[NRB], float* out,
-                                          const unsigned (&voff)[4], int n, int h) {
+                                          const float (&off1)[NRB], const float (&off2)[PASS == 2 ? NRB : 1][16],
+                                          float (&acc)[NRB], float* out, const unsigned (&voff)[4], int n, int h) {
   const unsigned ring_base = (unsigned)(uintptr_t)(lds_vec_ptr)ring;
   unsigned fa[8];
 #pragma unroll
   for (int s = 0; s < 8; ++s) fa[s] = ring_base + (unsigned)(n * 16 + ((2 * s + h) ^ (n & 15))) * 16u;
-  const unsigned nba = nbt + (unsigned)h * 16u;  // pass 2: this lane's first table entry (row 4h)
   f32x16 prev;
 #pragma unroll
   for (int v = 0; v < 16; ++v) prev[v] = -INFINITY;  // 2^(-inf) = 0: the first steps add nothing
   float x0 = -INFINITY, x1 = -INFINITY, ea0 = 0.0f, ea1 = 0.0f, eb0 = 0.0f, eb1 = 0.0f, sa = 0.0f, sb = 0.0f;
-  f32x4 oc[4], on[4];  // pass 2: offsets of prev's rows / of cur's rows
-#pragma unroll
-  for (int b = 0; b < 4; ++b) oc[b] = on[b] = (f32x4){0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
   for (int rb = 0; rb < NRB; ++rb) acc[rb] = 0.0f;
 
@@ -834,43 +353,26 @@ __device__ __forceinline__ void wave_walk(u32x4* ring, const uint16_t* kbase, in
         DAPQ_WAVE_SLICE_MID(kf[s], x0, x1);
         if (rb == kLast) kf[s] = lds_read16(fa[s] + next_slot, 0);  // last use: fetch the next sub-block's
         if (PASS == 2) {
-          if (s >= 1 && s <= 4)  // offsets of this unit's rows, needed from the next unit on
-            on[s - 1] = *(const f32x4 __attribute__((address_space(3)))*)(uintptr_t)(nba + (rb * 32 + 8 * (s - 1)) * 4);
-          if (s == 7) {
-            DAPQ_VALU_STEP_K(6, prev[12], prev[13], oc[3][0], oc[3][1], sa, sb);
-            DAPQ_VALU_STEP_K(7, prev[14], prev[15], oc[3][2], oc[3][3], sa, sb);
-          } else if (s >= 1) {
-            DAPQ_VALU_STEP_K(s - 1, prev[2 * s - 2], prev[2 * s - 1], oc[(2 * s - 2) >> 2][(2 * s - 2) & 3],
-                             oc[(2 * s - 1) >> 2][(2 * s - 1) & 3], sa, sb);
-            if (s == 3 && rb == 1) {
-              // the adds above took in the last logits of the previous sub-block: its column sums are complete
-              if (sub > sb0) {
-                const float total = sa + sb;
-                const float both = total + xhalf(total);
-                const int key = (sub - 1) * 32 + n;
-                if (h == 0 && key < nkeys) out[key] = both;
-              }
-              sa = sb = 0.0f;
+          DAPQ_VALU_STEP_K(s, prev[2 * s], prev[2 * s + 1], off2[PASS == 2 ? rb1 : 0][2 * s],
+                           off2[PASS == 2 ? rb1 : 0][2 * s + 1], sa, sb);
+          if (s == 2 && rb == 1) {
+            // the adds above took in the last logits of the previous sub-block: its column sums are complete
+            if (sub > sb0) {
+              const float total = sa + sb;
+              const float both = total + xhalf(total);
+              const int key = (sub - 1) * 32 + n;
+              if (h == 0 && key < nkeys) out[key] = both;
             }
+            sa = sb = 0.0f;
           }
-          DAPQ_WAVE_SLICE_END(prev, x0, x1, sa, sb, fa[(s + 1) & 7]);
+          DAPQ_WAVE_SLICE_END(prev, x0, x1, sa, sb, fa[(s + 1) & 7], kf[(s + 1) & 7]);
         } else {
-          if (s == 7) {
-            DAPQ_VALU_STEP_K(6, prev[12], prev[13], off1[rb1], off1[rb1], acc[rb1], acc[rb1]);
-            DAPQ_VALU_STEP_K(7, prev[14], prev[15], off1[rb1], off1[rb1], acc[rb1], acc[rb1]);
-          } else if (s >= 1 && s <= 3) {
-            DAPQ_VALU_STEP_K(s - 1, prev[2 * s - 2], prev[2 * s - 1], off1[rb1], off1[rb1], acc[rb2], acc[rb2]);
-          } else if (s >= 4) {
-            DAPQ_VALU_STEP_K(s - 1, prev[2 * s - 2], prev[2 * s - 1], off1[rb1], off1[rb1], acc[rb1], acc[rb1]);
-          }
-          DAPQ_WAVE_SLICE_END(prev, x0, x1, acc[rb1], acc[rb2], fa[(s + 1) & 7]);
+          if (s < 3) DAPQ_VALU_STEP_K(s, prev[2 * s], prev[2 * s + 1], off1[rb1], off1[rb1], acc[rb2], acc[rb2]);
+          else DAPQ_VALU_STEP_K(s, prev[2 * s], prev[2 * s + 1], off1[rb1], off1[rb1], acc[rb1], acc[rb1]);
+          DAPQ_WAVE_SLICE_END1(prev, x0, x1, acc[rb1], acc[rb2], fa[(s + 1) & 7]);
         }
       }
       prev = cur;
-      if (PASS == 2) {
-#pragma unroll
-        for (int b = 0; b < 4; ++b) oc[b] = on[b];
-      }
     }
   }
 
@@ -884,7 +386,7 @@ __device__ __forceinline__ void wave_walk(u32x4* ring, const uint16_t* kbase, in
         if (k < 3) DAPQ_VALU_STEP_K(k, a0, a1, off1[rbl], off1[rbl], acc[rbl1], acc[rbl1]);
         else DAPQ_VALU_STEP_K(k, a0, a1, off1[rbl], off1[rbl], acc[rbl], acc[rbl]);
       } else {
-        DAPQ_VALU_STEP_K(k, a0, a1, oc[((2 * k) & 15) >> 2][(2 * k) & 3], oc[((2 * k + 1) & 15) >> 2][(2 * k + 1) & 3], sa,
+        DAPQ_VALU_STEP_K(k, a0, a1, off2[PASS == 2 ? rbl : 0][(2 * k) & 15], off2[PASS == 2 ? rbl : 0][(2 * k + 1) & 15], sa,
                          sb);
       }
     }
@@ -953,14 +455,15 @@ __device__ __forceinline__ void wave_load_frags(bf16x8 (&kf)[8], const u32x4* sl
 template <int NRB>
 __global__ __launch_bounds__(64, 1) void score_wave_pass1_kernel(ScoreParams p) {
   extern __shared__ u32x4 ring[];
-  const Work w = locate(p, blockIdx.x);
+  const Work w = locate_uniform(p, blockIdx.x);
   if (w.nkeys == 0) return;
-  const int layer = blockIdx.z / p.n_kv_heads, kv = blockIdx.z - layer * p.n_kv_heads;
+  // (the division runs on the vector ALU: bring the quotient back to a scalar register)
+  const int layer = uniform_i32(blockIdx.z / p.n_kv_heads), kv = blockIdx.z - layer * p.n_kv_heads;
   const int lane = threadIdx.x, n = lane & 31, h = lane >> 5;
   const uint16_t* qbase = p.q + (int64_t)layer * p.q_stride_layer + (int64_t)w.seq * p.q_stride_seq +
                           (int64_t)kv * p.group * p.q_stride_head;
-  const uint16_t* kbase = p.k + (int64_t)layer * p.k_stride_layer + (int64_t)w.seq * p.k_stride_seq +
-                          (int64_t)kv * p.k_stride_head + w.tok0 * p.k_stride_token;
+  const uint16_t* kbase = uniform_ptr(p.k + (int64_t)layer * p.k_stride_layer + (int64_t)w.seq * p.k_stride_seq +
+                                      (int64_t)kv * p.k_stride_head + w.tok0 * p.k_stride_token);
   const int gbase = blockIdx.y * (NRB * 32);  // first row of this wave's row group
   const int nsubs = (w.nkeys + 31) / 32, nfull = w.nkeys / 32;
   unsigned voff[4];
@@ -992,8 +495,9 @@ __global__ __launch_bounds__(64, 1) void score_wave_pass1_kernel(ScoreParams p) 
       float off[NRB], zs[NRB];
 #pragma unroll
       for (int rb = 0; rb < NRB; ++rb) off[rb] = -ref[rb];
-      wave_walk<NRB, 1, kWaveStages1>(ring, kbase, p.k_stride_token, w.nkeys, 1, nfull, kf, qf, p.c, off, 0u, zs, nullptr,
-                                      voff, n, h);
+      const float no_off2[1][16] = {};
+      wave_walk<NRB, 1, kWaveStages1>(ring, kbase, p.k_stride_token, w.nkeys, 1, nfull, kf, qf, p.c, off, no_off2, zs,
+                                      nullptr, voff, n, h);
 #pragma unroll
       for (int rb = 0; rb < NRB; ++rb) z[rb] += zs[rb];
     }
@@ -1033,14 +537,15 @@ __global__ __launch_bounds__(64, 1) void score_wave_pass1_kernel(ScoreParams p) 
 template <int NRB>
 __global__ __launch_bounds__(64, 1) void score_wave_pass2_kernel(ScoreParams p) {
   extern __shared__ u32x4 ring[];
-  const Work w = locate(p, blockIdx.x);
+  const Work w = locate_uniform(p, blockIdx.x);
   if (w.nkeys == 0) return;
-  const int layer = blockIdx.z / p.n_kv_heads, kv = blockIdx.z - layer * p.n_kv_heads;
+  // (the division runs on the vector ALU: bring the quotient back to a scalar register)
+  const int layer = uniform_i32(blockIdx.z / p.n_kv_heads), kv = blockIdx.z - layer * p.n_kv_heads;
   const int lane = threadIdx.x, n = lane & 31, h = lane >> 5;
   const uint16_t* qbase = p.q + (int64_t)layer * p.q_stride_layer + (int64_t)w.seq * p.q_stride_seq +
                           (int64_t)kv * p.group * p.q_stride_head;
-  const uint16_t* kbase = p.k + (int64_t)layer * p.k_stride_layer + (int64_t)w.seq * p.k_stride_seq +
-                          (int64_t)kv * p.k_stride_head + w.tok0 * p.k_stride_token;
+  const uint16_t* kbase = uniform_ptr(p.k + (int64_t)layer * p.k_stride_layer + (int64_t)w.seq * p.k_stride_seq +
+                                      (int64_t)kv * p.k_stride_head + w.tok0 * p.k_stride_token);
   const float* lse = p.lse2 + (((int64_t)layer * p.batch + w.seq) * p.n_q_heads + (int64_t)kv * p.group) * p.n_pseudo;
   const int gbase = blockIdx.y * (NRB * 32);  // first row of this wave's row group
   // with several row groups each writes its own plane of column sums; a small kernel adds them up
@@ -1051,23 +556,26 @@ __global__ __launch_bounds__(64, 1) void score_wave_pass2_kernel(ScoreParams p) 
   sub_dma_lane_offsets(voff, p.k_stride_token, lane);
 #pragma unroll
   for (int i = 0; i < kWaveStages2; ++i) sub_dma(ring + i * kSubVec, kbase, p.k_stride_token, i * 32, w.nkeys, voff);
-  // table of -lse2 per row behind the ring; -inf for padding rows, which then add 0
-  float* nbt = reinterpret_cast<float*>(ring + kWaveStages2 * kSubVec);
-#pragma unroll
-  for (int r = lane; r < NRB * 32; r += 64) nbt[r] = gbase + r < p.rows ? -lse[gbase + r] : -INFINITY;
   bf16x8 qf[NRB][8];
 #pragma unroll
   for (int rb = 0; rb < NRB; ++rb) frag_from_q(qf[rb], p, qbase, gbase + rb * 32 + n, h);
   if (NRB == 8) pin_q_in_agprs<NRB>(qf);
-  __syncthreads();  // one wave: orders the table writes before the reads below
+  // -lse2 of the rows this lane's accumulator registers hold; -inf for padding rows, which then add 0
+  float off2[NRB][16];
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int row = gbase + rb * 32 + acc_row(v, h);
+      off2[rb][v] = row < p.rows ? -lse[row] : -INFINITY;
+    }
   bf16x8 kf[8];
   wait_subblocks(kWaveStages2 - 1);
   wave_load_frags<NRB>(kf, ring, n, h);
   float unused_off[NRB], unused_acc[NRB];
 #pragma unroll
   for (int rb = 0; rb < NRB; ++rb) unused_off[rb] = 0.0f;
-  wave_walk<NRB, 2, kWaveStages2>(ring, kbase, p.k_stride_token, w.nkeys, 0, nsubs, kf, qf, p.c,
-                                  unused_off, (unsigned)(uintptr_t)(lds_vec_ptr)(ring + kWaveStages2 * kSubVec),
+  wave_walk<NRB, 2, kWaveStages2>(ring, kbase, p.k_stride_token, w.nkeys, 0, nsubs, kf, qf, p.c, unused_off, off2,
                                   unused_acc, out, voff, n, h);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
@@ -1099,7 +607,7 @@ int fill_params(const dapq_shape* s, const ScorePlan& plan, ScoreParams* p) {
   p->total_tokens = s->total_tokens;
   p->n_layers = s->n_layers; p->batch = s->batch; p->n_q_heads = s->n_q_heads; p->n_kv_heads = s->n_kv_heads;
   p->group = s->n_q_heads / s->n_kv_heads; p->n_pseudo = s->n_pseudo;
-  p->rows = plan.rows; p->rows_pad = plan.rows_pad; p->n_super = plan.n_super; p->n_groups = plan.n_groups;
+  p->rows = plan.rows; p->rows_pad = plan.rows_pad; p->n_groups = plan.n_groups;
   p->chunk_keys = plan.chunk_keys; p->max_chunks = (int32_t)plan.max_chunks;
   p->c = s->scale * 1.4426950408889634f;
   return DAPQ_OK;
@@ -1118,26 +626,19 @@ int launch_stats(const dapq_shape* s, const ScorePlan& plan, ScoreParams p, hipS
     DAPQ_HIP_LAUNCH_CHECK("score_chunk_prefix_kernel");
   }
   int rc = DAPQ_OK;
-  if (plan.wave_path) {
-    const dim3 grid((unsigned)plan.max_chunks, (unsigned)plan.n_groups, (unsigned)(s->n_layers * s->n_kv_heads));
-#define DAPQ_LAUNCH_W1(NRBV)                                                                        \
-  do {                                                                                              \
-    if ((rc = set_lds(score_wave_pass1_kernel<NRBV>, kWaveLds1)) != DAPQ_OK) return rc;              \
-    hipLaunchKernelGGL(score_wave_pass1_kernel<NRBV>, grid, dim3(64), kWaveLds1, stream, p);        \
+  const dim3 grid((unsigned)plan.max_chunks, (unsigned)plan.n_groups, (unsigned)(s->n_layers * s->n_kv_heads));
+#define DAPQ_LAUNCH_W1(NRBV)                                                                      \
+  do {                                                                                            \
+    if ((rc = set_lds(score_wave_pass1_kernel<NRBV>, kWaveLds1)) != DAPQ_OK) return rc;            \
+    hipLaunchKernelGGL(score_wave_pass1_kernel<NRBV>, grid, dim3(64), kWaveLds1, stream, p);      \
   } while (0)
-    if (plan.row_blocks == 2) DAPQ_LAUNCH_W1(2);
-    else if (plan.row_blocks == 4) DAPQ_LAUNCH_W1(4);
-    else DAPQ_LAUNCH_W1(8);
+  if (plan.row_blocks == 2) DAPQ_LAUNCH_W1(2);
+  else if (plan.row_blocks == 4) DAPQ_LAUNCH_W1(4);
+  else DAPQ_LAUNCH_W1(8);
 #undef DAPQ_LAUNCH_W1
-  } else {
-    const dim3 grid((unsigned)plan.max_chunks, (unsigned)plan.n_super, (unsigned)(s->n_layers * s->n_kv_heads));
-    if ((rc = set_lds(score_pass1_kernel<4>, kLdsScore)) != DAPQ_OK) return rc;
-    hipLaunchKernelGGL(score_pass1_kernel<4>, grid, dim3(kThreads), kLdsScore, stream, p);
-  }
-  DAPQ_HIP_LAUNCH_CHECK("score_pass1_kernel");
+  DAPQ_HIP_LAUNCH_CHECK("score_wave_pass1_kernel");
   const int64_t rows_total = (int64_t)s->n_layers * s->batch * s->n_q_heads * s->n_pseudo;
-  hipLaunchKernelGGL(score_combine_kernel, dim3((unsigned)((rows_total + 255) / 256)), dim3(256), 0, stream, p,
-                     plan.key_waves);
+  hipLaunchKernelGGL(score_combine_kernel, dim3((unsigned)((rows_total + 255) / 256)), dim3(256), 0, stream, p);
   DAPQ_HIP_LAUNCH_CHECK("score_combine_kernel");
   return DAPQ_OK;
 }
@@ -1149,33 +650,26 @@ int launch_accumulate(const dapq_shape* s, const ScorePlan& plan, ScoreParams p,
                        plan.chunk_keys);
     DAPQ_HIP_LAUNCH_CHECK("score_chunk_prefix_kernel");
   }
-  const dim3 grid((unsigned)plan.max_chunks, 1, (unsigned)(s->n_layers * s->n_kv_heads));
   int rc = DAPQ_OK;
-  if (plan.wave_path) {
-    const dim3 wgrid((unsigned)plan.max_chunks, (unsigned)plan.n_groups, (unsigned)(s->n_layers * s->n_kv_heads));
-#define DAPQ_LAUNCH_W2(NRBV)                                                                        \
-  do {                                                                                              \
-    if ((rc = set_lds(score_wave_pass2_kernel<NRBV>, kWaveLds2)) != DAPQ_OK) return rc;              \
-    hipLaunchKernelGGL(score_wave_pass2_kernel<NRBV>, wgrid, dim3(64), kWaveLds2, stream, p);       \
+  const dim3 grid((unsigned)plan.max_chunks, (unsigned)plan.n_groups, (unsigned)(s->n_layers * s->n_kv_heads));
+#define DAPQ_LAUNCH_W2(NRBV)                                                                      \
+  do {                                                                                            \
+    if ((rc = set_lds(score_wave_pass2_kernel<NRBV>, kWaveLds2)) != DAPQ_OK) return rc;            \
+    hipLaunchKernelGGL(score_wave_pass2_kernel<NRBV>, grid, dim3(64), kWaveLds2, stream, p);      \
   } while (0)
-    if (plan.row_blocks == 2) DAPQ_LAUNCH_W2(2);
-    else if (plan.row_blocks == 4) DAPQ_LAUNCH_W2(4);
-    else DAPQ_LAUNCH_W2(8);
+  if (plan.row_blocks == 2) DAPQ_LAUNCH_W2(2);
+  else if (plan.row_blocks == 4) DAPQ_LAUNCH_W2(4);
+  else DAPQ_LAUNCH_W2(8);
 #undef DAPQ_LAUNCH_W2
-    if (plan.n_groups > 1) {
-      DAPQ_HIP_LAUNCH_CHECK("score_wave_pass2_kernel");
-      const int64_t count = (int64_t)s->n_layers * s->n_kv_heads * s->total_tokens;
-      const unsigned blocks = (unsigned)(count + 255) / 256 < 16384u ? (unsigned)((count + 255) / 256) : 16384u;
-      hipLaunchKernelGGL(score_group_sum_kernel, dim3(blocks > 0 ? blocks : 1), dim3(256), 0, stream, p.partial,
-                         p.scores, count, plan.n_groups);
-    }
-  } else {
-    // more than 256 rows: four row waves, the Q slab changes per super-group
-    const int lds_bytes = kLdsScore + 2 * 4 * kTileKeys * (int)sizeof(float);
-    if ((rc = set_lds(score_pass2_kernel<4, true>, lds_bytes)) != DAPQ_OK) return rc;
-    hipLaunchKernelGGL((score_pass2_kernel<4, true>), grid, dim3(kThreads), lds_bytes, stream, p);
+  DAPQ_HIP_LAUNCH_CHECK("score_wave_pass2_kernel");
+  if (plan.n_groups > 1) {
+    const int64_t count = (int64_t)s->n_layers * s->n_kv_heads * s->total_tokens;
+    const int64_t want = (count + 255) / 256;
+    const unsigned blocks = (unsigned)(want < 1 ? 1 : (want > 16384 ? 16384 : want));
+    hipLaunchKernelGGL(score_group_sum_kernel, dim3(blocks), dim3(256), 0, stream, p.partial, p.scores, count,
+                       plan.n_groups);
+    DAPQ_HIP_LAUNCH_CHECK("score_group_sum_kernel");
   }
-  DAPQ_HIP_LAUNCH_CHECK("score_pass2_kernel");
   return DAPQ_OK;
 }
 
