@@ -1,15 +1,23 @@
 // M_retain = TopK_j S(j) (Sec. 4.2): per (layer, sequence, KV head) the budget positions with the
 // largest pooled score, equal scores lowest position first, written in ascending position.
 //
-// One workgroup of 1024 threads per head.  The scores of the head are staged in LDS when they fit
-// (up to 36864 keys = 144 KB of the 160 KB LDS), so HBM is read once; longer heads are re-read from
-// L2.  Selection is an exact radix select on the order-preserving integer image of the fp32 score:
-// four 8-bit digits from the top, each pass a 256-bin LDS histogram followed by a suffix scan that
-// fixes one digit of the threshold T and the number of keys equal to T still needed.  The last step
-// is an ordered compaction: key j is kept if score > T, or score == T and fewer than `need` equal
-// keys precede it; one packed (greater, equal) prefix count per block of 1024 keys gives both the
-// decision and the output slot, so the result is ascending and deterministic (no atomics decide
-// an order).  Max-pooling makes runs of bit-equal scores, so the tie rule is on the main path.
+// One workgroup of 1024 threads per head.  Selection is an exact radix select on the
+// order-preserving integer image of the fp32 score: four 8-bit digits from the top, each pass a
+// 256-bin LDS histogram followed by a suffix scan that fixes one digit of the threshold T and the
+// number of keys equal to T still needed.  The last step is an ordered compaction: key j is kept if
+// score > T, or score == T and fewer than `need` equal keys precede it; prefix counts of (greater,
+// equal) give both the decision and the output slot, so the result is ascending and deterministic
+// (no atomic decides an order).  Max-pooling makes runs of bit-equal scores, so the tie rule is on
+// the main path.
+//
+// Scores are positive and bunch into a few binades, so in the first pass nearly every key lands in
+// the same bin: each wave therefore counts the keys that share the digit of its first candidate
+// with a reduction and issues one atomic for them; only the others go to the histogram one by one.
+//
+// Heads of up to 65536 keys (topk_reg_kernel) are read from HBM once into registers, thread t
+// owning the consecutive keys [t*KPT, (t+1)*KPT): every pass runs out of registers and the
+// compaction needs a single workgroup scan.  Longer heads (topk_stream_kernel) stage what fits in
+// LDS (36864 keys) or re-read the scores from L2 on every pass.
 #include "dapq_internal.h"
 
 namespace dapq {
@@ -27,6 +35,7 @@ struct TopkParams {
   int32_t* count;
   int64_t total_tokens;
   int32_t batch, n_kv_heads, budget;
+  int32_t min_len, max_len;  // this launch handles the heads with min_len <= L <= max_len
 };
 
 // fp32 -> uint32 with the same order for all non-NaN values.
@@ -35,36 +44,200 @@ __device__ __forceinline__ uint32_t order_key(float f) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-__global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkParams p) {
-  extern __shared__ uint32_t smem[];
-  uint32_t* hist = smem;             // [256]
-  uint32_t* wave_tot = smem + 256;   // [16]
-  uint32_t* bcast = smem + 256 + 16; // [4]: digit, need, running (greater, equal) base
-  uint32_t* keys = smem + 320;       // [kTopkLdsKeys] staged order keys (if they fit)
+// What every variant needs to know about its head; heads of another launch (length outside
+// [min_len, max_len]), keep == 0 and keep == L are finished here.
+struct TopkHead {
+  const float* src;
+  int32_t* out;
+  int L, keep;
+  bool done;
+};
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+__device__ __forceinline__ TopkHead topk_head(const TopkParams& p) {
+  TopkHead hd;
+  const int tid = threadIdx.x;
   const int kv = blockIdx.x, b = blockIdx.y, layer = blockIdx.z;
   int64_t start;
-  int L;
   if (p.cu_seqlens == nullptr) {
-    L = (int)(p.total_tokens / p.batch);
-    start = (int64_t)b * L;
+    hd.L = (int)(p.total_tokens / p.batch);
+    start = (int64_t)b * hd.L;
   } else {
     start = p.cu_seqlens[b];
-    L = p.cu_seqlens[b + 1] - (int)start;
+    hd.L = p.cu_seqlens[b + 1] - (int)start;
+  }
+  if (hd.L < p.min_len || hd.L > p.max_len) {
+    hd.done = true;
+    hd.keep = 0;
+    hd.out = nullptr;
+    hd.src = nullptr;
+    return hd;
   }
   int want = p.budget_per_seq ? p.budget_per_seq[b] : p.budget;
   want = want < 0 ? 0 : (want > p.budget ? p.budget : want);
-  const int keep = want < L ? want : L;
+  hd.keep = want < hd.L ? want : hd.L;
   const int64_t head = ((int64_t)layer * p.batch + b) * p.n_kv_heads + kv;
-  int32_t* out = p.idx + head * p.budget;
-  if (tid == 0) p.count[head] = keep;
-  if (keep == 0) return;
-  if (keep == L) {  // everything survives
-    for (int j = tid; j < L; j += kTopkThreads) out[j] = j;
-    return;
+  hd.out = p.idx + head * p.budget;
+  hd.src = p.pooled + ((int64_t)layer * p.n_kv_heads + kv) * p.total_tokens + start;
+  if (tid == 0) p.count[head] = hd.keep;
+  hd.done = hd.keep == 0;
+  if (!hd.done && hd.keep == hd.L) {  // everything survives
+    for (int j = tid; j < hd.L; j += kTopkThreads) hd.out[j] = j;
+    hd.done = true;
   }
-  const float* src = p.pooled + ((int64_t)layer * p.n_kv_heads + kv) * p.total_tokens + start;
+  return hd;
+}
+
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+  return v;
+}
+
+// After a histogram pass: wave 0 finds the digit d of T, the one with greater(d) < need <= greater(d)
+// + hist[d], and publishes (d, need - greater(d)) in bcast.
+__device__ __forceinline__ void topk_pick_digit(const uint32_t* hist, uint32_t* bcast, int need, int lane) {
+  // lane l owns digits 4l..4l+3; suffix sums over the lanes above, then inside the lane
+  const uint32_t h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
+  const uint32_t mine = h0 + h1 + h2 + h3;
+  uint32_t incl = mine;  // inclusive suffix sum over lanes >= l
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint32_t o = __shfl_down(incl, d, 64);
+    if (lane + d < 64) incl += o;
+  }
+  const uint32_t above = incl - mine;  // keys whose digit is > 4l+3
+  const uint32_t g3 = above, g2 = g3 + h3, g1 = g2 + h2, g0 = g1 + h1;  // keys with a larger digit
+  const uint32_t un = (uint32_t)need;
+  if (g3 < un && un <= g3 + h3) { bcast[0] = 4 * lane + 3; bcast[1] = un - g3; }
+  if (g2 < un && un <= g2 + h2) { bcast[0] = 4 * lane + 2; bcast[1] = un - g2; }
+  if (g1 < un && un <= g1 + h1) { bcast[0] = 4 * lane + 1; bcast[1] = un - g1; }
+  if (g0 < un && un <= g0 + h0) { bcast[0] = 4 * lane + 0; bcast[1] = un - g0; }
+}
+
+// ---- heads that fit in registers
+template <int KPT>
+__global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(TopkParams p) {
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t bcast[2];
+  __shared__ uint32_t wave_gt[kTopkWaves], wave_eq[kTopkWaves];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const TopkHead hd = topk_head(p);
+  if (hd.done) return;
+  const int L = hd.L;
+
+  // thread t owns keys [t*KPT, t*KPT + KPT): registers i < nvalid hold a key.  (A layout with
+  // contiguous rows per wave loads no faster here and makes the compaction twice as long.)
+  const int j0 = tid * KPT;
+  const int nvalid = L - j0 < 0 ? 0 : (L - j0 > KPT ? KPT : L - j0);
+  uint32_t key[KPT];
+  if (nvalid == KPT && (reinterpret_cast<uintptr_t>(hd.src + j0) & 15) == 0) {
+#pragma unroll
+    for (int i = 0; i < KPT; i += 4) {
+      const float4 v = *reinterpret_cast<const float4*>(hd.src + j0 + i);
+      key[i] = order_key(v.x);
+      key[i + 1] = order_key(v.y);
+      key[i + 2] = order_key(v.z);
+      key[i + 3] = order_key(v.w);
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) key[i] = i < nvalid ? order_key(hd.src[j0 + i]) : 0u;
+  }
+
+  // ---- radix select: threshold T = the keep-th largest key, need = how many keys == T to take
+  uint32_t prefix = 0, mask = 0;
+  int need = hd.keep;
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
+    // the digit most keys of this wave are likely to share: that of its first candidate
+    int first = -1;
+#pragma unroll
+    for (int i = KPT - 1; i >= 0; --i)
+      if (i < nvalid && (key[i] & mask) == prefix) first = (int)((key[i] >> shift) & 255u);
+    const uint64_t have = __ballot(first >= 0);
+    if (have != 0) {
+      const uint32_t d0 = (uint32_t)__shfl(first, __ffsll((long long)have) - 1, 64);
+      uint32_t same = 0;
+#pragma unroll
+      for (int i = 0; i < KPT; ++i) {
+        if (i < nvalid && (key[i] & mask) == prefix) {
+          const uint32_t d = (key[i] >> shift) & 255u;
+          if (d == d0) ++same;
+          else atomicAdd(&hist[d], 1u);
+        }
+      }
+      same = wave_sum(same);
+      if (lane == 0 && same != 0) atomicAdd(&hist[d0], same);
+    }
+    __syncthreads();
+    if (wave == 0) topk_pick_digit(hist, bcast, need, lane);
+    __syncthreads();
+    prefix |= bcast[0] << shift;
+    mask |= 255u << shift;
+    need = (int)bcast[1];
+    __syncthreads();
+  }
+  const uint32_t T = prefix;
+
+  // ---- ordered compaction: one exclusive scan of the per-thread (greater, equal) counts
+  uint32_t my_gt = 0, my_eq = 0;
+#pragma unroll
+  for (int i = 0; i < KPT; ++i) {
+    my_gt += (i < nvalid && key[i] > T) ? 1u : 0u;
+    my_eq += (i < nvalid && key[i] == T) ? 1u : 0u;
+  }
+  uint32_t inc_gt = my_gt, inc_eq = my_eq;  // inclusive scans inside the wave
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint32_t a = __shfl_up(inc_gt, d, 64), c = __shfl_up(inc_eq, d, 64);
+    if (lane >= d) {
+      inc_gt += a;
+      inc_eq += c;
+    }
+  }
+  if (lane == 63) {
+    wave_gt[wave] = inc_gt;
+    wave_eq[wave] = inc_eq;
+  }
+  __syncthreads();
+  uint32_t pre_gt = inc_gt - my_gt, pre_eq = inc_eq - my_eq;
+#pragma unroll
+  for (int w = 0; w < kTopkWaves; ++w) {
+    if (w < wave) {
+      pre_gt += wave_gt[w];
+      pre_eq += wave_eq[w];
+    }
+  }
+  const uint32_t un = (uint32_t)need;
+  uint32_t pos = pre_gt + (pre_eq < un ? pre_eq : un);
+#pragma unroll
+  for (int i = 0; i < KPT; ++i) {
+    if (i < nvalid) {
+      if (key[i] > T) {
+        hd.out[pos++] = j0 + i;
+      } else if (key[i] == T) {
+        if (pre_eq < un) hd.out[pos++] = j0 + i;
+        ++pre_eq;
+      }
+    }
+  }
+}
+
+// ---- longer heads
+__global__ __launch_bounds__(kTopkThreads) void topk_stream_kernel(TopkParams p) {
+  extern __shared__ uint32_t smem[];
+  uint32_t* hist = smem;             // [256]
+  uint32_t* wave_tot = smem + 256;   // [16]
+  uint32_t* bcast = smem + 256 + 16; // [2]: digit, need
+  uint32_t* keys = smem + 320;       // [kTopkLdsKeys] staged order keys (if they fit)
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const TopkHead hd = topk_head(p);
+  if (hd.done) return;
+  const int L = hd.L;
+  const float* src = hd.src;
+  int32_t* out = hd.out;
   const bool staged = L <= kTopkLdsKeys;
   if (staged) {
     for (int j = tid; j < L; j += kTopkThreads) keys[j] = order_key(src[j]);
@@ -74,34 +247,25 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkParams p) {
 
   // ---- radix select: threshold T = the keep-th largest key, need = how many keys == T to take
   uint32_t prefix = 0, mask = 0;
-  int need = keep;
+  int need = hd.keep;
   for (int shift = 24; shift >= 0; shift -= 8) {
     if (tid < 256) hist[tid] = 0;
     __syncthreads();
-    for (int j = tid; j < L; j += kTopkThreads) {
-      const uint32_t k = key_at(j);
-      if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
+    for (int jb = 0; jb < L; jb += kTopkThreads) {  // the trip count is the same for every thread
+      const int j = jb + tid;
+      const uint32_t k = j < L ? key_at(j) : 0u;
+      const bool cand = j < L && (k & mask) == prefix;
+      const uint32_t d = (k >> shift) & 255u;
+      const uint64_t have = __ballot(cand);
+      if (have != 0) {
+        const uint32_t d0 = (uint32_t)__shfl((int)d, __ffsll((long long)have) - 1, 64);
+        const uint64_t same = __ballot(cand && d == d0);
+        if (cand && d != d0) atomicAdd(&hist[d], 1u);
+        if (lane == 0) atomicAdd(&hist[d0], (uint32_t)__popcll(same));
+      }
     }
     __syncthreads();
-    if (wave == 0) {
-      // lane l owns digits 4l..4l+3; suffix sums over the lanes above, then inside the lane
-      const uint32_t h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
-      const uint32_t mine = h0 + h1 + h2 + h3;
-      uint32_t incl = mine;  // inclusive suffix sum over lanes >= l
-#pragma unroll
-      for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t o = __shfl_down(incl, d, 64);
-        if (lane + d < 64) incl += o;
-      }
-      const uint32_t above = incl - mine;  // keys whose digit is > 4l+3
-      const uint32_t g3 = above, g2 = g3 + h3, g1 = g2 + h2, g0 = g1 + h1;  // keys with a larger digit
-      const uint32_t un = (uint32_t)need;
-      // the digit d of T satisfies greater(d) < need <= greater(d) + hist[d]; exactly one digit does
-      if (g3 < un && un <= g3 + h3) { bcast[0] = 4 * lane + 3; bcast[1] = un - g3; }
-      if (g2 < un && un <= g2 + h2) { bcast[0] = 4 * lane + 2; bcast[1] = un - g2; }
-      if (g1 < un && un <= g1 + h1) { bcast[0] = 4 * lane + 1; bcast[1] = un - g1; }
-      if (g0 < un && un <= g0 + h0) { bcast[0] = 4 * lane + 0; bcast[1] = un - g0; }
-    }
+    if (wave == 0) topk_pick_digit(hist, bcast, need, lane);
     __syncthreads();
     prefix |= bcast[0] << shift;
     mask |= 255u << shift;
@@ -110,7 +274,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(TopkParams p) {
   }
   const uint32_t T = prefix;
 
-  // ---- ordered compaction
+  // ---- ordered compaction, one block of 1024 keys at a time
   uint32_t base_gt = 0, base_eq = 0;  // keys > T / == T before the current block (same in all threads)
   for (int j0 = 0; j0 < L; j0 += kTopkThreads) {
     const int j = j0 + tid;
@@ -166,12 +330,30 @@ extern "C" DAPQ_API int dapq_topk(const dapq_shape* shape, const float* pooled, 
   p.batch = shape->batch;
   p.n_kv_heads = shape->n_kv_heads;
   p.budget = budget;
-  const int lds_bytes = (320 + kTopkLdsKeys) * (int)sizeof(uint32_t);
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(topk_kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-  if (e != hipSuccess) return fail(DAPQ_ERR_HIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
-  hipLaunchKernelGGL(topk_kernel, dim3((unsigned)shape->n_kv_heads, (unsigned)shape->batch, (unsigned)shape->n_layers),
-                     dim3(kTopkThreads), lds_bytes, static_cast<hipStream_t>(stream), p);
-  DAPQ_HIP_LAUNCH_CHECK("topk_kernel");
+  // Heads of up to KPT*1024 keys go to the register variant, longer ones to the streaming one.  A
+  // dense batch knows its length; a ragged one picks KPT from the mean length and launches both
+  // variants, each skipping the heads of the other.
+  const dim3 grid((unsigned)shape->n_kv_heads, (unsigned)shape->batch, (unsigned)shape->n_layers);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int64_t mean = shape->total_tokens / shape->batch;
+  const int64_t longest = shape->cu_seqlens == nullptr ? mean : shape->total_tokens;
+  const int kpt = mean <= 4 * kTopkThreads ? 8 : (mean <= 16 * kTopkThreads || longest <= 32 * kTopkThreads ? 32 : 64);
+  const int64_t reg_max = (int64_t)kpt * kTopkThreads;
+  p.min_len = 0;
+  p.max_len = (int32_t)reg_max;
+  if (kpt == 8) hipLaunchKernelGGL(topk_reg_kernel<8>, grid, dim3(kTopkThreads), 0, st, p);
+  else if (kpt == 32) hipLaunchKernelGGL(topk_reg_kernel<32>, grid, dim3(kTopkThreads), 0, st, p);
+  else hipLaunchKernelGGL(topk_reg_kernel<64>, grid, dim3(kTopkThreads), 0, st, p);
+  DAPQ_HIP_LAUNCH_CHECK("topk_reg_kernel");
+  if (longest > reg_max) {
+    p.min_len = (int32_t)reg_max + 1;
+    p.max_len = INT32_MAX;
+    const int lds_bytes = (320 + kTopkLdsKeys) * (int)sizeof(uint32_t);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(topk_stream_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    if (e != hipSuccess) return fail(DAPQ_ERR_HIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
+    hipLaunchKernelGGL(topk_stream_kernel, grid, dim3(kTopkThreads), lds_bytes, st, p);
+  }
+  DAPQ_HIP_LAUNCH_CHECK("topk_stream_kernel");
   return DAPQ_OK;
 }

@@ -188,9 +188,9 @@ def test_pool_dense_batch_unaligned_total(H):
 
 
 # ----------------------------------------------------------------------------------------- top-K
-def _topk_case(H, lens, budget, P, per_seq=None, layers=1, Hkv=2):
+def _topk_case(H, lens, budget, P, per_seq=None, layers=1, Hkv=2, dense=False):
     q, k, v, cu = random_problem(4, layers, lens, Hkv, Hkv, 1)
-    prob = H.Problem(q, k, v, Hkv, cu, "thd")
+    prob = H.Problem(q, k, v, Hkv, None if dense else cu, "thd")
     idx, count = prob.topk(torch.from_numpy(P).cuda(), budget, per_seq)
     idx, count = idx.cpu().numpy(), count.cpu().numpy()
     for l in range(layers):
@@ -244,6 +244,20 @@ def test_topk_long_sequence_not_staged_in_lds(H):
     P = r.random((1, 1, 70000)).astype(np.float32)
     P[0, 0, 5000:5100] = 2.0
     _topk_case(H, [70000], 2048, P, Hkv=1)
+
+
+@pytest.mark.parametrize("L,batch", [(8192, 1), (8193, 3), (32768, 1), (32769, 2), (50001, 1), (65536, 1), (65537, 1)])
+def test_topk_dense_lengths_around_the_variant_limits(H, L, batch):
+    """Dense batches at the lengths where the kernel variant changes (8, 32, 64 keys per thread,
+    then streaming), with sequence starts that are not 16-byte aligned, heavy ties and a plateau
+    across the threshold."""
+    announce(f"topk dense L={L} batch={batch}")
+    r = np.random.default_rng(L)
+    P = (r.random((1, 1, L * batch)) ** 6).astype(np.float32)
+    P[0, 0, : L // 2] = np.round(P[0, 0, : L // 2] * 64) / 64
+    P[0, 0, L // 3: L // 3 + 3000] = 0.75
+    for budget in (7, 983, 3932):
+        _topk_case(H, [L] * batch, budget, P, Hkv=1, dense=True)
 
 
 # ----------------------------------------------------------------------------------------- gather
