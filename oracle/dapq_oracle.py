@@ -17,7 +17,8 @@ Symbols (the paper overloads N and K; this file uses):
 
 Readings taken where the paper is silent (each is listed in the design notes of
 this repository): the softmax runs over the L prompt keys only (Sec. 4.2 indexes
-j in [0, L_p-1]); scores of the g query heads of a group are summed and selection
+j in [0, L_p-1]) unless the pseudo tokens' own keys are passed in, in which case the
+extended sequence of Sec. 4.1 is attended causally; scores of the g query heads of a group are summed and selection
 is per KV head; pooling is a stride-1 max over a centred window clipped at the
 sequence ends, applied after the group sum; TopK ties go to the lowest index and
 the retained set is reported in ascending position; RoPE pairs channel c with
@@ -34,7 +35,7 @@ import numpy as np
 
 __all__ = [
     "bf16_bits_to_f64", "f64_to_bf16_bits", "rope_rotate", "rope_apply", "attention", "score_head",
-    "score", "pool", "topk", "gather", "compress", "recall", "topk_margin",
+    "score", "pool", "topk", "gather", "compress", "recall", "topk_margin", "attention_extended",
 ]
 
 
@@ -128,17 +129,47 @@ def attention(q, k, scale=None) -> np.ndarray:
     return e / e.sum(axis=1, keepdims=True)
 
 
+def attention_extended(q, k, k_pseudo, scale=None) -> np.ndarray:
+    """Attention weights of the pseudo queries over the extended sequence of Sec. 4.1: the L prompt
+    keys followed by the N keys of the pseudo tokens themselves, prefilled causally, so that query i
+    (position L_p+i) sees every prompt key and the pseudo keys at positions L_p..L_p+i.
+
+    q: float64 [N, d]; k: float64 [L, d]; k_pseudo: float64 [N, d]; returns float64 [N, L+N] with
+    zeros where the causal mask hides a key; every row sums to 1."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    kp = np.asarray(k_pseudo, dtype=np.float64)
+    N, L = q.shape[0], k.shape[0]
+    if scale is None:
+        scale = 1.0 / np.sqrt(q.shape[-1])
+    s = (q @ np.concatenate([k, kp], axis=0).T) * scale
+    for i in range(N):
+        s[i, L + i + 1:] = -np.inf                   # pseudo tokens after query i do not exist yet
+    s = s - s.max(axis=1, keepdims=True)
+    e = np.exp(s)
+    return e / e.sum(axis=1, keepdims=True)
+
+
 # --------------------------------------------------------------------------------------
 # Sec. 4.2, importance score: S(j) = sum over the pseudo queries of Attention(q_i, k_j)
 # --------------------------------------------------------------------------------------
-def score_head(q, k, scale=None) -> np.ndarray:
+def score_head(q, k, scale=None, k_pseudo=None) -> np.ndarray:
     """S(j) for one KV head.  q: float64 [g, N, d] (the g query heads of the group, N pseudo
     queries each, already rotated to L_p+i); k: float64 [L, d] (prompt keys, rotated).
-    Sum over the N pseudo queries (Sec. 4.2) and over the g heads of the group."""
+    Sum over the N pseudo queries (Sec. 4.2) and over the g heads of the group.
+    k_pseudo (float64 [N, d], the KV head's keys of the pseudo tokens): if given, every row is
+    normalised over the extended sequence (attention_extended); S is still reported for the
+    prompt keys only, j in [0, L_p-1]."""
     q = np.asarray(q, dtype=np.float64)
     g, N, d = q.shape
-    alpha = attention(q.reshape(g * N, d), k, scale)
-    return alpha.sum(axis=0)
+    if k_pseudo is None:
+        alpha = attention(q.reshape(g * N, d), k, scale)
+        return alpha.sum(axis=0)
+    L = np.asarray(k).shape[0]
+    S = np.zeros(L, dtype=np.float64)
+    for h in range(g):
+        S += attention_extended(q[h], k, k_pseudo, scale)[:, :L].sum(axis=0)
+    return S
 
 
 def _seq_bounds(total_tokens, batch, cu_seqlens):
@@ -149,10 +180,11 @@ def _seq_bounds(total_tokens, batch, cu_seqlens):
     return [(cu[b], cu[b + 1]) for b in range(batch)]
 
 
-def score(q_bits, k_bits, n_kv_heads, cu_seqlens=None, scale=None) -> np.ndarray:
+def score(q_bits, k_bits, n_kv_heads, cu_seqlens=None, scale=None, kp_bits=None) -> np.ndarray:
     """Scores for a (possibly ragged) batch.  q_bits: bf16 bits [layers, batch, Hq, N, d];
     k_bits: bf16 bits [layers, tokens, Hkv, d] with the sequences packed along tokens;
-    cu_seqlens: [batch+1] token offsets (None: equal lengths).  Returns float64
+    cu_seqlens: [batch+1] token offsets (None: equal lengths); kp_bits: optional bf16 bits
+    [layers, batch, Hkv, N, d], the pseudo tokens' own keys (see score_head).  Returns float64
     [layers, Hkv, tokens].  Query head h belongs to KV head h // g."""
     q_bits = np.asarray(q_bits)
     k_bits = np.asarray(k_bits)
@@ -167,7 +199,8 @@ def score(q_bits, k_bits, n_kv_heads, cu_seqlens=None, scale=None) -> np.ndarray
             for kv in range(n_kv_heads):
                 q = bf16_bits_to_f64(q_bits[l, b, kv * g:(kv + 1) * g])
                 k = bf16_bits_to_f64(k_bits[l, s:e, kv])
-                out[l, kv, s:e] = score_head(q, k, scale)
+                kp = None if kp_bits is None else bf16_bits_to_f64(np.asarray(kp_bits)[l, b, kv])
+                out[l, kv, s:e] = score_head(q, k, scale, kp)
     return out
 
 

@@ -354,3 +354,91 @@ def test_planted_needles_survive_eviction_small_workload():
 def test_recall_definition():
     assert O.recall([1, 2, 3, 4], [2, 4, 9]) == 0.5
     assert O.recall([5], [5]) == 1.0 and O.recall([5, 6], [7]) == 0.0
+
+
+# ------------------------------------------------------------------ extended sequence (Sec. 4.1): pseudo keys in the normaliser
+def test_extended_attention_golden_two_pseudo(golden):
+    g = golden("attention_extended_two_pseudo.txt")
+    q = np.array([g["q"], g["q"]])
+    k = np.array([g["k1"], g["k2"], g["k3"]])
+    kp = np.array([g["kp0"], g["kp1"]])
+    a = O.attention_extended(q, k, kp)
+    assert np.allclose(a[0], g["alpha0"], rtol=0, atol=1e-15)
+    assert np.allclose(a[1], g["alpha1"], rtol=0, atol=1e-15)
+    S = O.score_head(q[None], k, None, kp)
+    assert np.allclose(S, g["S"], rtol=0, atol=1e-15)
+
+
+def test_extended_attention_identical_keys_is_harmonic():
+    # every key, prompt or pseudo, equal: query i spreads evenly over its L + i + 1 visible keys,
+    # so S(j) = g * sum_i 1/(L + i + 1); a mask that hid the wrong side would give 1/(L + N - i)
+    L, N, g, d = 9, 5, 3, 8
+    key = rng(70).standard_normal(d)
+    q = rng(71).standard_normal((g, N, d))
+    S = O.score_head(q, np.tile(key, (L, 1)), None, np.tile(key, (N, 1)))
+    want = g * sum(1.0 / (L + i + 1) for i in range(N))
+    assert np.allclose(S, want, rtol=1e-13)
+    a = O.attention_extended(q[0], np.tile(key, (L, 1)), np.tile(key, (N, 1)))
+    assert np.allclose(a[0, :L + 1], 1.0 / (L + 1)) and np.all(a[0, L + 1:] == 0)
+
+
+def test_extended_attention_matches_torch_masked_softmax_and_conserves_mass():
+    L, N, d = 37, 11, 16
+    r = rng(72)
+    q, k, kp = r.standard_normal((N, d)), r.standard_normal((L, d)), r.standard_normal((N, d))
+    a = O.attention_extended(q, k, kp)
+    logits = torch.from_numpy(np.concatenate([k, kp]) @ q.T).T / math.sqrt(d)         # [N, L+N]
+    visible = torch.cat([torch.ones(N, L, dtype=torch.bool), torch.tril(torch.ones(N, N, dtype=torch.bool))], dim=1)
+    want = torch.softmax(logits.masked_fill(~visible, float("-inf")), dim=1).numpy()
+    assert np.allclose(a, want, rtol=1e-12, atol=1e-16)
+    assert np.allclose(a.sum(axis=1), 1.0, rtol=1e-13)
+    # S over the prompt keys + the mass that went to the pseudo keys = N
+    S = O.score_head(q[None], k, None, kp)
+    assert np.isclose(S.sum() + want[:, L:].sum(), N, rtol=1e-12)
+
+
+def test_extended_attention_brute_force_and_causality():
+    L, N, d, scale = 6, 4, 5, 0.3
+    r = rng(73)
+    q, k, kp = r.standard_normal((N, d)), r.standard_normal((L, d)), r.standard_normal((N, d))
+    a = O.attention_extended(q, k, kp, scale)
+    for i in range(N):
+        w = [math.exp(scale * sum(q[i, c] * k[j, c] for c in range(d))) for j in range(L)]
+        w += [math.exp(scale * sum(q[i, c] * kp[t, c] for c in range(d))) for t in range(i + 1)]
+        tot = sum(w)
+        for j, x in enumerate(w):
+            assert math.isclose(a[i, j], x / tot, rel_tol=1e-12)
+        assert np.all(a[i, L + i + 1:] == 0)
+    # a later pseudo key cannot change an earlier query's weights
+    kp2 = kp.copy()
+    kp2[N - 1] += 5.0
+    a2 = O.attention_extended(q, k, kp2, scale)
+    assert np.array_equal(a2[:N - 1], a[:N - 1]) and not np.allclose(a2[N - 1], a[N - 1])
+
+
+def test_extended_score_reduces_to_prompt_only_when_pseudo_keys_are_far():
+    # pseudo keys opposite to every query: their weight vanishes and S equals the prompt-only score
+    L, N, g, d = 50, 8, 2, 16
+    r = rng(74)
+    q = np.abs(r.standard_normal((g, N, d))) + 0.5
+    k = r.standard_normal((L, d))
+    kp = -200.0 * np.ones((N, d))
+    assert np.allclose(O.score_head(q, k, None, kp), O.score_head(q, k), rtol=1e-12)
+    # and never exceeds it: the extra keys only take mass away
+    kp = r.standard_normal((N, d))
+    assert np.all(O.score_head(q, k, None, kp) < O.score_head(q, k))
+
+
+def test_extended_score_batch_layout():
+    layers, B, Hq, Hkv, N, d = 2, 2, 4, 2, 3, 8
+    lens = [5, 9]
+    r = rng(75)
+    qb = W.to_bf16_bits(r.standard_normal((layers, B, Hq, N, d)))
+    kb = W.to_bf16_bits(r.standard_normal((layers, sum(lens), Hkv, d)))
+    kpb = W.to_bf16_bits(r.standard_normal((layers, B, Hkv, N, d)))
+    cu = np.array([0, 5, 14])
+    S = O.score(qb, kb, Hkv, cu, None, kpb)
+    l, b, kv = 1, 1, 1
+    want = O.score_head(O.bf16_bits_to_f64(qb[l, b, 2:4]), O.bf16_bits_to_f64(kb[l, 5:14, kv]), None,
+                        O.bf16_bits_to_f64(kpb[l, b, kv]))
+    assert np.array_equal(S[l, kv, 5:14], want)
