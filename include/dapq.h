@@ -105,6 +105,21 @@ int dapq_score_stats(const dapq_shape* shape, const void* q, const void* k, floa
 int dapq_score_accumulate(const dapq_shape* shape, const void* q, const void* k, const float* lse2,
                           float* scores, void* workspace, size_t workspace_bytes, void* stream);
 
+/* Sec. 4.1 prefills the pseudo tokens in the same sequence as the prompt, so pseudo query i (position
+ * L_p+i) also attends, causally, to the keys of the pseudo tokens at positions L_p..L_p+i.  This call
+ * adds that block to the normaliser written by dapq_score_stats, in place:
+ *   lse2[row i] <- log2( 2^lse2[row i] + sum_{t<=i} 2^(c * q_i.kp_t) ),
+ * after which dapq_score_accumulate yields S(j) over the prompt keys with every softmax row
+ * normalised over the extended sequence (the rows then sum to less than 1 over the prompt keys).
+ *   k_pseudo   device, bf16, the pseudo tokens' own keys after RoPE: element (layer, seq, kv head,
+ *              t, c) at kp_stride_layer*layer + kp_stride_seq*seq + kp_stride_head*head +
+ *              kp_stride_row*t + c (strides in elements, rows of head_dim contiguous, 16-byte aligned)
+ *   lse2       in/out, fp32 [n_layers][batch][n_q_heads][n_pseudo]
+ * Uses q and the q strides of shape; the K/V strides and cu_seqlens are not read. */
+int dapq_score_stats_extend(const dapq_shape* shape, const void* q, const void* k_pseudo,
+                            int64_t kp_stride_layer, int64_t kp_stride_seq, int64_t kp_stride_head,
+                            int64_t kp_stride_row, float* lse2, void* stream);
+
 /* Pooling of the accumulated scores before selection (Sec. 1 / Sec. 5.1: selection runs on pooled
  * accumulated attention scores): pooled(j) = max of scores over |t-j| <= (width-1)/2 inside the
  * same sequence (the window is clipped at the sequence ends).  width odd, 1 <= width <= 63.

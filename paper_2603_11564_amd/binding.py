@@ -15,7 +15,7 @@ _lib = None
 
 EXPORTS = (
     "dapq_workspace_bytes", "dapq_last_error", "dapq_rope_apply", "dapq_score", "dapq_score_stats",
-    "dapq_score_accumulate", "dapq_pool", "dapq_topk", "dapq_gather",
+    "dapq_score_accumulate", "dapq_score_stats_extend", "dapq_pool", "dapq_topk", "dapq_gather",
 )
 
 
@@ -64,6 +64,7 @@ def load_library():
     lib.dapq_score.argtypes = [sp, vp, vp, vp, vp, sz, vp]
     lib.dapq_score_stats.argtypes = [sp, vp, vp, vp, vp, sz, vp]
     lib.dapq_score_accumulate.argtypes = [sp, vp, vp, vp, vp, vp, sz, vp]
+    lib.dapq_score_stats_extend.argtypes = [sp, vp, vp, i64, i64, i64, i64, vp, vp]
     lib.dapq_pool.argtypes = [sp, vp, vp, i32, vp]
     lib.dapq_topk.argtypes = [sp, vp, i32, vp, vp, vp, vp, sz, vp]
     lib.dapq_gather.argtypes = [sp, vp, vp, vp, vp, i32, vp, vp, vp]
@@ -130,6 +131,13 @@ def dapq_score_accumulate(shape, q, k, lse2, scores, workspace, stream=None):
     _check(load_library().dapq_score_accumulate(
         C.byref(shape), _ptr(q), _ptr(k), _ptr(lse2), _ptr(scores), _ptr(workspace),
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def dapq_score_stats_extend(shape, q, k_pseudo, kp_strides, lse2, stream=None):
+    """kp_strides = (layer, seq, head, row) in elements."""
+    sl, ss, sh, sr = kp_strides
+    _check(load_library().dapq_score_stats_extend(C.byref(shape), _ptr(q), _ptr(k_pseudo), sl, ss, sh, sr, _ptr(lse2),
+                                                  _stream(stream)))
 
 
 def dapq_pool(shape, scores, pooled, width=7, stream=None):

@@ -399,17 +399,23 @@ __device__ __forceinline__ void wave_walk(u32x4* ring, const uint16_t* kbase, in
   }
 }
 
-// One sub-block the plain way (pass 1): masks keys >= nkeys, fixes the reference logits (FIRST) or
-// tracks a running maximum (SAFE).
-template <int NRB, bool SAFE, bool FIRST>
+// One sub-block the plain way (pass 1): masks keys >= nkeys (or, CAUSAL, the keys after each query's
+// own position), fixes the reference logits (FIRST) or tracks a running maximum (SAFE).
+template <int NRB, bool SAFE, bool FIRST, bool CAUSAL = false>
 __device__ __forceinline__ void wave_sub_simple(const bf16x8 (&kf)[8], const bf16x8 (&qf)[NRB][8], float c,
-                                                float (&ref)[NRB], float (&z)[NRB], int key0, int nkeys, int h) {
+                                                float (&ref)[NRB], float (&z)[NRB], int key0, int nkeys, int h,
+                                                const int* last_key = nullptr) {
 #pragma unroll
   for (int rb = 0; rb < NRB; ++rb) {
     f32x16 a = {0};
 #pragma unroll
     for (int s = 0; s < 8; ++s) a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[rb][s], a, 0, 0, 0);
-    if (key0 + 32 > nkeys) {
+    if (CAUSAL) {
+      // last_key[rb]: the last key this lane's query of row block rb may see
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        if (key0 + acc_row(v, h) > last_key[rb]) a[v] = -INFINITY;
+    } else if (key0 + 32 > nkeys) {
 #pragma unroll
       for (int v = 0; v < 16; ++v)
         if (key0 + acc_row(v, h) >= nkeys) a[v] = -INFINITY;
@@ -580,6 +586,62 @@ __global__ __launch_bounds__(64, 1) void score_wave_pass2_kernel(ScoreParams p) 
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
+// The causal block of the pseudo tokens' own keys (Sec. 4.1: they are prefilled in-sequence): one wave
+// per (sequence, row group, layer x KV head) scores its Q rows against the n_pseudo pseudo keys, row
+// i = row % n_pseudo seeing keys 0..i, and folds the result into lse2 in place.  Every row sees key 0,
+// so its running maximum is finite from the first sub-block on.
+struct PseudoParams {
+  const uint16_t* kp;
+  int64_t stride_layer, stride_seq, stride_head, stride_row;
+};
+
+template <int NRB>
+__global__ __launch_bounds__(64, 1) void score_wave_pseudo_kernel(ScoreParams p, PseudoParams pp) {
+  extern __shared__ u32x4 ring[];
+  const int seq = blockIdx.x;
+  const int layer = uniform_i32(blockIdx.z / p.n_kv_heads), kv = blockIdx.z - layer * p.n_kv_heads;
+  const int lane = threadIdx.x, n = lane & 31, h = lane >> 5;
+  const uint16_t* qbase = p.q + (int64_t)layer * p.q_stride_layer + (int64_t)seq * p.q_stride_seq +
+                          (int64_t)kv * p.group * p.q_stride_head;
+  const uint16_t* kbase = uniform_ptr(pp.kp + (int64_t)layer * pp.stride_layer + (int64_t)seq * pp.stride_seq +
+                                      (int64_t)kv * pp.stride_head);
+  float* lse = p.lse2 + (((int64_t)layer * p.batch + seq) * p.n_q_heads + (int64_t)kv * p.group) * p.n_pseudo;
+  const int gbase = blockIdx.y * (NRB * 32);
+  unsigned voff[4];
+  sub_dma_lane_offsets(voff, pp.stride_row, lane);
+  bf16x8 qf[NRB][8];
+  int last_key[NRB];
+  float ref[NRB], z[NRB];
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb) {
+    frag_from_q(qf[rb], p, qbase, gbase + rb * 32 + n, h);
+    const int row = gbase + rb * 32 + n;
+    last_key[rb] = (row < p.rows ? row : p.rows - 1) % p.n_pseudo;
+    ref[rb] = -INFINITY;
+    z[rb] = 0.0f;
+  }
+  bf16x8 kf[8];
+  const int nsubs = (p.n_pseudo + 31) / 32;
+  for (int sub = 0; sub < nsubs; ++sub) {
+    sub_dma(ring, kbase, pp.stride_row, sub * 32, p.n_pseudo, voff);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    wave_load_frags<NRB>(kf, ring, n, h);
+    wave_sub_simple<NRB, true, false, true>(kf, qf, p.c, ref, z, sub * 32, p.n_pseudo, h, last_key);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the fragments are out of the slot before it is refilled
+  }
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb) {
+    const float zz = z[rb] + xhalf(z[rb]);
+    const int row = gbase + rb * 32 + n;
+    if (h == 0 && row < p.rows) {
+      const float block = ref[rb] + log2f(zz);  // log2 of the block's sum; zz >= 1
+      const float old = lse[row];
+      const float m = fmaxf(old, block);
+      lse[row] = m + log2f(__builtin_amdgcn_exp2f(old - m) + __builtin_amdgcn_exp2f(block - m));
+    }
+  }
+}
+
 // S = sum over row groups of their planes of column sums, in group order.
 __global__ void score_group_sum_kernel(const float* partial, float* scores, int64_t count, int n_groups) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -745,4 +807,44 @@ extern "C" DAPQ_API int dapq_score(const dapq_shape* shape, const void* q, const
   float* lse2 = reinterpret_cast<float*>(static_cast<char*>(workspace) + plan.off_lse2);
   if ((rc = dapq_score_stats(shape, q, k, lse2, workspace, workspace_bytes, stream)) != DAPQ_OK) return rc;
   return dapq_score_accumulate(shape, q, k, lse2, scores, workspace, workspace_bytes, stream);
+}
+
+
+extern "C" DAPQ_API int dapq_score_stats_extend(const dapq_shape* shape, const void* q, const void* k_pseudo,
+                                                int64_t kp_stride_layer, int64_t kp_stride_seq, int64_t kp_stride_head,
+                                                int64_t kp_stride_row, float* lse2, void* stream) {
+  int rc = check_shape(shape, true, false, false);
+  if (rc != DAPQ_OK) return rc;
+  ScorePlan plan;
+  if ((rc = make_score_plan(shape, &plan)) != DAPQ_OK) return rc;
+  if ((rc = aligned16(q, "q")) != DAPQ_OK) return rc;
+  if ((rc = aligned16(k_pseudo, "k_pseudo")) != DAPQ_OK) return rc;
+  DAPQ_REQUIRE(lse2 != nullptr, DAPQ_ERR_INVALID_ARG, "lse2 is NULL");
+  DAPQ_REQUIRE(kp_stride_layer >= 0 && kp_stride_seq >= 0 && kp_stride_head >= 0, DAPQ_ERR_INVALID_ARG,
+               "k_pseudo strides must be >= 0");
+  DAPQ_REQUIRE(kp_stride_row >= shape->head_dim && kp_stride_row < ((int64_t)1 << 26), DAPQ_ERR_INVALID_ARG,
+               "kp_stride_row (%lld) must be in [head_dim, 2^26)", (long long)kp_stride_row);
+  DAPQ_REQUIRE(kp_stride_layer % 8 == 0 && kp_stride_seq % 8 == 0 && kp_stride_head % 8 == 0 && kp_stride_row % 8 == 0,
+               DAPQ_ERR_UNSUPPORTED, "k_pseudo strides must be multiples of 8 elements (16-byte rows)");
+  DAPQ_REQUIRE(shape->batch <= 65535, DAPQ_ERR_UNSUPPORTED, "batch must be <= 65535");
+  ScoreParams p;
+  fill_params(shape, plan, &p);
+  p.q = static_cast<const uint16_t*>(q);
+  p.k = nullptr;
+  p.cu_chunks = nullptr;
+  p.parts = nullptr;
+  p.partial = nullptr;
+  p.scores = nullptr;
+  p.lse2 = lse2;
+  PseudoParams pp;
+  pp.kp = static_cast<const uint16_t*>(k_pseudo);
+  pp.stride_layer = kp_stride_layer; pp.stride_seq = kp_stride_seq;
+  pp.stride_head = kp_stride_head; pp.stride_row = kp_stride_row;
+  const dim3 grid((unsigned)shape->batch, (unsigned)plan.n_groups, (unsigned)(shape->n_layers * shape->n_kv_heads));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (plan.row_blocks == 2) hipLaunchKernelGGL(score_wave_pseudo_kernel<2>, grid, dim3(64), kSubBytes, st, p, pp);
+  else if (plan.row_blocks == 4) hipLaunchKernelGGL(score_wave_pseudo_kernel<4>, grid, dim3(64), kSubBytes, st, p, pp);
+  else hipLaunchKernelGGL(score_wave_pseudo_kernel<8>, grid, dim3(64), kSubBytes, st, p, pp);
+  DAPQ_HIP_LAUNCH_CHECK("score_wave_pseudo_kernel");
+  return DAPQ_OK;
 }

@@ -66,6 +66,17 @@ class Problem:
         D.dapq_score_stats(self.shape, self.q, self.k, lse, self.ws)
         return lse
 
+    def score_extended(self, kp_bits):
+        """S with every row normalised over the extended sequence: pass 1, the causal block of the pseudo
+        tokens' own keys (kp_bits: [layers, batch, Hkv, N, d]), pass 2."""
+        kp = dev_bf16(kp_bits, self.device)
+        lse = self.stats()
+        strides = (self.batch * self.Hkv * self.N * self.d, self.Hkv * self.N * self.d, self.N * self.d, self.d)
+        D.dapq_score_stats_extend(self.shape, self.q, kp, strides, lse)
+        S = torch.full((self.layers, self.Hkv, self.tokens), float("nan"), dtype=torch.float32, device=self.device)
+        D.dapq_score_accumulate(self.shape, self.q, self.k, lse, S, self.ws)
+        return S
+
     def pool(self, S, width=7):
         P = torch.full_like(S, float("nan"))
         D.dapq_pool(self.shape, S, P, width)

@@ -157,6 +157,33 @@ def test_score_scale_and_large_gain(H):
     H.assert_scores_close(S, O.score(q, k, 2, None, 0.2), "scale 0.2")
 
 
+EXTENDED_CASES = [
+    # name, layers, lens, Hq, Hkv, N, gain
+    ("N64 g4 one sequence", 1, [700], 8, 2, 64, 1.0),
+    ("N1 g1: a single pseudo key", 1, [33], 2, 2, 1, 1.0),
+    ("N5 g2 ragged, short prompts", 2, [3, 40, 0, 129], 4, 2, 5, 1.0),
+    ("N128 g4: two row groups", 1, [300], 4, 1, 128, 1.0),
+    ("N40 g3: rows not a multiple of 32, sharp logits", 1, [257], 6, 2, 40, 3.0),
+]
+
+
+@pytest.mark.parametrize("case", EXTENDED_CASES, ids=[c[0] for c in EXTENDED_CASES])
+def test_score_extended_normaliser_matches_oracle(H, case):
+    """Sec. 4.1 prefills the pseudo tokens in-sequence: the causal block of their own keys joins
+    every row's normaliser (dapq_score_stats_extend between the two passes)."""
+    name, layers, lens, Hq, Hkv, N, gain = case
+    announce(f"score, extended normaliser: {name}")
+    q, k, v, cu = random_problem(31, layers, lens, Hq, Hkv, N, gain=gain)
+    kp = W.to_bf16_bits(np.random.default_rng(32).standard_normal((layers, len(lens), Hkv, N, 128)) * gain)
+    prob = H.Problem(q, k, v, Hkv, cu if len(lens) > 1 else None, "thd")
+    S = prob.score_extended(kp).cpu().numpy()
+    want = O.score(q, k, Hkv, cu, None, kp)
+    H.assert_scores_close(S, want, name)
+    # the pseudo keys only take mass away from the prompt keys
+    plain = prob.score().cpu().numpy()
+    assert (S <= plain * (1 + 1e-6)).all()
+
+
 # ----------------------------------------------------------------------------------------- pool
 @pytest.mark.parametrize("width", [1, 3, 7, 9, 11, 63])
 def test_pool_bit_exact(H, width):
