@@ -3,7 +3,7 @@
 
 A step is one pass of the whole hot path over one synthetic batch, all layers and heads:
   dapq_rope_apply (pseudo queries to positions L_p..L_p+N-1) -> dapq_score_stats (pass 1 over K)
-  -> dapq_score_accumulate (pass 2 over K) -> dapq_pool -> dapq_topk -> dapq_gather.
+  -> dapq_score_accumulate (pass 2 over K) -> dapq_pool_topk (max-pool + TopK) -> dapq_gather.
 Inputs are resident in HBM before the timed region.  Prints one JSON line:
   value     prompt keys scored+evicted per second (layers x KV heads x prompt keys / step time)
   roofline  the dominant kernel against the nearer roof (HBM for up to ~310 query rows per KV head,
@@ -88,8 +88,10 @@ def cpu_baseline(w, seed, n_layers):
 class Context:
     """Everything one benchmark step needs, resident in HBM: inputs, outputs, workspace, and step()."""
 
-    def __init__(self, w, seed, dev, overrides=None):
-        """overrides: optional {(layer_index, sequence, kv_head): (k_bits [L, d], v_bits [L, d])} of post-RoPE
+    def __init__(self, w, seed, dev, overrides=None, keep_pooled=False):
+        """keep_pooled: also write the pooled scores to self.P (the tests look at them); otherwise pooling
+        happens inside the selection kernel whenever dapq_pool_topk can fuse the two.
+        overrides: optional {(layer_index, sequence, kv_head): (k_bits [L, d], v_bits [L, d])} of post-RoPE
         host slices written over the device-generated ones; the parity tests use it to give the oracle and
         the GPU the same bits for the heads they compare."""
         import numpy as np
@@ -135,7 +137,10 @@ class Context:
         self.ws = torch.empty(D.workspace_bytes(self.shape), dtype=torch.uint8, device=dev)
         self.lse2 = torch.empty((nl, B, Hq, N), dtype=torch.float32, device=dev)
         self.S = torch.empty((nl, Hkv, tokens), dtype=torch.float32, device=dev)
-        self.P = torch.empty_like(self.S)
+        # dapq_pool_topk is one kernel for windows up to 9 and heads up to 65536 keys; else it needs P as scratch
+        longest = max(lens) if w.ragged is None else tokens
+        self.fused_select = w.pool_width <= 9 and longest <= 65536
+        self.P = torch.empty_like(self.S) if (keep_pooled or not self.fused_select) else None
         self.idx = torch.zeros((nl, B, Hkv, w.budget), dtype=torch.int32, device=dev)
         self.count = torch.zeros((nl, B, Hkv), dtype=torch.int32, device=dev)
         self.k_out = torch.zeros((nl, B, Hkv, w.budget, d), dtype=torch.bfloat16, device=dev)
@@ -144,7 +149,7 @@ class Context:
         self.stream = torch.cuda.current_stream()
         self.key_units = nl * Hkv * tokens
 
-    names = ["rope", "score_pass1", "score_pass2", "pool", "topk", "gather"]
+    names = ["rope", "score_pass1", "score_pass2", "pool_topk", "gather"]
 
     def step(self, events=None):
         D, w, stream = self.D, self.w, self.stream
@@ -161,12 +166,10 @@ class Context:
         mark(2)
         D.dapq_score_accumulate(self.shape, self.q, self.k, self.lse2, self.S, self.ws, stream)
         mark(3)
-        D.dapq_pool(self.shape, self.S, self.P, w.pool_width, stream)
+        D.dapq_pool_topk(self.shape, self.S, w.pool_width, w.budget, None, self.idx, self.count, self.P, stream)
         mark(4)
-        D.dapq_topk(self.shape, self.P, w.budget, None, self.idx, self.count, None, stream)
-        mark(5)
         D.dapq_gather(self.shape, self.k, self.v, self.idx, self.count, w.budget, self.k_out, self.v_out, stream)
-        mark(6)
+        mark(5)
 
 
 def main():
@@ -197,7 +200,7 @@ def main():
     for _ in range(args.warmup):
         ctx.step()
     torch.cuda.synchronize()
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(7)] for _ in range(args.steps)]
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):

@@ -135,6 +135,16 @@ int dapq_pool(const dapq_shape* shape, const float* scores, float* pooled, int32
 int dapq_topk(const dapq_shape* shape, const float* pooled, int32_t budget, const int32_t* budget_per_seq,
               int32_t* idx, int32_t* count, void* workspace, size_t workspace_bytes, void* stream);
 
+/* dapq_pool followed by dapq_topk as one call.  When every head has at most 65536 keys and width <= 9
+ * this is a single kernel: each thread pools its run of scores in registers (window clipped at the
+ * sequence ends) and the pooled scores never travel through HBM; `pooled` may then be NULL, and if it
+ * is not NULL it receives the pooled scores as dapq_pool would write them.  Otherwise the two kernels
+ * run one after the other and `pooled` (fp32 [n_layers][n_kv_heads][total_tokens], not aliasing
+ * scores) is required as the intermediate: DAPQ_ERR_UNSUPPORTED if it is NULL.  Results are identical
+ * to the two separate calls in every case. */
+int dapq_pool_topk(const dapq_shape* shape, const float* scores, int32_t width, int32_t budget,
+                   const int32_t* budget_per_seq, int32_t* idx, int32_t* count, float* pooled, void* stream);
+
 /* Sec. 4.2 — cache pruning: copies the retained K and V rows, bit for bit, into the compact cache;
  * nothing of the pseudo segment is kept.  Rows past count are left untouched.
  * k_out / v_out must not overlap k / v. */

@@ -15,7 +15,7 @@ _lib = None
 
 EXPORTS = (
     "dapq_workspace_bytes", "dapq_last_error", "dapq_rope_apply", "dapq_score", "dapq_score_stats",
-    "dapq_score_accumulate", "dapq_score_stats_extend", "dapq_pool", "dapq_topk", "dapq_gather",
+    "dapq_score_accumulate", "dapq_score_stats_extend", "dapq_pool", "dapq_topk", "dapq_pool_topk", "dapq_gather",
 )
 
 
@@ -67,6 +67,7 @@ def load_library():
     lib.dapq_score_stats_extend.argtypes = [sp, vp, vp, i64, i64, i64, i64, vp, vp]
     lib.dapq_pool.argtypes = [sp, vp, vp, i32, vp]
     lib.dapq_topk.argtypes = [sp, vp, i32, vp, vp, vp, vp, sz, vp]
+    lib.dapq_pool_topk.argtypes = [sp, vp, i32, i32, vp, vp, vp, vp, vp]
     lib.dapq_gather.argtypes = [sp, vp, vp, vp, vp, i32, vp, vp, vp]
     for name in EXPORTS[2:]:
         getattr(lib, name).restype = C.c_int
@@ -149,6 +150,11 @@ def dapq_topk(shape, pooled, budget, budget_per_seq, idx, count, workspace=None,
                                     _ptr(count), _ptr(workspace),
                                     0 if workspace is None else workspace.numel() * workspace.element_size(),
                                     _stream(stream)))
+
+
+def dapq_pool_topk(shape, scores, width, budget, budget_per_seq, idx, count, pooled=None, stream=None):
+    _check(load_library().dapq_pool_topk(C.byref(shape), _ptr(scores), width, budget, _ptr(budget_per_seq), _ptr(idx),
+                                         _ptr(count), _ptr(pooled), _stream(stream)))
 
 
 def dapq_gather(shape, k, v, idx, count, budget, k_out, v_out, stream=None):

@@ -16,7 +16,9 @@
 //
 // Heads of up to 65536 keys (topk_reg_kernel) are read from HBM once into registers, thread t
 // owning the consecutive keys [t*KPT, (t+1)*KPT): every pass runs out of registers and the
-// compaction needs a single workgroup scan.  Longer heads (topk_stream_kernel) stage what fits in
+// compaction needs a single workgroup scan.  Because a thread holds a run of consecutive scores, the
+// same kernel can apply the max-pool that precedes selection (Sec. 1 / Sec. 5.1) on the way in
+// (dapq_pool_topk): three halo scores per side for the window of 7, no pooled array in HBM.  Longer heads (topk_stream_kernel) stage what fits in
 // LDS (36864 keys) or re-read the scores from L2 on every pass.
 #include "dapq_internal.h"
 
@@ -28,7 +30,8 @@ constexpr int kTopkWaves = kTopkThreads / 64;
 constexpr int kTopkLdsKeys = 36864;
 
 struct TopkParams {
-  const float* pooled;
+  const float* pooled;        // the scores selection runs on (the register variant can pool them itself)
+  float* pooled_out;          // register variant with a pooling radius: where to write the pooled scores, or NULL
   const int32_t* cu_seqlens;
   const int32_t* budget_per_seq;
   int32_t* idx;
@@ -50,7 +53,8 @@ struct TopkHead {
   const float* src;
   int32_t* out;
   int L, keep;
-  bool done;
+  bool done;     // nothing left to select
+  bool foreign;  // the head belongs to another launch
 };
 
 __device__ __forceinline__ TopkHead topk_head(const TopkParams& p) {
@@ -65,7 +69,8 @@ __device__ __forceinline__ TopkHead topk_head(const TopkParams& p) {
     start = p.cu_seqlens[b];
     hd.L = p.cu_seqlens[b + 1] - (int)start;
   }
-  if (hd.L < p.min_len || hd.L > p.max_len) {
+  hd.foreign = hd.L < p.min_len || hd.L > p.max_len;
+  if (hd.foreign) {
     hd.done = true;
     hd.keep = 0;
     hd.out = nullptr;
@@ -114,35 +119,52 @@ __device__ __forceinline__ void topk_pick_digit(const uint32_t* hist, uint32_t* 
   if (g0 < un && un <= g0 + h0) { bcast[0] = 4 * lane + 0; bcast[1] = un - g0; }
 }
 
-// ---- heads that fit in registers
-template <int KPT>
+// ---- heads that fit in registers.  R > 0: the input is the un-pooled score and the kernel applies
+// the max-pool of radius R itself (window clipped at the ends of the sequence) before selecting.
+template <int KPT, int R>
 __global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(TopkParams p) {
   __shared__ uint32_t hist[256];
   __shared__ uint32_t bcast[2];
   __shared__ uint32_t wave_gt[kTopkWaves], wave_eq[kTopkWaves];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const TopkHead hd = topk_head(p);
-  if (hd.done) return;
+  if (hd.foreign || (hd.done && p.pooled_out == nullptr)) return;  // a finished head may still owe its pooled scores
   const int L = hd.L;
 
   // thread t owns keys [t*KPT, t*KPT + KPT): registers i < nvalid hold a key.  (A layout with
   // contiguous rows per wave loads no faster here and makes the compaction twice as long.)
   const int j0 = tid * KPT;
   const int nvalid = L - j0 < 0 ? 0 : (L - j0 > KPT ? KPT : L - j0);
-  uint32_t key[KPT];
+  float ext[KPT + 2 * R];  // scores j0-R .. j0+KPT+R-1; -inf outside the sequence
   if (nvalid == KPT && (reinterpret_cast<uintptr_t>(hd.src + j0) & 15) == 0) {
 #pragma unroll
     for (int i = 0; i < KPT; i += 4) {
       const float4 v = *reinterpret_cast<const float4*>(hd.src + j0 + i);
-      key[i] = order_key(v.x);
-      key[i + 1] = order_key(v.y);
-      key[i + 2] = order_key(v.z);
-      key[i + 3] = order_key(v.w);
+      ext[R + i] = v.x;
+      ext[R + i + 1] = v.y;
+      ext[R + i + 2] = v.z;
+      ext[R + i + 3] = v.w;
     }
   } else {
 #pragma unroll
-    for (int i = 0; i < KPT; ++i) key[i] = i < nvalid ? order_key(hd.src[j0 + i]) : 0u;
+    for (int i = 0; i < KPT; ++i) ext[R + i] = i < nvalid ? hd.src[j0 + i] : -INFINITY;
   }
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int jl = j0 - R + r, jr = j0 + KPT + r;
+    ext[r] = (jl >= 0 && jl < L) ? hd.src[jl] : -INFINITY;
+    ext[R + KPT + r] = jr < L ? hd.src[jr] : -INFINITY;
+  }
+  uint32_t key[KPT];
+#pragma unroll
+  for (int i = 0; i < KPT; ++i) {
+    float m = ext[i];
+#pragma unroll
+    for (int t = 1; t <= 2 * R; ++t) m = fmaxf(m, ext[i + t]);
+    if (p.pooled_out != nullptr && i < nvalid) p.pooled_out[(hd.src - p.pooled) + j0 + i] = m;
+    key[i] = i < nvalid ? order_key(m) : 0u;
+  }
+  if (hd.done) return;
 
   // ---- radix select: threshold T = the keep-th largest key, need = how many keys == T to take
   uint32_t prefix = 0, mask = 0;
@@ -309,19 +331,39 @@ __global__ __launch_bounds__(kTopkThreads) void topk_stream_kernel(TopkParams p)
 
 using namespace dapq;
 
+namespace dapq {
+namespace {
+
+template <int R>
+void launch_reg(int kpt, dim3 grid, hipStream_t st, const TopkParams& p) {
+  if (kpt == 8) hipLaunchKernelGGL((topk_reg_kernel<8, R>), grid, dim3(kTopkThreads), 0, st, p);
+  else if (kpt == 32) hipLaunchKernelGGL((topk_reg_kernel<32, R>), grid, dim3(kTopkThreads), 0, st, p);
+  else hipLaunchKernelGGL((topk_reg_kernel<64, R>), grid, dim3(kTopkThreads), 0, st, p);
+}
+
+int topk_common_checks(const dapq_shape* shape, const float* in, int32_t budget, const int32_t* idx, const int32_t* count) {
+  int rc = check_shape(shape, false, false, false);
+  if (rc != DAPQ_OK) return rc;
+  DAPQ_REQUIRE(in != nullptr && idx != nullptr && count != nullptr, DAPQ_ERR_INVALID_ARG,
+               "scores, idx and count must not be NULL");
+  DAPQ_REQUIRE(budget >= 1, DAPQ_ERR_INVALID_ARG, "budget (%d) must be >= 1", budget);
+  DAPQ_REQUIRE(shape->batch <= 65535 && shape->n_layers <= 65535, DAPQ_ERR_UNSUPPORTED,
+               "batch and n_layers must be <= 65535");
+  return DAPQ_OK;
+}
+
+}  // namespace
+}  // namespace dapq
+
 extern "C" DAPQ_API int dapq_topk(const dapq_shape* shape, const float* pooled, int32_t budget, const int32_t* budget_per_seq,
                          int32_t* idx, int32_t* count, void* workspace, size_t workspace_bytes, void* stream) {
   (void)workspace;
   (void)workspace_bytes;
-  int rc = check_shape(shape, false, false, false);
+  int rc = topk_common_checks(shape, pooled, budget, idx, count);
   if (rc != DAPQ_OK) return rc;
-  DAPQ_REQUIRE(pooled != nullptr && idx != nullptr && count != nullptr, DAPQ_ERR_INVALID_ARG,
-               "pooled, idx and count must not be NULL");
-  DAPQ_REQUIRE(budget >= 1, DAPQ_ERR_INVALID_ARG, "budget (%d) must be >= 1", budget);
-  DAPQ_REQUIRE(shape->batch <= 65535 && shape->n_layers <= 65535, DAPQ_ERR_UNSUPPORTED,
-               "batch and n_layers must be <= 65535");
   TopkParams p;
   p.pooled = pooled;
+  p.pooled_out = nullptr;
   p.cu_seqlens = shape->cu_seqlens;
   p.budget_per_seq = budget_per_seq;
   p.idx = idx;
@@ -341,9 +383,7 @@ extern "C" DAPQ_API int dapq_topk(const dapq_shape* shape, const float* pooled, 
   const int64_t reg_max = (int64_t)kpt * kTopkThreads;
   p.min_len = 0;
   p.max_len = (int32_t)reg_max;
-  if (kpt == 8) hipLaunchKernelGGL(topk_reg_kernel<8>, grid, dim3(kTopkThreads), 0, st, p);
-  else if (kpt == 32) hipLaunchKernelGGL(topk_reg_kernel<32>, grid, dim3(kTopkThreads), 0, st, p);
-  else hipLaunchKernelGGL(topk_reg_kernel<64>, grid, dim3(kTopkThreads), 0, st, p);
+  launch_reg<0>(kpt, grid, st, p);
   DAPQ_HIP_LAUNCH_CHECK("topk_reg_kernel");
   if (longest > reg_max) {
     p.min_len = (int32_t)reg_max + 1;
@@ -355,5 +395,49 @@ extern "C" DAPQ_API int dapq_topk(const dapq_shape* shape, const float* pooled, 
     hipLaunchKernelGGL(topk_stream_kernel, grid, dim3(kTopkThreads), lds_bytes, st, p);
   }
   DAPQ_HIP_LAUNCH_CHECK("topk_stream_kernel");
+  return DAPQ_OK;
+}
+
+extern "C" DAPQ_API int dapq_pool_topk(const dapq_shape* shape, const float* scores, int32_t width, int32_t budget,
+                                       const int32_t* budget_per_seq, int32_t* idx, int32_t* count, float* pooled,
+                                       void* stream) {
+  int rc = topk_common_checks(shape, scores, budget, idx, count);
+  if (rc != DAPQ_OK) return rc;
+  DAPQ_REQUIRE(width >= 1 && width <= 63 && (width & 1) == 1, DAPQ_ERR_INVALID_ARG,
+               "width (%d) must be odd and in [1, 63]", width);
+  DAPQ_REQUIRE(pooled != scores, DAPQ_ERR_INVALID_ARG, "pooled must not alias scores");
+  // one kernel if every head fits the register variant and the window is one of the compiled radii
+  const int64_t longest = shape->cu_seqlens == nullptr ? shape->total_tokens / shape->batch : shape->total_tokens;
+  const bool fused = width <= 9 && longest <= 64 * kTopkThreads;
+  if (!fused) {
+    DAPQ_REQUIRE(pooled != nullptr, DAPQ_ERR_UNSUPPORTED,
+                 "width %d / head length %lld need the two-kernel path: pass a pooled buffer", width, (long long)longest);
+    if ((rc = dapq_pool(shape, scores, pooled, width, stream)) != DAPQ_OK) return rc;
+    return dapq_topk(shape, pooled, budget, budget_per_seq, idx, count, nullptr, 0, stream);
+  }
+  TopkParams p;
+  p.pooled = scores;
+  p.pooled_out = pooled;
+  p.cu_seqlens = shape->cu_seqlens;
+  p.budget_per_seq = budget_per_seq;
+  p.idx = idx;
+  p.count = count;
+  p.total_tokens = shape->total_tokens;
+  p.batch = shape->batch;
+  p.n_kv_heads = shape->n_kv_heads;
+  p.budget = budget;
+  p.min_len = 0;
+  p.max_len = INT32_MAX;
+  const int kpt = longest <= 8 * kTopkThreads ? 8 : (longest <= 32 * kTopkThreads ? 32 : 64);
+  const dim3 grid((unsigned)shape->n_kv_heads, (unsigned)shape->batch, (unsigned)shape->n_layers);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  switch (width / 2) {
+    case 0: launch_reg<0>(kpt, grid, st, p); break;
+    case 1: launch_reg<1>(kpt, grid, st, p); break;
+    case 2: launch_reg<2>(kpt, grid, st, p); break;
+    case 3: launch_reg<3>(kpt, grid, st, p); break;
+    default: launch_reg<4>(kpt, grid, st, p); break;
+  }
+  DAPQ_HIP_LAUNCH_CHECK("topk_reg_kernel");
   return DAPQ_OK;
 }

@@ -89,6 +89,14 @@ class Problem:
         D.dapq_topk(self.shape, P, budget, ps, idx, count, self.ws)
         return idx, count
 
+    def pool_topk(self, S, width, budget, per_seq=None, want_pooled=True):
+        idx = torch.full((self.layers, self.batch, self.Hkv, budget), -7, dtype=torch.int32, device=self.device)
+        count = torch.full((self.layers, self.batch, self.Hkv), -7, dtype=torch.int32, device=self.device)
+        ps = None if per_seq is None else torch.tensor(per_seq, dtype=torch.int32, device=self.device)
+        P = torch.full_like(S, float("nan")) if want_pooled else None
+        D.dapq_pool_topk(self.shape, S, width, budget, ps, idx, count, P)
+        return idx, count, P
+
     def gather(self, idx, count, budget):
         ko = torch.zeros((self.layers, self.batch, self.Hkv, budget, self.d), dtype=torch.bfloat16,
                          device=self.device)

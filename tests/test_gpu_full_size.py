@@ -80,7 +80,7 @@ def test_full_size_dense_workload(env, name, samples):
     announce(f"full size {name}: building the workload")
     host = {(li, kv): host_slice(w, seed, li, 0, kv, L) for (li, kv) in samples}
     ctx = bench.Context(w, seed, torch.device("cuda:0"),
-                        {(li, 0, kv): (k, v) for (li, kv), (q, k, v) in host.items()})
+                        {(li, 0, kv): (k, v) for (li, kv), (q, k, v) in host.items()}, keep_pooled=True)
     announce(f"full size {name}: one step")
     ctx.step()
     torch.cuda.synchronize()
@@ -120,7 +120,8 @@ def test_full_size_ragged_batch(env):
     announce(f"full size C3 (4 layers): lens {lens}")
     samples = [(0, 0, 0), (3, 7, 5), (2, 3, 2)]
     host = {(li, b, kv): host_slice(w, seed, li, b, kv, lens[b]) for (li, b, kv) in samples}
-    ctx = bench.Context(w, seed, torch.device("cuda:0"), {key: (k, v) for key, (q, k, v) in host.items()})
+    ctx = bench.Context(w, seed, torch.device("cuda:0"), {key: (k, v) for key, (q, k, v) in host.items()},
+                        keep_pooled=True)
     ctx.step()
     torch.cuda.synchronize()
     check_all_heads(ctx, w)

@@ -287,6 +287,39 @@ def test_topk_dense_lengths_around_the_variant_limits(H, L, batch):
         _topk_case(H, [L] * batch, budget, P, Hkv=1, dense=True)
 
 
+@pytest.mark.parametrize("width", [1, 3, 5, 7, 9, 11])
+@pytest.mark.parametrize("lens,dense", [([5000], True), ([8193] * 2, True), ([40000], True), ([70000], True),
+                                        ([1, 6, 100, 1025, 0, 4097], False)])
+def test_pool_topk_one_call_equals_the_two(H, width, lens, dense):
+    """dapq_pool_topk against the oracle's pool followed by its top-K, for windows the selection kernel
+    pools itself (<= 9), a window it does not (11), head lengths of every kernel variant and a ragged
+    batch (sequence ends clip the window); with and without the pooled output."""
+    announce(f"pool+topk width={width} lens={lens} dense={dense}")
+    r = np.random.default_rng(width * 1000 + len(lens))
+    tot = sum(lens)
+    S = (r.random((1, 2, tot)) ** 4).astype(np.float32)
+    S[0, 0] = np.round(S[0, 0] * 32) / 32                       # ties before pooling: longer plateaus after
+    q, k, v, cu = random_problem(4, 1, lens, 2, 2, 1)
+    prob = H.Problem(q, k, v, 2, None if dense else cu, "thd")
+    Sd = torch.from_numpy(S).cuda()
+    fusable = width <= 9 and (max(lens) if dense else tot) <= 65536
+    for budget, want_pooled in ((983, True), (64, False)):
+        if not want_pooled and not fusable:
+            with pytest.raises(H.D.DapqError):
+                prob.pool_topk(Sd, width, budget, None, False)
+            continue
+        idx, count, P = prob.pool_topk(Sd, width, budget, None, want_pooled)
+        idx, count = idx.cpu().numpy(), count.cpu().numpy()
+        for b in range(len(lens)):
+            for kv in range(2):
+                Pw = O.pool(S[0, kv, cu[b]:cu[b + 1]].astype(np.float64), width)
+                if want_pooled:
+                    assert np.array_equal(P[0, kv, cu[b]:cu[b + 1]].cpu().numpy().astype(np.float64), Pw), (b, kv)
+                n = min(budget, lens[b])
+                assert count[0, b, kv] == n
+                assert np.array_equal(idx[0, b, kv, :n], O.topk(Pw, budget)), (b, kv)
+
+
 # ----------------------------------------------------------------------------------------- gather
 @pytest.mark.parametrize("layout", ["thd", "hnd"])
 def test_gather_bit_exact(H, layout):
