@@ -127,10 +127,11 @@ class Context:
                 else:
                     k[li, s0:s1, kv].copy_(kt)
                     v[li, s0:s1, kv].copy_(vt)
-        # pseudo queries laid out [batch][layer][Hq][N][d] so that one rope call covers a sequence
-        self.q_pre = data["q"].permute(1, 0, 2, 3, 4).contiguous()
+        # pseudo queries laid out [layer][Hq][batch][N][d]: (sequence, pseudo token) is then one row axis and
+        # (layer, head) one head axis, so a single rope call covers the whole batch
+        self.q_pre = data["q"].permute(0, 2, 1, 3, 4).contiguous()
         self.q = torch.empty_like(self.q_pre)
-        qstr = (Hq * N * d, nl * Hq * N * d, N * d, d)
+        qstr = (Hq * B * N * d, N * d, B * N * d, d)
         self.shape = D.make_shape(n_layers=nl, batch=B, n_q_heads=Hq, n_kv_heads=Hkv, n_pseudo=N,
                                   total_tokens=tokens, cu_seqlens=self.cu, k_strides=kstr, v_strides=kstr,
                                   q_strides=qstr, scale=w.scale)
@@ -145,7 +146,7 @@ class Context:
         self.count = torch.zeros((nl, B, Hkv), dtype=torch.int32, device=dev)
         self.k_out = torch.zeros((nl, B, Hkv, w.budget, d), dtype=torch.bfloat16, device=dev)
         self.v_out = torch.zeros_like(self.k_out)
-        self.q_pos = data["q_pos"]
+        self.q_pos = data["q_pos"].reshape(-1).contiguous()
         self.stream = torch.cuda.current_stream()
         self.key_units = nl * Hkv * tokens
 
@@ -159,8 +160,7 @@ class Context:
             if events is not None:
                 events[i].record(stream)
         mark(0)
-        for b in range(w.batch):
-            D.dapq_rope_apply(self.q_pre[b], self.q[b], self.q_pos[b], N, nl * Hq, d, d, N * d, w.theta, 0, stream)
+        D.dapq_rope_apply(self.q_pre, self.q, self.q_pos, w.batch * N, nl * Hq, d, d, w.batch * N * d, w.theta, 0, stream)
         mark(1)
         D.dapq_score_stats(self.shape, self.q, self.k, self.lse2, self.ws, stream)
         mark(2)
@@ -248,7 +248,7 @@ def main():
     }
     ncpu = args.cpu_layers
     if ncpu is None:
-        ncpu = max(1, min(nl, int(round(6 * (32768 * 8 * 256) / (lens[0] * Hkv * (Hq // Hkv) * N)))))
+        ncpu = max(1, min(nl, int(round(24 * (32768 * 8 * 256) / (lens[0] * Hkv * (Hq // Hkv) * N)))))
     if ncpu > 0:
         out["cpu_baseline"] = cpu_baseline(w, args.seed, min(ncpu, nl))
     print(json.dumps(out), flush=True)
