@@ -1,10 +1,14 @@
 // Position assignment (Sec. 4.1): rotary embedding of bf16 vectors at given absolute positions.
 // The pseudo queries get positions L_p .. L_p+N-1, the positions of the first N decode steps.
 //
-// One thread owns one (row, channel pair) and a run of up to 8 heads: it evaluates the angle
+// One thread owns one (row, channel pair) and a run of heads: it evaluates the angle
 // pos * theta^(-2c/d) and its sine / cosine once in fp64 and then walks its heads, so the
-// transcendental work is shared by the heads of a run.  fp64 keeps the angle exact enough at positions beyond 10^5 (an fp32
-// product pos * omega would be off by ~1e-2 rad there); the result is rounded to bf16 once.
+// transcendental work (more than ten times the work of one rotation) is shared by the heads of a
+// run; runs are 8 heads long, longer (up to 64) while the launch still has thousands of waves.
+// fp64 keeps the angle exact enough at positions beyond 10^5 (an fp32 product pos * omega would be
+// off by ~1e-2 rad there); the rotation is done in fp64 as well and rounded to bf16 once, which is
+// what makes the result equal to a float64 evaluation bit for bit, and what the kernel's time goes
+// into (about 35 instructions per rotated pair).
 #include <math.h>
 
 #include "dapq_internal.h"
@@ -28,11 +32,9 @@ __device__ __forceinline__ uint16_t f64_to_bf16(double x) {
   return (uint16_t)(hi + (up ? 1u : 0u));
 }
 
-constexpr int kHeadsPerThread = 8;
-
 __global__ void rope_kernel(const uint16_t* __restrict__ x_in, uint16_t* x_out, const int32_t* __restrict__ pos,
                             int64_t rows, int heads, int head_dim, int64_t stride_row, int64_t stride_head,
-                            double neg_log2_theta_2_over_d, int pairing) {
+                            double neg_log2_theta_2_over_d, int pairing, int heads_per_thread) {
   const int half = head_dim >> 1;
   const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (gid >= rows * half) return;
@@ -45,8 +47,8 @@ __global__ void rope_kernel(const uint16_t* __restrict__ x_in, uint16_t* x_out, 
   const int ib = pairing == 0 ? c + half : 2 * c + 1;
   const uint16_t* src = x_in + row * stride_row;
   uint16_t* dst = x_out + row * stride_row;
-  const int hd0 = blockIdx.y * kHeadsPerThread;
-  const int hd1 = hd0 + kHeadsPerThread < heads ? hd0 + kHeadsPerThread : heads;
+  const int hd0 = blockIdx.y * heads_per_thread;
+  const int hd1 = hd0 + heads_per_thread < heads ? hd0 + heads_per_thread : heads;
   for (int hd = hd0; hd < hd1; ++hd) {
     const double a = bf16_to_f64(src[(int64_t)hd * stride_head + ia]);
     const double b = bf16_to_f64(src[(int64_t)hd * stride_head + ib]);
@@ -77,13 +79,15 @@ extern "C" DAPQ_API int dapq_rope_apply(const void* x_in, void* x_out, const int
   const int64_t work = rows * (head_dim / 2);
   DAPQ_REQUIRE(work / 256 < ((int64_t)1 << 31), DAPQ_ERR_UNSUPPORTED, "too many rows");
   if (work == 0) return DAPQ_OK;
-  const int64_t head_runs = ((int64_t)heads + kHeadsPerThread - 1) / kHeadsPerThread;
-  DAPQ_REQUIRE(head_runs <= 65535, DAPQ_ERR_UNSUPPORTED, "heads (%d) exceeds %d", heads, 65535 * kHeadsPerThread);
+  int hpt = 8;
+  while (hpt < 64 && hpt * 2 <= heads && (work / 64) * ((heads + 2 * hpt - 1) / (2 * hpt)) >= 4096) hpt *= 2;
+  const int64_t head_runs = ((int64_t)heads + hpt - 1) / hpt;
+  DAPQ_REQUIRE(head_runs <= 65535, DAPQ_ERR_UNSUPPORTED, "heads (%d) exceeds %d", heads, 65535 * hpt);
   const double e = -2.0 * log2(theta) / (double)head_dim;
   hipLaunchKernelGGL(rope_kernel, dim3((unsigned)((work + 255) / 256), (unsigned)head_runs), dim3(256), 0,
                      static_cast<hipStream_t>(stream),
                      static_cast<const uint16_t*>(x_in), static_cast<uint16_t*>(x_out), pos, rows, heads, head_dim,
-                     stride_row, stride_head, e, pairing);
+                     stride_row, stride_head, e, pairing, hpt);
   DAPQ_HIP_LAUNCH_CHECK("rope_kernel");
   return DAPQ_OK;
 }
