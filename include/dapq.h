@@ -25,7 +25,8 @@
  *   K, V  prompt keys / values, bf16, keys already rotated to their positions:
  *        k[layer*k_stride_layer + seq*k_stride_seq + kv_head*k_stride_head + t*k_stride_token + c]
  *        where t = cu_seqlens[seq] + j is the packed token index of key j of sequence seq
- *        (set k_stride_seq = 0 for a packed [tokens][heads][d] layout).
+ *        (k_stride_seq comes on top of the packed token offset: 0 for a packed [tokens][heads][d]
+ *        layout, g*k_stride_token if g rows that are not part of the batch follow every sequence).
  *   scores / pooled   fp32 [n_layers][n_kv_heads][total_tokens]   (packed token index)
  *   idx     int32 [n_layers][batch][n_kv_heads][budget]   positions j inside the sequence, ascending
  *   count   int32 [n_layers][batch][n_kv_heads]           = min(budget of the sequence, L_p)
@@ -150,6 +151,16 @@ int dapq_pool_topk(const dapq_shape* shape, const float* scores, int32_t width, 
  * k_out / v_out must not overlap k / v. */
 int dapq_gather(const dapq_shape* shape, const void* k, const void* v, const int32_t* idx,
                 const int32_t* count, int32_t budget, void* k_out, void* v_out, void* stream);
+
+/* Sec. 3.3, recall of an eviction decision: Recall_W = |M_gold ∩ M_pred| / |M_gold| for every
+ * (layer, sequence, KV head).  Both index sets are in dapq_topk's format (ascending, distinct
+ * positions; idx_* int32 [n_layers][batch][n_kv_heads][budget_*], count_* int32
+ * [n_layers][batch][n_kv_heads]; only the first count entries of a head are read).
+ *   common   out, int32 [n_layers][batch][n_kv_heads]: |M_gold ∩ M_pred|
+ *   recall   out, fp32 same shape, or NULL: common / count_gold (0 where count_gold is 0) */
+int dapq_recall(const dapq_shape* shape, const int32_t* idx_gold, const int32_t* count_gold, int32_t budget_gold,
+                const int32_t* idx_pred, const int32_t* count_pred, int32_t budget_pred, int32_t* common,
+                float* recall, void* stream);
 
 #ifdef __cplusplus
 }

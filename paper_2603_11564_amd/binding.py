@@ -15,7 +15,7 @@ _lib = None
 
 EXPORTS = (
     "dapq_workspace_bytes", "dapq_last_error", "dapq_rope_apply", "dapq_score", "dapq_score_stats",
-    "dapq_score_accumulate", "dapq_score_stats_extend", "dapq_pool", "dapq_topk", "dapq_pool_topk", "dapq_gather",
+    "dapq_score_accumulate", "dapq_score_stats_extend", "dapq_pool", "dapq_topk", "dapq_pool_topk", "dapq_gather", "dapq_recall",
 )
 
 
@@ -69,6 +69,7 @@ def load_library():
     lib.dapq_topk.argtypes = [sp, vp, i32, vp, vp, vp, vp, sz, vp]
     lib.dapq_pool_topk.argtypes = [sp, vp, i32, i32, vp, vp, vp, vp, vp]
     lib.dapq_gather.argtypes = [sp, vp, vp, vp, vp, i32, vp, vp, vp]
+    lib.dapq_recall.argtypes = [sp, vp, vp, i32, vp, vp, i32, vp, vp, vp]
     for name in EXPORTS[2:]:
         getattr(lib, name).restype = C.c_int
     _lib = lib
@@ -160,3 +161,9 @@ def dapq_pool_topk(shape, scores, width, budget, budget_per_seq, idx, count, poo
 def dapq_gather(shape, k, v, idx, count, budget, k_out, v_out, stream=None):
     _check(load_library().dapq_gather(C.byref(shape), _ptr(k), _ptr(v), _ptr(idx), _ptr(count), budget,
                                       _ptr(k_out), _ptr(v_out), _stream(stream)))
+
+
+def dapq_recall(shape, idx_gold, count_gold, budget_gold, idx_pred, count_pred, budget_pred, common, recall=None,
+                stream=None):
+    _check(load_library().dapq_recall(C.byref(shape), _ptr(idx_gold), _ptr(count_gold), budget_gold, _ptr(idx_pred),
+                                      _ptr(count_pred), budget_pred, _ptr(common), _ptr(recall), _stream(stream)))

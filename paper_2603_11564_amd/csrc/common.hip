@@ -120,7 +120,7 @@ int make_score_plan(const dapq_shape* s, ScorePlan* p) {
   p->off_lse2 = off;
   off = align_up(off + sizeof(float) * (size_t)s->n_layers * s->batch * s->n_q_heads * s->n_pseudo, 256);
   p->off_partial = off;
-  if (p->n_groups > 1) off = align_up(off + sizeof(float) * (size_t)p->n_groups * (size_t)heads * (size_t)s->total_tokens, 256);
+  if (p->n_groups > 1) off = align_up(off + sizeof(float) * (size_t)(p->n_groups - 1) * (size_t)heads * (size_t)s->total_tokens, 256);
   p->total_bytes = off;
   return DAPQ_OK;
 }

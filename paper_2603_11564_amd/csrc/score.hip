@@ -12,7 +12,7 @@
 // walks its own chunk of keys of one (layer, sequence, KV head).  Nothing is shared between waves:
 // no barrier anywhere, no cross-wave reduction.  Heads with more than 256 rows are split into row
 // groups (grid.y): pass 1 needs nothing more (its sums are per row), pass 2 writes one plane of
-// column sums per group and a small kernel adds the planes in group order.
+// column sums per group (group 0 into the result) and a small kernel adds the planes in group order.
 // Keys arrive through a per-wave ring of 32-key sub-blocks in LDS (buffer_load_dwordx4 ... lds, five
 // slots of 8 KB: four sub-blocks = 32 KB in flight per wave, 128 KB per compute unit; 16-byte
 // chunks XOR-swizzled so that the MFMA operand reads are bank-conflict free), and every fragment is
@@ -52,7 +52,7 @@ struct ScoreParams {
   float2* parts;              // [layer*Hkv][max_chunks][rows_pad] (reference, sum) in the log2 domain
   float* lse2;                // [layer][batch][Hq][N]
   float* scores;              // [layer][Hkv][total_tokens]
-  float* partial;             // [n_groups][layer][Hkv][total_tokens] per-row-group column sums (n_groups > 1)
+  float* partial;             // [n_groups-1][layer][Hkv][total_tokens] column sums of row groups 1.. (n_groups > 1)
   int64_t k_stride_layer, k_stride_seq, k_stride_head, k_stride_token;
   int64_t q_stride_layer, q_stride_seq, q_stride_head, q_stride_row;
   int64_t total_tokens;
@@ -554,8 +554,10 @@ __global__ __launch_bounds__(64, 1) void score_wave_pass2_kernel(ScoreParams p) 
                                       (int64_t)kv * p.k_stride_head + w.tok0 * p.k_stride_token);
   const float* lse = p.lse2 + (((int64_t)layer * p.batch + w.seq) * p.n_q_heads + (int64_t)kv * p.group) * p.n_pseudo;
   const int gbase = blockIdx.y * (NRB * 32);  // first row of this wave's row group
-  // with several row groups each writes its own plane of column sums; a small kernel adds them up
-  float* plane = p.n_groups > 1 ? p.partial + (int64_t)blockIdx.y * p.n_layers * p.n_kv_heads * p.total_tokens : p.scores;
+  // with several row groups each writes its own plane of column sums (group 0 straight into the
+  // result); a small kernel adds the others onto it
+  float* plane = blockIdx.y == 0 ? p.scores
+                                 : p.partial + (int64_t)(blockIdx.y - 1) * p.n_layers * p.n_kv_heads * p.total_tokens;
   float* out = plane + ((int64_t)layer * p.n_kv_heads + kv) * p.total_tokens + w.tok0;
   const int nsubs = (w.nkeys + 31) / 32;
   unsigned voff[4];
@@ -642,12 +644,13 @@ __global__ __launch_bounds__(64, 1) void score_wave_pseudo_kernel(ScoreParams p,
   }
 }
 
-// S = sum over row groups of their planes of column sums, in group order.
+// S = sum over row groups of their planes of column sums, in group order; group 0's plane is the
+// result array itself.
 __global__ void score_group_sum_kernel(const float* partial, float* scores, int64_t count, int n_groups) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < count; e += stride) {
-    float s = partial[e];
-    for (int g = 1; g < n_groups; ++g) s += partial[(int64_t)g * count + e];
+    float s = scores[e];
+    for (int g = 1; g < n_groups; ++g) s += partial[(int64_t)(g - 1) * count + e];
     scores[e] = s;
   }
 }

@@ -426,3 +426,79 @@ def test_chain_budget_edges(H):
     compare_chain(H, prob, q, k, v, 64, 7)
     compare_chain(H, prob, q, k, v, 1, 7)
     compare_chain(H, prob, q, k, v, 1000, 7, per_seq=[2, 1000, 0])
+
+
+# ----------------------------------------------------------------------------------------- recall, observation window
+def test_recall_counts_match_oracle(H):
+    """dapq_recall on index sets in dapq_topk's format against the set definition of Sec. 3.3."""
+    announce("recall of retained sets")
+    r = np.random.default_rng(21)
+    layers, B, Hkv, L = 2, 3, 2, 5000
+    bg, bp = 700, 300
+    q, k, v, cu = random_problem(22, layers, [L] * B, Hkv, Hkv, 1)
+    prob = H.Problem(q, k, v, Hkv, None, "thd")
+    idx_g = np.full((layers, B, Hkv, bg), -3, dtype=np.int32)
+    idx_p = np.full((layers, B, Hkv, bp), -3, dtype=np.int32)
+    cnt_g = np.zeros((layers, B, Hkv), dtype=np.int32)
+    cnt_p = np.zeros_like(cnt_g)
+    for l in range(layers):
+        for b in range(B):
+            for kv in range(Hkv):
+                ng = [bg, 1, 257, 0][(l + b + kv) % 4]
+                npred = [bp, 0, 64][(l + 2 * b + kv) % 3]
+                pool_ = r.choice(L, size=900, replace=False)             # both sets drawn from 900 positions: they overlap
+                cnt_g[l, b, kv], cnt_p[l, b, kv] = ng, npred
+                idx_g[l, b, kv, :ng] = np.sort(r.choice(pool_, size=ng, replace=False))
+                idx_p[l, b, kv, :npred] = np.sort(r.choice(pool_, size=npred, replace=False))
+    common = torch.full((layers, B, Hkv), -1, dtype=torch.int32, device="cuda")
+    rec = torch.full((layers, B, Hkv), float("nan"), dtype=torch.float32, device="cuda")
+    H.D.dapq_recall(prob.shape, torch.from_numpy(idx_g).cuda(), torch.from_numpy(cnt_g).cuda(), bg,
+                    torch.from_numpy(idx_p).cuda(), torch.from_numpy(cnt_p).cuda(), bp, common, rec)
+    common, rec = common.cpu().numpy(), rec.cpu().numpy()
+    for l in range(layers):
+        for b in range(B):
+            for kv in range(Hkv):
+                ng, npred = cnt_g[l, b, kv], cnt_p[l, b, kv]
+                want = len(set(idx_g[l, b, kv, :ng].tolist()) & set(idx_p[l, b, kv, :npred].tolist()))
+                assert common[l, b, kv] == want
+                if ng > 0:
+                    assert rec[l, b, kv] == np.float32(want) / np.float32(ng)
+                    assert abs(rec[l, b, kv] - O.recall(idx_g[l, b, kv, :ng], idx_p[l, b, kv, :npred])) < 1e-6
+                else:
+                    assert rec[l, b, kv] == 0.0
+
+
+def test_observation_window_scores_by_composition(H):
+    """The observation window of Sec. 1 / Sec. 3.3 (the last N prompt tokens as queries, causal inside the
+    window) needs no kernel of its own: pass 1 over the keys before the window, the causal block of the
+    window's own keys via dapq_score_stats_extend, pass 2 over the keys before the window.  The result is
+    the accumulated attention the window pays to every earlier key."""
+    announce("observation window by composition")
+    layers, B, Hq, Hkv, N, L, d = 2, 2, 4, 2, 16, 300, 128
+    r = np.random.default_rng(23)
+    k_bits = W.to_bf16_bits(r.standard_normal((layers, B * L, Hkv, d)))
+    q_bits = W.to_bf16_bits(r.standard_normal((layers, B, Hq, N, d)))          # queries of the last N tokens
+    k = H.dev_bf16(k_bits)
+    q = H.dev_bf16(q_bits)
+    Lp = L - N                                                                   # keys before the window
+    tok, seq, lay = Hkv * d, L * Hkv * d, B * L * Hkv * d
+    # the batch as the library sees it: B sequences of Lp keys, each followed by N rows (the window) it skips
+    shape = H.D.make_shape(n_layers=layers, batch=B, n_q_heads=Hq, n_kv_heads=Hkv, n_pseudo=N, total_tokens=B * Lp,
+                           k_strides=(lay, N * tok, d, tok), v_strides=(lay, N * tok, d, tok),
+                           q_strides=(B * Hq * N * d, Hq * N * d, N * d, d))
+    ws = torch.empty(max(H.D.workspace_bytes(shape), 256), dtype=torch.uint8, device="cuda")
+    lse = torch.empty((layers, B, Hq, N), dtype=torch.float32, device="cuda")
+    S = torch.full((layers, Hkv, B * Lp), float("nan"), dtype=torch.float32, device="cuda")
+    H.D.dapq_score_stats(shape, q, k, lse, ws)
+    window_keys = k.view(layers, B, L, Hkv, d)[:, :, Lp:]                       # a view: same memory, offset Lp tokens
+    H.D.dapq_score_stats_extend(shape, q, window_keys, (lay, seq, d, tok), lse)
+    H.D.dapq_score_accumulate(shape, q, k, lse, S, ws)
+    S = S.cpu().numpy()
+    g = Hq // Hkv
+    kf = O.bf16_bits_to_f64(k_bits).reshape(layers, B, L, Hkv, d)
+    for l in range(layers):
+        for b in range(B):
+            for kv in range(Hkv):
+                want = O.score_head(O.bf16_bits_to_f64(q_bits[l, b, kv * g:(kv + 1) * g]), kf[l, b, :Lp, kv], None,
+                                    kf[l, b, Lp:, kv])
+                H.assert_scores_close(S[l, kv, b * Lp:(b + 1) * Lp], want, f"window S[{l},{b},{kv}]")
