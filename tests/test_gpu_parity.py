@@ -77,6 +77,8 @@ SCORE_CASES = [
     ("R=128", 1, [515], 8, 2, 32, "thd"),
     ("R=512 two super-groups", 1, [400, 260], 8, 2, 128, "thd"),
     ("R=640 g=5", 1, [257], 5, 1, 128, "thd"),
+    ("R=2048 eight row groups", 1, [300], 4, 1, 512, "thd"),
+    ("R=512 several chunks", 1, [5000], 8, 2, 128, "hnd"),
     ("long chunked", 1, [9000], 4, 1, 64, "hnd"),
     ("ragged with empty", 1, [130, 0, 64, 0], 4, 2, 16, "thd"),
 ]
