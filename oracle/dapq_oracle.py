@@ -36,6 +36,7 @@ import numpy as np
 __all__ = [
     "bf16_bits_to_f64", "f64_to_bf16_bits", "rope_rotate", "rope_apply", "attention", "score_head",
     "score", "pool", "topk", "gather", "compress", "recall", "topk_margin", "attention_extended",
+    "decode_attention",
 ]
 
 
@@ -293,6 +294,15 @@ def compress(q_bits, k_bits, v_bits, n_kv_heads, Kb, cu_seqlens=None, width=7, s
 # --------------------------------------------------------------------------------------
 # Sec. 3.3: recall of a predicted retained set against a gold one
 # --------------------------------------------------------------------------------------
+def decode_attention(q, k_cache, v_cache, scale=None) -> np.ndarray:
+    """One decode step over a cache (Sec. 4.2, last paragraph: decoding starts at position L_p and uses
+    only the compressed cache): o = Attention(q, K) V with Attention = softmax(q K^T / sqrt(d_k))
+    (App. C.1).  q: float64 [rows, d] (already rotated to the decode position); k_cache, v_cache:
+    float64 [n, d]; returns float64 [rows, d]."""
+    alpha = attention(q, k_cache, scale)
+    return alpha @ np.asarray(v_cache, dtype=np.float64)
+
+
 def recall(M_gold, M_pred) -> float:
     """|M_gold ∩ M_pred| / |M_gold| (Sec. 3.3, recall equation)."""
     gold = set(int(v) for v in M_gold)

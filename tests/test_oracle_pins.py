@@ -442,3 +442,50 @@ def test_extended_score_batch_layout():
     want = O.score_head(O.bf16_bits_to_f64(qb[l, b, 2:4]), O.bf16_bits_to_f64(kb[l, 5:14, kv]), None,
                         O.bf16_bits_to_f64(kpb[l, b, kv]))
     assert np.array_equal(S[l, kv, 5:14], want)
+
+
+# ------------------------------------------------------------------ decode step over a cache (Sec. 4.2, last paragraph)
+def test_decode_attention_closed_forms():
+    r = rng(80)
+    d = 8
+    q = r.standard_normal((3, d))
+    v = r.standard_normal((5, d))
+    # one key: the output is its value, whatever the logit
+    assert np.allclose(O.decode_attention(q, r.standard_normal((1, d)), v[:1]), np.tile(v[0], (3, 1)), rtol=1e-14)
+    # identical keys: uniform weights, the output is the mean value
+    key = r.standard_normal(d)
+    assert np.allclose(O.decode_attention(q, np.tile(key, (5, 1)), v), np.tile(v.mean(axis=0), (3, 1)), rtol=1e-13)
+    # two keys: logistic weight on the first (App. C.1 with d_k = 8)
+    k2 = r.standard_normal((2, d))
+    w = 1.0 / (1.0 + np.exp(-(q @ (k2[0] - k2[1])) / math.sqrt(d)))
+    want = w[:, None] * v[0] + (1 - w)[:, None] * v[1]
+    assert np.allclose(O.decode_attention(q, k2, v[:2]), want, rtol=1e-13)
+
+
+def test_decode_attention_matches_torch_sdpa():
+    r = rng(81)
+    q, k, v = r.standard_normal((4, 16)), r.standard_normal((50, 16)), r.standard_normal((50, 16))
+    want = torch.nn.functional.scaled_dot_product_attention(torch.from_numpy(q)[None], torch.from_numpy(k)[None],
+                                                            torch.from_numpy(v)[None])[0].numpy()
+    assert np.allclose(O.decode_attention(q, k, v), want, rtol=1e-12, atol=1e-15)
+    # every output channel is a convex combination of that channel's values
+    o = O.decode_attention(q, k, v)
+    assert np.all(o <= v.max(axis=0) + 1e-12) and np.all(o >= v.min(axis=0) - 1e-12)
+
+
+def test_decode_over_compact_cache_is_within_the_dropped_mass_bound():
+    # dropping keys that hold attention mass m moves the output by at most 2 m max|v|:
+    # o_full = sum_kept a_j v_j + sum_drop a_j v_j and o_compact = sum_kept a_j v_j / (1 - m)
+    r = rng(82)
+    L, d, Kb = 400, 16, 60
+    q = r.standard_normal((1, d)) * 3.0
+    k, v = r.standard_normal((L, d)), r.standard_normal((L, d))
+    alpha = O.attention(q, k)[0]
+    keep = O.topk(alpha, Kb)
+    m = 1.0 - alpha[keep].sum()
+    diff = np.abs(O.decode_attention(q, k[keep], v[keep]) - O.decode_attention(q, k, v)).max()
+    assert 0 < m < 1 and diff <= 2 * m * np.abs(v).max()
+    # and keeping the keys with the LEAST mass is far worse than keeping those with the most
+    worst = np.argsort(alpha, kind="stable")[:Kb]
+    diff_worst = np.abs(O.decode_attention(q, k[worst], v[worst]) - O.decode_attention(q, k, v)).max()
+    assert diff_worst > 3 * diff
