@@ -44,6 +44,9 @@ def parse():
     ap.add_argument("--layers", type=int, default=None, help="override the layer count (fits memory / quick runs)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--cpu-layers", type=int, default=None, help="layers the CPU oracle baseline runs (0 = skip)")
+    ap.add_argument("--extras", action="store_true",
+                    help="also time the entry points around the step (extended normaliser, decode over the compact "
+                         "cache, recall); reported under extras_ms, not part of value")
     return ap.parse_args()
 
 
@@ -172,6 +175,40 @@ class Context:
         mark(5)
 
 
+def time_extras(ctx, reps):
+    """Event-timed averages of the entry points that sit around the eviction step, on the step's own outputs."""
+    import torch
+    D, w, dev, stream = ctx.D, ctx.w, ctx.dev, ctx.stream
+    d, Hq, Hkv, N, nl, B = w.head_dim, w.n_q_heads, w.n_kv_heads, w.n_pseudo, w.n_layers, w.batch
+    g = torch.Generator(device=dev).manual_seed(1)
+    kp = torch.randn((nl, B, Hkv, N, d), generator=g, device=dev).to(torch.bfloat16)
+    qd = torch.randn((nl, B, Hq, d), generator=g, device=dev).to(torch.bfloat16)
+    dec = torch.empty((nl, B, Hq, d), dtype=torch.float32, device=dev)
+    common = torch.empty((nl, B, Hkv), dtype=torch.int32, device=dev)
+    rec = torch.empty((nl, B, Hkv), dtype=torch.float32, device=dev)
+    lse = ctx.lse2.clone()
+    calls = {
+        "score_stats_extend": lambda: D.dapq_score_stats_extend(ctx.shape, ctx.q, kp, (B * Hkv * N * d, Hkv * N * d, N * d, d),
+                                                                lse, stream),
+        "recall": lambda: D.dapq_recall(ctx.shape, ctx.idx, ctx.count, w.budget, ctx.idx, ctx.count, w.budget, common, rec,
+                                        stream),
+    }
+    if w.budget <= 8192:
+        calls["decode_attention"] = lambda: D.dapq_decode_attention(ctx.shape, qd, ctx.k_out, ctx.v_out, ctx.count, w.budget,
+                                                                    dec, stream)
+    res = {}
+    for name, fn in calls.items():
+        fn()
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        evs[0].record(stream)
+        for i in range(reps):
+            fn()
+            evs[i + 1].record(stream)
+        torch.cuda.synchronize()
+        res[name] = sum(evs[i].elapsed_time(evs[i + 1]) for i in range(reps)) / reps
+    return res
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -246,6 +283,8 @@ def main():
         "kernel_ms": per,
         "roofline": roofline,
     }
+    if args.extras:
+        out["extras_ms"] = time_extras(ctx, args.steps)
     ncpu = args.cpu_layers
     if ncpu is None:
         ncpu = max(1, min(nl, int(round(24 * (32768 * 8 * 256) / (lens[0] * Hkv * (Hq // Hkv) * N)))))

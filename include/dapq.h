@@ -162,6 +162,17 @@ int dapq_recall(const dapq_shape* shape, const int32_t* idx_gold, const int32_t*
                 const int32_t* idx_pred, const int32_t* count_pred, int32_t budget_pred, int32_t* common,
                 float* recall, void* stream);
 
+/* Sec. 4.2, last paragraph: after pruning, decoding starts at position L_p and uses only the compressed
+ * cache.  One decode step of attention over the compact cache dapq_gather wrote:
+ *   out[layer][seq][h] = softmax(q K_c^T * scale) V_c   over the first count rows of KV head h / (H_q/H_kv)
+ *   q_decode   device, bf16 [n_layers][batch][n_q_heads][head_dim], rotated to the decode position
+ *   k_cache, v_cache   device, bf16 [n_layers][batch][n_kv_heads][budget][head_dim] (keys rotated), 16-byte aligned
+ *   count      device, int32 [n_layers][batch][n_kv_heads]
+ *   out        device, fp32 [n_layers][batch][n_q_heads][head_dim]; zeros where count is 0
+ * budget <= 8192.  Only n_layers, batch, the head counts and scale of shape are used. */
+int dapq_decode_attention(const dapq_shape* shape, const void* q_decode, const void* k_cache, const void* v_cache,
+                          const int32_t* count, int32_t budget, float* out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

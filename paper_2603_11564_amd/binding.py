@@ -15,7 +15,7 @@ _lib = None
 
 EXPORTS = (
     "dapq_workspace_bytes", "dapq_last_error", "dapq_rope_apply", "dapq_score", "dapq_score_stats",
-    "dapq_score_accumulate", "dapq_score_stats_extend", "dapq_pool", "dapq_topk", "dapq_pool_topk", "dapq_gather", "dapq_recall",
+    "dapq_score_accumulate", "dapq_score_stats_extend", "dapq_pool", "dapq_topk", "dapq_pool_topk", "dapq_gather", "dapq_recall", "dapq_decode_attention",
 )
 
 
@@ -70,6 +70,7 @@ def load_library():
     lib.dapq_pool_topk.argtypes = [sp, vp, i32, i32, vp, vp, vp, vp, vp]
     lib.dapq_gather.argtypes = [sp, vp, vp, vp, vp, i32, vp, vp, vp]
     lib.dapq_recall.argtypes = [sp, vp, vp, i32, vp, vp, i32, vp, vp, vp]
+    lib.dapq_decode_attention.argtypes = [sp, vp, vp, vp, vp, i32, vp, vp]
     for name in EXPORTS[2:]:
         getattr(lib, name).restype = C.c_int
     _lib = lib
@@ -167,3 +168,8 @@ def dapq_recall(shape, idx_gold, count_gold, budget_gold, idx_pred, count_pred, 
                 stream=None):
     _check(load_library().dapq_recall(C.byref(shape), _ptr(idx_gold), _ptr(count_gold), budget_gold, _ptr(idx_pred),
                                       _ptr(count_pred), budget_pred, _ptr(common), _ptr(recall), _stream(stream)))
+
+
+def dapq_decode_attention(shape, q_decode, k_cache, v_cache, count, budget, out, stream=None):
+    _check(load_library().dapq_decode_attention(C.byref(shape), _ptr(q_decode), _ptr(k_cache), _ptr(v_cache), _ptr(count),
+                                                budget, _ptr(out), _stream(stream)))

@@ -504,3 +504,45 @@ def test_observation_window_scores_by_composition(H):
                 want = O.score_head(O.bf16_bits_to_f64(q_bits[l, b, kv * g:(kv + 1) * g]), kf[l, b, :Lp, kv], None,
                                     kf[l, b, Lp:, kv])
                 H.assert_scores_close(S[l, kv, b * Lp:(b + 1) * Lp], want, f"window S[{l},{b},{kv}]")
+
+
+# ----------------------------------------------------------------------------------------- decode over the compact cache
+@pytest.mark.parametrize("Hq,Hkv", [(8, 2), (5, 1), (2, 2)])
+def test_decode_step_over_the_compact_cache(H, Hq, Hkv):
+    """Sec. 4.2, last paragraph: decoding uses only the compressed cache.  Eviction chain on the GPU, then one
+    decode step of attention over the compact cache, against the oracle's attention over the same retained
+    rows; and the distance to attention over the full cache stays inside the dropped-mass bound 2 m max|v|."""
+    announce(f"decode step over the compact cache, {Hq} query / {Hkv} KV heads")
+    layers, lens, N, budget = 2, [700, 40, 0, 300], 16, 64
+    q, k, v_raw, cu = random_problem(41, layers, lens, Hq, Hkv, N)
+    r = np.random.default_rng(42)
+    v = W.to_bf16_bits(r.standard_normal(v_raw.shape))                          # values that are real numbers
+    prob = H.Problem(q, k, v, Hkv, cu, "thd")
+    idx, count, _ = prob.pool_topk(prob.score(), 7, budget, None, False)
+    ko, vo = prob.gather(idx, count, budget)
+    qd_bits = W.to_bf16_bits(r.standard_normal((layers, len(lens), Hq, 128)) * 2.0)
+    out = torch.full((layers, len(lens), Hq, 128), float("nan"), dtype=torch.float32, device="cuda")
+    H.D.dapq_decode_attention(prob.shape, H.dev_bf16(qd_bits), ko, vo, count, budget, out)
+    out = out.cpu().numpy().astype(np.float64)
+    idx, count = idx.cpu().numpy(), count.cpu().numpy()
+    g = Hq // Hkv
+    kf, vf, qd = O.bf16_bits_to_f64(k), O.bf16_bits_to_f64(v), O.bf16_bits_to_f64(qd_bits)
+    for l in range(layers):
+        for b, L in enumerate(lens):
+            for hq in range(Hq):
+                kv = hq // g
+                n = count[l, b, kv]
+                assert n == min(budget, L)
+                if n == 0:
+                    assert np.all(out[l, b, hq] == 0.0)
+                    continue
+                keep = idx[l, b, kv, :n]
+                kk, vv = kf[l, cu[b]:cu[b + 1], kv], vf[l, cu[b]:cu[b + 1], kv]
+                want = O.decode_attention(qd[l, b, hq][None], kk[keep], vv[keep])[0]
+                vmax = np.abs(vv).max()
+                assert np.all(np.abs(out[l, b, hq] - want) <= 1e-5 * vmax + 1e-4 * np.abs(want)), (l, b, hq)
+                # against the full cache: bounded by the attention mass of the dropped keys
+                alpha = O.attention(qd[l, b, hq][None], kk)[0]
+                m = 1.0 - alpha[keep].sum()
+                full = O.decode_attention(qd[l, b, hq][None], kk, vv)[0]
+                assert np.abs(out[l, b, hq] - full).max() <= 2 * m * vmax + 1e-5 * vmax
