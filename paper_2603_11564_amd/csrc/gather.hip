@@ -3,7 +3,8 @@
 // [layer][sequence][KV head][slot][d].
 //
 // Pure copy: 16 lanes move one 256-byte row with one 16-byte load and store each, so every row is
-// read and written in full cache lines; a workgroup of 256 threads moves 16 rows of K or of V.
+// read and written in full cache lines; a workgroup of 256 threads moves 64 rows of K or of V, four
+// per 16-lane group, with the four loads in flight together.
 #include "dapq_internal.h"
 
 namespace dapq {
@@ -23,12 +24,16 @@ struct GatherParams {
   int32_t batch, n_kv_heads, budget;
 };
 
+constexpr int kGatherRowsPerGroup = 4;  // rows in flight per 16-lane group
+constexpr int kGatherRowsPerBlock = 16 * kGatherRowsPerGroup;
+
 __global__ __launch_bounds__(256) void gather_kernel(GatherParams p) {
   const int ch = threadIdx.x & 15;
-  const int slot = blockIdx.x * 16 + (threadIdx.x >> 4);
+  const int slot0 = blockIdx.x * kGatherRowsPerBlock + (threadIdx.x >> 4);  // this group's slots: slot0 + 16*r
   const int64_t head = blockIdx.y;  // (layer * batch + seq) * Hkv + kv
   const bool is_v = blockIdx.z == 1;
-  if (slot >= p.count[head]) return;
+  const int n = p.count[head];
+  if (slot0 >= n) return;
   const int kv = (int)(head % p.n_kv_heads);
   const int seq = (int)((head / p.n_kv_heads) % p.batch);
   const int layer = (int)(head / ((int64_t)p.n_kv_heads * p.batch));
@@ -41,14 +46,28 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherParams p) {
     start = p.cu_seqlens[seq];
     L = p.cu_seqlens[seq + 1] - (int)start;
   }
-  const int j = p.idx[head * p.budget + slot];
-  if (j < 0 || j >= L) return;  // never follow an index outside the sequence
-  const uint16_t* src = is_v ? p.v + layer * p.v_stride_layer + seq * p.v_stride_seq + kv * p.v_stride_head +
-                                   (start + j) * p.v_stride_token
-                             : p.k + layer * p.k_stride_layer + seq * p.k_stride_seq + kv * p.k_stride_head +
-                                   (start + j) * p.k_stride_token;
-  uint16_t* dst = (is_v ? p.v_out : p.k_out) + (head * p.budget + slot) * kHeadDim;
-  reinterpret_cast<uint4*>(dst)[ch] = reinterpret_cast<const uint4*>(src)[ch];
+  const uint16_t* base = is_v ? p.v + layer * p.v_stride_layer + seq * p.v_stride_seq + kv * p.v_stride_head
+                              : p.k + layer * p.k_stride_layer + seq * p.k_stride_seq + kv * p.k_stride_head;
+  const int64_t stride_token = is_v ? p.v_stride_token : p.k_stride_token;
+  uint16_t* dst = (is_v ? p.v_out : p.k_out) + head * p.budget * kHeadDim;
+  // all index loads first, then all row loads, then the stores: four rows in flight per group
+  int j[kGatherRowsPerGroup];
+#pragma unroll
+  for (int r = 0; r < kGatherRowsPerGroup; ++r) {
+    const int slot = slot0 + 16 * r;
+    j[r] = slot < n ? p.idx[head * p.budget + slot] : -1;
+  }
+  uint4 row[kGatherRowsPerGroup];
+#pragma unroll
+  for (int r = 0; r < kGatherRowsPerGroup; ++r) {
+    const bool ok = j[r] >= 0 && j[r] < L;  // never follow an index outside the sequence
+    row[r] = ok ? reinterpret_cast<const uint4*>(base + (start + j[r]) * stride_token)[ch] : make_uint4(0, 0, 0, 0);
+  }
+#pragma unroll
+  for (int r = 0; r < kGatherRowsPerGroup; ++r) {
+    const int slot = slot0 + 16 * r;
+    if (j[r] >= 0 && j[r] < L) reinterpret_cast<uint4*>(dst + (int64_t)slot * kHeadDim)[ch] = row[r];
+  }
 }
 
 }  // namespace
@@ -86,7 +105,7 @@ extern "C" DAPQ_API int dapq_gather(const dapq_shape* shape, const void* k, cons
   p.batch = shape->batch;
   p.n_kv_heads = shape->n_kv_heads;
   p.budget = budget;
-  hipLaunchKernelGGL(gather_kernel, dim3((unsigned)((budget + 15) / 16), (unsigned)heads, 2), dim3(256), 0,
+  hipLaunchKernelGGL(gather_kernel, dim3((unsigned)((budget + kGatherRowsPerBlock - 1) / kGatherRowsPerBlock), (unsigned)heads, 2), dim3(256), 0,
                      static_cast<hipStream_t>(stream), p);
   DAPQ_HIP_LAUNCH_CHECK("gather_kernel");
   return DAPQ_OK;
