@@ -92,6 +92,55 @@ def test_invalid_arguments_are_rejected_on_the_host(lib):
     assert lib.dapq_rope_apply(FAKE, FAKE, FAKE, 0, 2, 128, 256, 128, 5e5, 0, None) == 0       # nothing to do
 
 
+def test_invalid_arguments_of_the_entry_points_around_the_step(lib):
+    s = good_shape()
+    sp = C.byref(s)
+    i64 = C.c_int64
+    # extended normaliser
+    kp = (i64(8 * 64 * 128), i64(8 * 64 * 128), i64(64 * 128), i64(128))
+    assert lib.dapq_score_stats_extend(sp, FAKE, None, *kp, FAKE, None) == ERR_INVALID
+    assert lib.dapq_score_stats_extend(sp, FAKE, FAKE, *kp, None, None) == ERR_INVALID
+    assert lib.dapq_score_stats_extend(sp, FAKE, FAKE + 4, *kp, FAKE, None) == ERR_UNSUPPORTED          # misaligned keys
+    assert lib.dapq_score_stats_extend(sp, FAKE, FAKE, kp[0], kp[1], kp[2], i64(64), FAKE, None) == ERR_INVALID   # row < d
+    assert lib.dapq_score_stats_extend(sp, FAKE, FAKE, kp[0], kp[1], i64(132), kp[3], FAKE, None) == ERR_UNSUPPORTED
+    # pooling + selection in one call
+    assert lib.dapq_pool_topk(sp, FAKE, 4, 8, None, FAKE, FAKE, None, None) == ERR_INVALID             # even width
+    assert lib.dapq_pool_topk(sp, FAKE, 7, 0, None, FAKE, FAKE, None, None) == ERR_INVALID             # budget
+    assert lib.dapq_pool_topk(sp, FAKE, 7, 8, None, FAKE, FAKE, FAKE, None) == ERR_INVALID             # pooled aliases scores
+    assert lib.dapq_pool_topk(sp, FAKE, 11, 8, None, FAKE, FAKE, None, None) == ERR_UNSUPPORTED        # needs the buffer
+    assert b"pooled" in lib.dapq_last_error()
+    long_heads = good_shape(total_tokens=70000, k_strides=(70000 * 8 * 128, 0, 128, 8 * 128),
+                            v_strides=(70000 * 8 * 128, 0, 128, 8 * 128))
+    assert lib.dapq_pool_topk(C.byref(long_heads), FAKE, 7, 8, None, FAKE, FAKE, None, None) == ERR_UNSUPPORTED
+    # recall
+    assert lib.dapq_recall(sp, FAKE, FAKE, 8, FAKE, FAKE, 8, None, None, None) == ERR_INVALID
+    assert lib.dapq_recall(sp, FAKE, FAKE, 0, FAKE, FAKE, 8, FAKE, None, None) == ERR_INVALID
+    assert lib.dapq_recall(sp, None, FAKE, 8, FAKE, FAKE, 8, FAKE, None, None) == ERR_INVALID
+    # decode step over the compact cache
+    assert lib.dapq_decode_attention(sp, FAKE, FAKE, FAKE, FAKE, 8193, FAKE, None) == ERR_UNSUPPORTED
+    assert lib.dapq_decode_attention(sp, FAKE, FAKE, FAKE, FAKE, 0, FAKE, None) == ERR_UNSUPPORTED
+    assert lib.dapq_decode_attention(sp, FAKE, FAKE + 8, FAKE, FAKE, 64, FAKE, None) == ERR_UNSUPPORTED  # misaligned cache
+    assert lib.dapq_decode_attention(sp, FAKE, FAKE, FAKE, None, 64, FAKE, None) == ERR_INVALID
+    bad = good_shape(scale=float("nan"))
+    assert lib.dapq_decode_attention(C.byref(bad), FAKE, FAKE, FAKE, FAKE, 64, FAKE, None) == ERR_INVALID
+
+
+def test_score_plan_covers_every_shape(lib):
+    """The launch plan is a pure function of the shape; its workspace figure pins the split it chose."""
+    def ws(**kw):
+        return D.workspace_bytes(good_shape(**kw))
+    lse = 2 * 1 * 32 * 64 * 4
+    # 2 layers x 8 KV heads x 4096 keys, 256 rows: 128-key chunks -> 32 chunks per head, (ref, sum) per row and chunk
+    assert ws() == 256 + 2 * 8 * 32 * 256 * 8 + lse
+    # 512 rows per KV head: two row groups; one extra plane of column sums
+    big = dict(n_pseudo=128, q_strides=(32 * 128 * 128, 32 * 128 * 128, 128 * 128, 128))
+    lse2 = 2 * 1 * 32 * 128 * 4
+    assert ws(**big) == 256 + 2 * 8 * 32 * 512 * 8 + lse2 + 2 * 8 * 4096 * 4
+    # very many rows are still planned (row groups on the grid), absurdly many are refused
+    assert ws(n_pseudo=4096, q_strides=(32 * 4096 * 128, 32 * 4096 * 128, 4096 * 128, 128)) > 0
+    assert ws(n_pseudo=1 << 19) == 0 and b"rows per KV head" in lib.dapq_last_error()
+
+
 def test_binding_raises_with_the_library_message():
     with pytest.raises(D.DapqError) as e:
         D.dapq_pool(good_shape(), None, None, 7, stream=0)
