@@ -226,14 +226,14 @@ __device__ __forceinline__ void sub_dma_lane_offsets(unsigned (&voff)[4], int64_
 // (buffer_load_dwordx4 ... lds).  The buffer descriptor spans from the first row of the sub-block to
 // the end of the last key row of the chunk, so rows past the end of the chunk read as zeros; the
 // uniform part of every address lives in scalar registers (descriptor base, scalar offset per
-// transfer) and the lane part is one of the four precomputed offsets.  A sub-block that starts at or
-// past the end of the chunk gets an empty descriptor: the eight transfers still count as vector
+// transfer) and the lane part is one of the four precomputed offsets.  A sub-block that starts before
+// the chunk or at or past its end gets an empty descriptor: the eight transfers still count as vector
 // memory operations (the waits rely on a fixed number per sub-block) but fetch nothing and fill the
 // slot with zeros.
 __device__ __forceinline__ void sub_dma(u32x4* slot, const uint16_t* kbase, int64_t stride_token, int key0, int nkeys,
                                         const unsigned (&voff)[4]) {
   const int64_t stride_b = stride_token * 2;
-  const bool live = key0 < nkeys;
+  const bool live = key0 >= 0 && key0 < nkeys;
   const char* base = reinterpret_cast<const char*>(kbase) + (live ? (int64_t)key0 * stride_b : (int64_t)0);
   const int64_t span = (int64_t)(nkeys - key0 - 1) * stride_b + kHeadDim * 2;
   const unsigned records = !live ? 0u : (span > (int64_t)0xFFFFFFFFll ? 0xFFFFFFFFu : (unsigned)span);
@@ -313,11 +313,15 @@ __device__ __forceinline__ void wait_ring_full() {
 // PASS 2: off2[rb][v] = -lse2 of the row that accumulator register v of this lane holds in row
 //         block rb (-inf for padding rows, which then add 0).  S of every key goes to out.
 // NST = slots of the sub-block ring.
-template <int NRB, int PASS, int NST>
+template <int NRB, int PASS, int NST, bool REV = false>
 __device__ __forceinline__ void wave_walk(u32x4* ring, const uint16_t* kbase, int64_t stride_token, int nkeys,
                                           int sb0, int sb1, bf16x8 (&kf)[8], const bf16x8 (&qf)[NRB][8], float c,
                                           const float (&off1)[NRB], const float (&off2)[PASS == 2 ? NRB : 1][16],
-                                          float (&acc)[NRB], float* out, const unsigned (&voff)[4], int n, int h) {
+                                          float (&acc)[NRB], float* out, const unsigned (&voff)[4], int n, int h,
+                                          int last_sub = 0) {
+  // REV: step `sub` of the walk works on sub-block last_sub - sub of the chunk (the chunk is walked from
+  // its end to its start); otherwise on sub-block sub
+  auto first_key = [&](int sub) { return (REV ? last_sub - sub : sub) * 32; };
   const unsigned ring_base = (unsigned)(uintptr_t)(lds_vec_ptr)ring;
   unsigned fa[8];
 #pragma unroll
@@ -341,7 +345,7 @@ __device__ __forceinline__ void wave_walk(u32x4* ring, const uint16_t* kbase, in
       const int rb2 = (rb + NRB - 2) % NRB;  // row block of the unit before it
       if (rb == 1) {
         // the slot of this sub-block is free (its fragments are in registers and have been used)
-        sub_dma(ring + issue_slot * kSubVec, kbase, stride_token, (sub + NST) * 32, nkeys, voff);
+        sub_dma(ring + issue_slot * kSubVec, kbase, stride_token, first_key(sub + NST), nkeys, voff);
         issue_slot = issue_slot + 1 == NST ? 0 : issue_slot + 1;
       }
       if (rb == kLast) wait_ring_full<NST>();  // sub-block sub+1 has landed: NST-1 newer ones are in flight
@@ -360,7 +364,7 @@ __device__ __forceinline__ void wave_walk(u32x4* ring, const uint16_t* kbase, in
             if (sub > sb0) {
               const float total = sa + sb;
               const float both = total + xhalf(total);
-              const int key = (sub - 1) * 32 + n;
+              const int key = first_key(sub - 1) + n;
               if (h == 0 && key < nkeys) out[key] = both;
             }
             sa = sb = 0.0f;
@@ -393,7 +397,7 @@ __device__ __forceinline__ void wave_walk(u32x4* ring, const uint16_t* kbase, in
     if (PASS == 2 && sb1 > sb0) {
       const float total = sa + sb;
       const float both = total + xhalf(total);
-      const int key = (sb1 - 1) * 32 + n;
+      const int key = first_key(sb1 - 1) + n;
       if (h == 0 && key < nkeys) out[key] = both;
     }
   }
@@ -546,7 +550,11 @@ __global__ __launch_bounds__(64, 1) void score_wave_pass2_kernel(ScoreParams p) 
   const Work w = locate_uniform(p, blockIdx.x);
   if (w.nkeys == 0) return;
   // (the division runs on the vector ALU: bring the quotient back to a scalar register)
-  const int layer = uniform_i32(blockIdx.z / p.n_kv_heads), kv = blockIdx.z - layer * p.n_kv_heads;
+  // heads and, below, the keys of a chunk are walked in the opposite order to pass 1: what pass 1 read
+  // last (the ends of the chunks in flight, the heads of the last round) is still in the 256 MB
+  // memory-side cache when pass 2 starts
+  const int zz = (int)(gridDim.z - 1 - blockIdx.z);
+  const int layer = uniform_i32(zz / p.n_kv_heads), kv = zz - layer * p.n_kv_heads;
   const int lane = threadIdx.x, n = lane & 31, h = lane >> 5;
   const uint16_t* qbase = p.q + (int64_t)layer * p.q_stride_layer + (int64_t)w.seq * p.q_stride_seq +
                           (int64_t)kv * p.group * p.q_stride_head;
@@ -563,7 +571,8 @@ __global__ __launch_bounds__(64, 1) void score_wave_pass2_kernel(ScoreParams p) 
   unsigned voff[4];
   sub_dma_lane_offsets(voff, p.k_stride_token, lane);
 #pragma unroll
-  for (int i = 0; i < kWaveStages2; ++i) sub_dma(ring + i * kSubVec, kbase, p.k_stride_token, i * 32, w.nkeys, voff);
+  for (int i = 0; i < kWaveStages2; ++i)
+    sub_dma(ring + i * kSubVec, kbase, p.k_stride_token, (nsubs - 1 - i) * 32, w.nkeys, voff);
   bf16x8 qf[NRB][8];
 #pragma unroll
   for (int rb = 0; rb < NRB; ++rb) frag_from_q(qf[rb], p, qbase, gbase + rb * 32 + n, h);
@@ -583,8 +592,8 @@ __global__ __launch_bounds__(64, 1) void score_wave_pass2_kernel(ScoreParams p) 
   float unused_off[NRB], unused_acc[NRB];
 #pragma unroll
   for (int rb = 0; rb < NRB; ++rb) unused_off[rb] = 0.0f;
-  wave_walk<NRB, 2, kWaveStages2>(ring, kbase, p.k_stride_token, w.nkeys, 0, nsubs, kf, qf, p.c, unused_off, off2,
-                                  unused_acc, out, voff, n, h);
+  wave_walk<NRB, 2, kWaveStages2, true>(ring, kbase, p.k_stride_token, w.nkeys, 0, nsubs, kf, qf, p.c, unused_off, off2,
+                                        unused_acc, out, voff, n, h, nsubs - 1);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
