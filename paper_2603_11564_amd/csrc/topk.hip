@@ -86,7 +86,7 @@ __device__ __forceinline__ TopkHead topk_head(const TopkParams& p) {
   if (tid == 0) p.count[head] = hd.keep;
   hd.done = hd.keep == 0;
   if (!hd.done && hd.keep == hd.L) {  // everything survives
-    for (int j = tid; j < hd.L; j += kTopkThreads) hd.out[j] = j;
+    for (int j = tid; j < hd.L; j += (int)blockDim.x) hd.out[j] = j;
     hd.done = true;
   }
   return hd;
@@ -121,11 +121,12 @@ __device__ __forceinline__ void topk_pick_digit(const uint32_t* hist, uint32_t* 
 
 // ---- heads that fit in registers.  R > 0: the input is the un-pooled score and the kernel applies
 // the max-pool of radius R itself (window clipped at the ends of the sequence) before selecting.
-template <int KPT, int R>
-__global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(TopkParams p) {
+template <int THREADS, int KPT, int R>
+__global__ __launch_bounds__(THREADS) void topk_reg_kernel(TopkParams p) {
+  constexpr int kWaves = THREADS / 64;
   __shared__ uint32_t hist[256];
   __shared__ uint32_t bcast[2];
-  __shared__ uint32_t wave_gt[kTopkWaves], wave_eq[kTopkWaves];
+  __shared__ uint32_t wave_gt[kWaves], wave_eq[kWaves];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const TopkHead hd = topk_head(p);
   if (hd.foreign || (hd.done && p.pooled_out == nullptr)) return;  // a finished head may still owe its pooled scores
@@ -170,7 +171,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(TopkParams p) {
   uint32_t prefix = 0, mask = 0;
   int need = hd.keep;
   for (int shift = 24; shift >= 0; shift -= 8) {
-    if (tid < 256) hist[tid] = 0;
+    for (int e = tid; e < 256; e += THREADS) hist[e] = 0;
     __syncthreads();
     // the digit most keys of this wave are likely to share: that of its first candidate
     int first = -1;
@@ -225,7 +226,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(TopkParams p) {
   __syncthreads();
   uint32_t pre_gt = inc_gt - my_gt, pre_eq = inc_eq - my_eq;
 #pragma unroll
-  for (int w = 0; w < kTopkWaves; ++w) {
+  for (int w = 0; w < kWaves; ++w) {
     if (w < wave) {
       pre_gt += wave_gt[w];
       pre_eq += wave_eq[w];
@@ -334,11 +335,26 @@ using namespace dapq;
 namespace dapq {
 namespace {
 
+// Register-variant shapes: (threads, keys per thread).  Short heads use small workgroups so that
+// several of them share a compute unit.
+struct RegVariant {
+  int threads, kpt;
+  int64_t max_len() const { return (int64_t)threads * kpt; }
+};
+
+RegVariant reg_variant_for(int64_t len) {
+  if (len <= 256 * 32) return {256, 32};
+  if (len <= 256 * 64) return {256, 64};
+  if (len <= 1024 * 32) return {1024, 32};
+  return {1024, 64};
+}
+
 template <int R>
-void launch_reg(int kpt, dim3 grid, hipStream_t st, const TopkParams& p) {
-  if (kpt == 8) hipLaunchKernelGGL((topk_reg_kernel<8, R>), grid, dim3(kTopkThreads), 0, st, p);
-  else if (kpt == 32) hipLaunchKernelGGL((topk_reg_kernel<32, R>), grid, dim3(kTopkThreads), 0, st, p);
-  else hipLaunchKernelGGL((topk_reg_kernel<64, R>), grid, dim3(kTopkThreads), 0, st, p);
+void launch_reg(RegVariant v, dim3 grid, hipStream_t st, const TopkParams& p) {
+  if (v.threads == 256 && v.kpt == 32) hipLaunchKernelGGL((topk_reg_kernel<256, 32, R>), grid, dim3(256), 0, st, p);
+  else if (v.threads == 256) hipLaunchKernelGGL((topk_reg_kernel<256, 64, R>), grid, dim3(256), 0, st, p);
+  else if (v.kpt == 32) hipLaunchKernelGGL((topk_reg_kernel<1024, 32, R>), grid, dim3(1024), 0, st, p);
+  else hipLaunchKernelGGL((topk_reg_kernel<1024, 64, R>), grid, dim3(1024), 0, st, p);
 }
 
 int topk_common_checks(const dapq_shape* shape, const float* in, int32_t budget, const int32_t* idx, const int32_t* count) {
@@ -372,18 +388,20 @@ extern "C" DAPQ_API int dapq_topk(const dapq_shape* shape, const float* pooled, 
   p.batch = shape->batch;
   p.n_kv_heads = shape->n_kv_heads;
   p.budget = budget;
-  // Heads of up to KPT*1024 keys go to the register variant, longer ones to the streaming one.  A
-  // dense batch knows its length; a ragged one picks KPT from the mean length and launches both
-  // variants, each skipping the heads of the other.
+  // Heads that fit the chosen register variant go there, longer ones to the streaming kernel.  A
+  // dense batch knows its length; a ragged one launches both kernels, each skipping the heads of
+  // the other.
   const dim3 grid((unsigned)shape->n_kv_heads, (unsigned)shape->batch, (unsigned)shape->n_layers);
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int64_t mean = shape->total_tokens / shape->batch;
   const int64_t longest = shape->cu_seqlens == nullptr ? mean : shape->total_tokens;
-  const int kpt = mean <= 4 * kTopkThreads ? 8 : (mean <= 16 * kTopkThreads || longest <= 32 * kTopkThreads ? 32 : 64);
-  const int64_t reg_max = (int64_t)kpt * kTopkThreads;
+  // a ragged batch sizes the variant for 1.5 x its mean length (or everything, if that is less)
+  const int64_t sized_for = shape->cu_seqlens == nullptr ? mean : (mean + mean / 2 < longest ? mean + mean / 2 : longest);
+  const RegVariant variant = reg_variant_for(sized_for);
+  const int64_t reg_max = variant.max_len();
   p.min_len = 0;
   p.max_len = (int32_t)reg_max;
-  launch_reg<0>(kpt, grid, st, p);
+  launch_reg<0>(variant, grid, st, p);
   DAPQ_HIP_LAUNCH_CHECK("topk_reg_kernel");
   if (longest > reg_max) {
     p.min_len = (int32_t)reg_max + 1;
@@ -428,15 +446,15 @@ extern "C" DAPQ_API int dapq_pool_topk(const dapq_shape* shape, const float* sco
   p.budget = budget;
   p.min_len = 0;
   p.max_len = INT32_MAX;
-  const int kpt = longest <= 8 * kTopkThreads ? 8 : (longest <= 32 * kTopkThreads ? 32 : 64);
+  const RegVariant variant = reg_variant_for(longest);
   const dim3 grid((unsigned)shape->n_kv_heads, (unsigned)shape->batch, (unsigned)shape->n_layers);
   hipStream_t st = static_cast<hipStream_t>(stream);
   switch (width / 2) {
-    case 0: launch_reg<0>(kpt, grid, st, p); break;
-    case 1: launch_reg<1>(kpt, grid, st, p); break;
-    case 2: launch_reg<2>(kpt, grid, st, p); break;
-    case 3: launch_reg<3>(kpt, grid, st, p); break;
-    default: launch_reg<4>(kpt, grid, st, p); break;
+    case 0: launch_reg<0>(variant, grid, st, p); break;
+    case 1: launch_reg<1>(variant, grid, st, p); break;
+    case 2: launch_reg<2>(variant, grid, st, p); break;
+    case 3: launch_reg<3>(variant, grid, st, p); break;
+    default: launch_reg<4>(variant, grid, st, p); break;
   }
   DAPQ_HIP_LAUNCH_CHECK("topk_reg_kernel");
   return DAPQ_OK;

@@ -275,7 +275,8 @@ def test_topk_long_sequence_not_staged_in_lds(H):
     _topk_case(H, [70000], 2048, P, Hkv=1)
 
 
-@pytest.mark.parametrize("L,batch", [(8192, 1), (8193, 3), (32768, 1), (32769, 2), (50001, 1), (65536, 1), (65537, 1)])
+@pytest.mark.parametrize("L,batch", [(8192, 1), (8193, 3), (16384, 2), (16385, 1), (32768, 1), (32769, 2), (50001, 1),
+                                     (65536, 1), (65537, 1)])
 def test_topk_dense_lengths_around_the_variant_limits(H, L, batch):
     """Dense batches at the lengths where the kernel variant changes (8, 32, 64 keys per thread,
     then streaming), with sequence starts that are not 16-byte aligned, heavy ties and a plateau
