@@ -579,13 +579,28 @@ __global__ __launch_bounds__(64, 1) void score_wave_pass2_kernel(ScoreParams p) 
   if (NRB == 8) pin_q_in_agprs<NRB>(qf);
   // -lse2 of the rows this lane's accumulator registers hold; -inf for padding rows, which then add 0
   float off2[NRB][16];
+  if ((reinterpret_cast<uintptr_t>(lse) & 15) == 0 && (p.rows & 3) == 0) {
+    // the four rows of an accumulator quad are consecutive: one 16-byte load each
 #pragma unroll
-  for (int rb = 0; rb < NRB; ++rb)
+    for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int row = gbase + rb * 32 + acc_row(v, h);
-      off2[rb][v] = row < p.rows ? -lse[row] : -INFINITY;
-    }
+      for (int b = 0; b < 4; ++b) {
+        const int row = gbase + rb * 32 + acc_row(4 * b, h);
+        const float4 v = row < p.rows ? *reinterpret_cast<const float4*>(lse + row) : make_float4(INFINITY, INFINITY, INFINITY, INFINITY);
+        off2[rb][4 * b] = -v.x;
+        off2[rb][4 * b + 1] = -v.y;
+        off2[rb][4 * b + 2] = -v.z;
+        off2[rb][4 * b + 3] = -v.w;
+      }
+  } else {
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = gbase + rb * 32 + acc_row(v, h);
+        off2[rb][v] = row < p.rows ? -lse[row] : -INFINITY;
+      }
+  }
   bf16x8 kf[8];
   wait_subblocks(kWaveStages2 - 1);
   wave_load_frags<NRB>(kf, ring, n, h);
