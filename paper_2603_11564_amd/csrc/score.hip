@@ -41,7 +41,6 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));  // 16 bytes; native vector, stays in registers
 
 struct ScoreParams {
@@ -126,7 +125,7 @@ __device__ __forceinline__ Work locate(const ScoreParams& p, int gchunk) {
   return w;
 }
 
-// LDS position of 16-byte chunk `ch` of tile row `key`: rows are 256 B apart, chunks XOR-swizzled by
+// LDS position of 16-byte chunk `ch` of sub-block row `key`: rows are 256 B apart, chunks XOR-swizzled by
 // the row so that 16 consecutive rows reading the same logical chunk hit 16 different bank groups.
 __device__ __forceinline__ int lds_chunk_index(int key, int ch) { return key * 16 + (ch ^ (key & 15)); }
 
@@ -146,7 +145,6 @@ __device__ __forceinline__ float xhalf(float v) { return __shfl_xor(v, 32, 64); 
 // Row of the 32x32 MFMA result held in accumulator register v of a lane in half h.
 __device__ __forceinline__ int acc_row(int v, int h) { return 8 * (v >> 2) + 4 * h + (v & 3); }
 
-
 typedef const u32x4 __attribute__((address_space(3))) * lds_vec_ptr;
 
 // 16-byte LDS read at a per-lane byte address plus a compile-time offset (folds into the instruction).
@@ -154,8 +152,6 @@ __device__ __forceinline__ bf16x8 lds_read16(unsigned lane_addr, int const_off) 
   return __builtin_bit_cast(bf16x8, *(lds_vec_ptr)(uintptr_t)(lane_addr + const_off));
 }
 
-// Column sums of a tile -> S (pass 2): lane halves hold different query rows of the same key (one
-// shuffle), the RW slabs of a workgroup are added through LDS by the first 128 threads after a barrier.
 // Per-sequence prefix of chunk counts for ragged batches (tiny, one block).
 __global__ void score_chunk_prefix_kernel(const int32_t* cu_seqlens, int32_t* cu_chunks, int batch, int chunk_keys) {
   if (threadIdx.x == 0 && blockIdx.x == 0) {
