@@ -36,7 +36,7 @@ import numpy as np
 __all__ = [
     "bf16_bits_to_f64", "f64_to_bf16_bits", "rope_rotate", "rope_apply", "attention", "score_head",
     "score", "pool", "topk", "gather", "compress", "recall", "topk_margin", "attention_extended",
-    "decode_attention",
+    "decode_attention", "pseudo_tokens",
 ]
 
 
@@ -294,6 +294,20 @@ def compress(q_bits, k_bits, v_bits, n_kv_heads, Kb, cu_seqlens=None, width=7, s
 # --------------------------------------------------------------------------------------
 # Sec. 3.3: recall of a predicted retained set against a gold one
 # --------------------------------------------------------------------------------------
+def pseudo_tokens(L: int, first_m: int, last_n: int):
+    """Sec. 4.1 / Sec. 5.1: the N = m + n pseudo tokens take their content from the first m and the
+    last n tokens of the prompt (the paper's Fm_Ln construction) and the positions L_p .. L_p+N-1 of the
+    first N decode steps.  Returns (source token of each pseudo token, position of each pseudo token).
+    A prompt shorter than m or n repeats its first / last token; an empty prompt has no source (-1)."""
+    src = []
+    for t in range(first_m):
+        src.append(min(t, L - 1))
+    for t in range(last_n):
+        src.append(max(L - last_n + t, 0) if L > 0 else -1)
+    pos = [L + i for i in range(first_m + last_n)]
+    return np.asarray(src, dtype=np.int64), np.asarray(pos, dtype=np.int64)
+
+
 def decode_attention(q, k_cache, v_cache, scale=None) -> np.ndarray:
     """One decode step over a cache (Sec. 4.2, last paragraph: decoding starts at position L_p and uses
     only the compressed cache): o = Attention(q, K) V with Attention = softmax(q K^T / sqrt(d_k))

@@ -489,3 +489,16 @@ def test_decode_over_compact_cache_is_within_the_dropped_mass_bound():
     worst = np.argsort(alpha, kind="stable")[:Kb]
     diff_worst = np.abs(O.decode_attention(q, k[worst], v[worst]) - O.decode_attention(q, k, v)).max()
     assert diff_worst > 3 * diff
+
+
+# ------------------------------------------------------------------ pseudo tokens (Sec. 4.1 positions, Sec. 5.1 Fm_Ln content)
+def test_pseudo_tokens_first_m_last_n_and_positions():
+    # the paper's own example shapes: first 4 + last 28, first 2 + last 30 (Sec. 5.1)
+    src, pos = O.pseudo_tokens(1000, 4, 28)
+    assert src.tolist() == [0, 1, 2, 3] + list(range(972, 1000))
+    assert pos.tolist() == list(range(1000, 1032))                  # Positions(T_pseudo) = [L_p, ..., L_p+N-1]
+    src, pos = O.pseudo_tokens(50, 2, 30)
+    assert src.tolist() == [0, 1] + list(range(20, 50)) and pos[0] == 50 and pos[-1] == 81
+    # short prompts repeat their ends, an empty one has no source
+    assert O.pseudo_tokens(3, 4, 5)[0].tolist() == [0, 1, 2, 2, 0, 0, 0, 1, 2]
+    assert O.pseudo_tokens(0, 1, 2)[0].tolist() == [-1, -1, -1] and O.pseudo_tokens(0, 1, 2)[1].tolist() == [0, 1, 2]
