@@ -85,6 +85,17 @@ int dapq_rope_apply(const void* x_in, void* x_out, const int32_t* pos, int64_t r
                     int32_t head_dim, int64_t stride_row, int64_t stride_head, double theta,
                     int32_t pairing, void* stream);
 
+/* Sec. 4.1 (Positions(T_pseudo) = [L_p, ..., L_p+N-1]) with the content choice of Sec. 5.1 (the first m and
+ * the last n tokens of the prompt, N = m + n): for every sequence of the batch
+ *   token_idx[seq][i]   packed index (cu_seqlens[seq] + j) of the prompt token pseudo token i copies:
+ *                       j = i for i < m, j = L_p - n + (i - m) after that; a prompt shorter than m or n
+ *                       repeats its first / last token; -1 for an empty prompt
+ *   positions[seq][i]   L_p + i, ready for dapq_rope_apply
+ * Both device, int32 [batch][n_pseudo]; first_m + last_n must equal shape->n_pseudo.  Sequence lengths are
+ * read on the device (cu_seqlens), so a ragged batch needs no host round trip. */
+int dapq_pseudo_tokens(const dapq_shape* shape, int32_t first_m, int32_t last_n, int32_t* token_idx,
+                       int32_t* positions, void* stream);
+
 /* Sec. 4.2, importance score — S(j) = sum_i Attention(q_i, k_j), summed also over the query heads
  * that share the KV head; Attention is the softmax over the L_p prompt keys of one sequence
  * (App. C.1).  Two streaming passes over K, no N x L_p matrix is stored.

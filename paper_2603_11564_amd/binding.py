@@ -14,7 +14,7 @@ _LIB_PATH = os.path.join(_PKG, "libdapq.so")
 _lib = None
 
 EXPORTS = (
-    "dapq_workspace_bytes", "dapq_last_error", "dapq_rope_apply", "dapq_score", "dapq_score_stats",
+    "dapq_workspace_bytes", "dapq_last_error", "dapq_rope_apply", "dapq_pseudo_tokens", "dapq_score", "dapq_score_stats",
     "dapq_score_accumulate", "dapq_score_stats_extend", "dapq_pool", "dapq_topk", "dapq_pool_topk", "dapq_gather", "dapq_recall", "dapq_decode_attention",
 )
 
@@ -61,6 +61,7 @@ def load_library():
     lib.dapq_last_error.restype = C.c_char_p
     lib.dapq_last_error.argtypes = []
     lib.dapq_rope_apply.argtypes = [vp, vp, vp, i64, i32, i32, i64, i64, C.c_double, i32, vp]
+    lib.dapq_pseudo_tokens.argtypes = [sp, i32, i32, vp, vp, vp]
     lib.dapq_score.argtypes = [sp, vp, vp, vp, vp, sz, vp]
     lib.dapq_score_stats.argtypes = [sp, vp, vp, vp, vp, sz, vp]
     lib.dapq_score_accumulate.argtypes = [sp, vp, vp, vp, vp, vp, sz, vp]
@@ -173,3 +174,8 @@ def dapq_recall(shape, idx_gold, count_gold, budget_gold, idx_pred, count_pred, 
 def dapq_decode_attention(shape, q_decode, k_cache, v_cache, count, budget, out, stream=None):
     _check(load_library().dapq_decode_attention(C.byref(shape), _ptr(q_decode), _ptr(k_cache), _ptr(v_cache), _ptr(count),
                                                 budget, _ptr(out), _stream(stream)))
+
+
+def dapq_pseudo_tokens(shape, first_m, last_n, token_idx, positions, stream=None):
+    _check(load_library().dapq_pseudo_tokens(C.byref(shape), first_m, last_n, _ptr(token_idx), _ptr(positions),
+                                             _stream(stream)))

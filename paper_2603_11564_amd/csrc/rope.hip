@@ -57,10 +57,52 @@ __global__ void rope_kernel(const uint16_t* __restrict__ x_in, uint16_t* x_out, 
   }
 }
 
+// Sec. 4.1 / Sec. 5.1: which prompt token each pseudo token copies (first m, last n) and the position
+// it is given (L_p + i), for every sequence of a possibly ragged batch, without a host round trip
+// for the sequence lengths.
+__global__ void pseudo_tokens_kernel(const int32_t* cu_seqlens, int64_t total_tokens, int batch, int first_m, int last_n,
+                                     int32_t* token_idx, int32_t* positions) {
+  const int n = first_m + last_n;
+  const int gid = blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= batch * n) return;
+  const int b = gid / n, i = gid - b * n;
+  int64_t start;
+  int L;
+  if (cu_seqlens == nullptr) {
+    L = (int)(total_tokens / batch);
+    start = (int64_t)b * L;
+  } else {
+    start = cu_seqlens[b];
+    L = cu_seqlens[b + 1] - (int)start;
+  }
+  int src;
+  if (i < first_m) src = i < L - 1 ? i : L - 1;
+  else src = L > 0 ? (L - last_n + (i - first_m) > 0 ? L - last_n + (i - first_m) : 0) : -1;
+  token_idx[gid] = src >= 0 ? (int32_t)(start + src) : -1;
+  positions[gid] = L + i;
+}
+
 }  // namespace
 }  // namespace dapq
 
 using namespace dapq;
+
+extern "C" DAPQ_API int dapq_pseudo_tokens(const dapq_shape* shape, int32_t first_m, int32_t last_n, int32_t* token_idx,
+                                           int32_t* positions, void* stream) {
+  int rc = check_shape(shape, false, false, false);
+  if (rc != DAPQ_OK) return rc;
+  DAPQ_REQUIRE(token_idx != nullptr && positions != nullptr, DAPQ_ERR_INVALID_ARG, "token_idx and positions must not be NULL");
+  DAPQ_REQUIRE(first_m >= 0 && last_n >= 0 && (int64_t)first_m + last_n == shape->n_pseudo, DAPQ_ERR_INVALID_ARG,
+               "first_m (%d) + last_n (%d) must equal n_pseudo (%d)", first_m, last_n, shape->n_pseudo);
+  const int64_t work = (int64_t)shape->batch * shape->n_pseudo;
+  DAPQ_REQUIRE(work < ((int64_t)1 << 31), DAPQ_ERR_UNSUPPORTED, "batch * n_pseudo is too large");
+  hipLaunchKernelGGL(pseudo_tokens_kernel, dim3((unsigned)((work + 255) / 256)), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), shape->cu_seqlens, shape->total_tokens, shape->batch, first_m, last_n,
+                     token_idx, positions);
+  DAPQ_HIP_LAUNCH_CHECK("pseudo_tokens_kernel");
+  return DAPQ_OK;
+}
+
 
 extern "C" DAPQ_API int dapq_rope_apply(const void* x_in, void* x_out, const int32_t* pos, int64_t rows, int32_t heads,
                                int32_t head_dim, int64_t stride_row, int64_t stride_head, double theta,

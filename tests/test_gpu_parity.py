@@ -547,3 +547,20 @@ def test_decode_step_over_the_compact_cache(H, Hq, Hkv):
                 m = 1.0 - alpha[keep].sum()
                 full = O.decode_attention(qd[l, b, hq][None], kk, vv)[0]
                 assert np.abs(out[l, b, hq] - full).max() <= 2 * m * vmax + 1e-5 * vmax
+
+
+def test_pseudo_tokens_and_positions(H):
+    """Sec. 4.1 positions and the first-m / last-n content choice, for a ragged and a dense batch."""
+    announce("pseudo tokens (first m + last n) and their positions")
+    for lens, dense in (([1000, 3, 0, 50, 4097], False), ([777] * 3, True)):
+        for m, n in ((4, 28), (2, 30), (0, 16), (8, 0)):
+            q, k, v, cu = random_problem(5, 1, lens, 2, 2, m + n)
+            prob = H.Problem(q, k, v, 2, None if dense else cu, "thd")
+            tok = torch.full((len(lens), m + n), -9, dtype=torch.int32, device="cuda")
+            pos = torch.full((len(lens), m + n), -9, dtype=torch.int32, device="cuda")
+            H.D.dapq_pseudo_tokens(prob.shape, m, n, tok, pos)
+            tok, pos = tok.cpu().numpy(), pos.cpu().numpy()
+            for b, L in enumerate(lens):
+                src, want_pos = O.pseudo_tokens(L, m, n)
+                assert np.array_equal(pos[b], want_pos)
+                assert np.array_equal(tok[b], np.where(src >= 0, src + cu[b], -1))
