@@ -273,6 +273,18 @@ def main():
         "avg_launch_ms": per[dom], "hbm_gbs": hbm_gbs, "mfma_tflops": mfma_tflops,
     })
 
+    # whole step against HBM: bytes the method must move (K once, scores, selection, retained rows) and bytes
+    # of the two-pass design (K twice), per step time
+    retained = sum(min(w.budget, L) for L in lens) * nl * Hkv
+    step_alg = key_units * (2 * d + 16) + retained * (4 + 8 * d)
+    step_design = step_alg + key_units * 2 * d
+    step_hbm = {
+        "algorithmic_bytes": step_alg, "design_bytes": step_design,
+        "algorithmic_gbs": step_alg / (ms_per_step * 1e-3) / 1e9, "design_gbs": step_design / (ms_per_step * 1e-3) / 1e9,
+        "design_frac_of_peak": step_design / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "mfma_frac_of_peak": {n: flops_pass / (per[n] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS for n in bytes_pass},
+    }
+
     out = {
         "metric": "prompt keys scored+evicted/sec (all layers x KV heads)", "value": value, "unit": "keys/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -282,6 +294,7 @@ def main():
                                f"K layout {w.layout}"},
         "kernel_ms": per,
         "roofline": roofline,
+        "step_hbm": step_hbm,
     }
     if args.extras:
         out["extras_ms"] = time_extras(ctx, args.steps)
