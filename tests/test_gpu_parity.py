@@ -564,3 +564,38 @@ def test_pseudo_tokens_and_positions(H):
                 src, want_pos = O.pseudo_tokens(L, m, n)
                 assert np.array_equal(pos[b], want_pos)
                 assert np.array_equal(tok[b], np.where(src >= 0, src + cu[b], -1))
+
+
+# ----------------------------------------------------------------------------------------- random shapes
+@pytest.mark.parametrize("seed", range(40))
+def test_chain_random_shapes(H, seed):
+    """The whole step on seeded random shapes (head counts, pseudo-query counts, ragged or dense lengths
+    with chunk-boundary values, both K layouts, window widths, budgets), both ways of selecting (two calls /
+    one call), against the oracle's compress()."""
+    r = np.random.default_rng(1000 + seed)
+    layers = int(r.integers(1, 3))
+    Hkv = int(r.choice([1, 2, 3]))
+    g = int(r.choice([1, 2, 4, 5, 8]))
+    N = int(r.choice([1, 7, 16, 32, 33, 64, 100, 128]))
+    while g * N > 640:
+        N //= 2
+    dense = bool(r.integers(0, 2))
+    special = [1, 31, 32, 33, 127, 128, 129, 255, 256, 257, 1023, 1024, 1025, 2047, 2048, 2049, 4100]
+    if dense:
+        lens = [int(r.choice(special + [int(r.integers(1, 3000))]))] * int(r.integers(1, 4))
+    else:
+        lens = [int(r.choice(special + [0, int(r.integers(1, 3000))])) for _ in range(int(r.integers(1, 5)))]
+        if sum(lens) == 0:
+            lens[0] = 77
+    layout = "thd" if (not dense or len(lens) > 1 or r.integers(0, 2)) else "hnd"
+    width = int(r.choice([1, 3, 7, 7, 7, 9, 13]))
+    budget = int(r.choice([1, 5, 64, 300, 983]))
+    gain = float(r.choice([0.5, 1.0, 2.5]))
+    announce(f"random shape {seed}: layers {layers} Hkv {Hkv} g {g} N {N} lens {lens} dense {dense} {layout} "
+             f"width {width} budget {budget} gain {gain}")
+    q, k, v, cu = random_problem(2000 + seed, layers, lens, Hkv * g, Hkv, N, gain=gain)
+    prob = H.Problem(q, k, v, Hkv, None if dense else cu, layout)
+    classes, idx = compare_chain(H, prob, q, k, v, budget, width)
+    # the one-call selection gives the same indices as the two calls
+    idx2, count2, _ = prob.pool_topk(prob.score(), width, budget, None, True)
+    assert np.array_equal(idx2.cpu().numpy(), idx)
