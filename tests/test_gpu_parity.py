@@ -599,3 +599,23 @@ def test_chain_random_shapes(H, seed):
     # the one-call selection gives the same indices as the two calls
     idx2, count2, _ = prob.pool_topk(prob.score(), width, budget, None, True)
     assert np.array_equal(idx2.cpu().numpy(), idx)
+
+
+def test_score_keys_with_a_huge_row_stride(H):
+    """Keys that sit 2 MiB apart (a strided view of a wide buffer): the transfers' scalar and lane offsets
+    reach into the gigabytes."""
+    announce("score with k_stride_token = 2^20 elements")
+    L, N, Hq, d, stride = 70, 8, 2, 128, 1 << 20
+    r = np.random.default_rng(51)
+    k_bits = W.to_bf16_bits(r.standard_normal((1, L, 1, d)))
+    q_bits = W.to_bf16_bits(r.standard_normal((1, 1, Hq, N, d)))
+    wide = torch.zeros((L, stride), dtype=torch.bfloat16, device="cuda")            # 140 MiB
+    wide[:, :d] = H.dev_bf16(k_bits[0, :, 0])
+    q = H.dev_bf16(q_bits)
+    shape = H.D.make_shape(n_layers=1, batch=1, n_q_heads=Hq, n_kv_heads=1, n_pseudo=N, total_tokens=L,
+                           k_strides=(0, 0, 0, stride), v_strides=(0, 0, 0, stride),
+                           q_strides=(Hq * N * d, Hq * N * d, N * d, d))
+    ws = torch.empty(max(H.D.workspace_bytes(shape), 256), dtype=torch.uint8, device="cuda")
+    S = torch.full((1, 1, L), float("nan"), dtype=torch.float32, device="cuda")
+    H.D.dapq_score(shape, q, wide, S, ws)
+    H.assert_scores_close(S.cpu().numpy(), O.score(q_bits, k_bits, 1), "S, strided keys")
