@@ -22,7 +22,10 @@ extended sequence of Sec. 4.1 is attended causally; scores of the g query heads 
 is per KV head; pooling is a stride-1 max over a centred window clipped at the
 sequence ends, applied after the group sum; TopK ties go to the lowest index and
 the retained set is reported in ascending position; RoPE pairs channel c with
-c + d/2 and uses no frequency rescaling.
+c + d/2 and uses no frequency rescaling; a pseudo token's row of a layer's query
+projection input is the row of the prompt token it copies (exact where rows do not
+depend on position, i.e. at the embedding; the paper's point that content is
+secondary covers the rest), and the projection is rounded to bf16 before the rotation.
 
 Parity status: every function below is pinned by tests/test_oracle_pins.py against
 closed forms, invariants, brute force or hand-worked fixtures (tests/golden/).
@@ -36,7 +39,7 @@ import numpy as np
 __all__ = [
     "bf16_bits_to_f64", "f64_to_bf16_bits", "rope_rotate", "rope_apply", "attention", "score_head",
     "score", "pool", "topk", "gather", "compress", "recall", "topk_margin", "attention_extended",
-    "decode_attention", "pseudo_tokens",
+    "decode_attention", "pseudo_tokens", "pseudo_queries",
 ]
 
 
@@ -306,6 +309,34 @@ def pseudo_tokens(L: int, first_m: int, last_n: int):
         src.append(max(L - last_n + t, 0) if L > 0 else -1)
     pos = [L + i for i in range(first_m + last_n)]
     return np.asarray(src, dtype=np.int64), np.asarray(pos, dtype=np.int64)
+
+
+def pseudo_queries(x_bits, token_idx, w_bits, n_q_heads, positions=None, theta: float = 500000.0,
+                   pairing: str = "half") -> np.ndarray:
+    """Sec. 4.1: the queries the model computes for the pseudo tokens of one layer.  Pseudo token r takes
+    its content from prompt token token_idx[r] (its row of the layer's query-projection input is that
+    token's row: content is secondary, the position is what is assigned), is projected by the layer's
+    query weight, split into heads and rotated to its position:
+        q[h, r, :] = RoPE_{positions[r]}( bf16( x[token_idx[r], :] . w[h*d:(h+1)*d, :]^T ) ).
+    x_bits: bf16 bits [tokens, hidden]; token_idx: [rows], -1 = no source (an empty prompt), the query is
+    zero; w_bits: bf16 bits [Hq*d, hidden], one row per output feature; positions: [rows] or None (no
+    rotation).  The product is exact in float64 up to its summation; it is rounded to bf16 once, which is
+    the precision the model hands its queries on in, then rotated by rope_apply.
+    Returns bf16 bits [Hq, rows, d]."""
+    x = bf16_bits_to_f64(x_bits)
+    w = bf16_bits_to_f64(w_bits)
+    token_idx = np.asarray(token_idx, dtype=np.int64)
+    rows, hidden = token_idx.shape[0], w.shape[1]
+    assert w.shape[0] % n_q_heads == 0
+    d = w.shape[0] // n_q_heads
+    xg = np.zeros((rows, hidden), dtype=np.float64)
+    for r in range(rows):
+        if token_idx[r] >= 0:
+            xg[r] = x[token_idx[r]]
+    q_bits = f64_to_bf16_bits(xg @ w.T).reshape(rows, n_q_heads, d)
+    if positions is not None:
+        q_bits = rope_apply(q_bits, positions, theta, pairing)
+    return np.ascontiguousarray(q_bits.transpose(1, 0, 2))
 
 
 def decode_attention(q, k_cache, v_cache, scale=None) -> np.ndarray:

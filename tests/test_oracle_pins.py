@@ -502,3 +502,103 @@ def test_pseudo_tokens_first_m_last_n_and_positions():
     # short prompts repeat their ends, an empty one has no source
     assert O.pseudo_tokens(3, 4, 5)[0].tolist() == [0, 1, 2, 2, 0, 0, 0, 1, 2]
     assert O.pseudo_tokens(0, 1, 2)[0].tolist() == [-1, -1, -1] and O.pseudo_tokens(0, 1, 2)[1].tolist() == [0, 1, 2]
+
+
+# ------------------------------------------------------------------ queries of the pseudo tokens (Sec. 4.1)
+def _bits(x):
+    return W.to_bf16_bits(np.asarray(x, dtype=np.float64))
+
+
+def test_pseudo_queries_golden_two_heads(golden):
+    g = golden("pseudo_queries_two_heads.txt")
+    x = _bits([g["x0"], g["x1"], g["x2"]])
+    w = _bits([g["w0"], g["w1"], g["w2"], g["w3"]])
+    tok = [int(v) for v in g["token_idx"]]
+    pre = O.bf16_bits_to_f64(O.pseudo_queries(x, tok, w, 2))
+    assert pre[0].ravel().tolist() == g["q_pre_head0"] and pre[1].ravel().tolist() == g["q_pre_head1"]
+    q = O.bf16_bits_to_f64(O.pseudo_queries(x, tok, w, 2, positions=[int(v) for v in g["positions"]], theta=10000.0))
+    assert q[0].ravel().tolist() == g["q_head0"] and q[1].ravel().tolist() == g["q_head1"]
+
+
+def test_pseudo_queries_permutation_weight_is_a_gather():
+    # w = rows of a permutation matrix: feature f copies hidden channel perm[f], bit for bit; using w
+    # transposed would apply the inverse permutation instead
+    r = rng(90)
+    tokens, hidden, Hq, rows = 11, 24, 3, 7
+    x = W.to_bf16_bits(r.standard_normal((tokens, hidden)))
+    perm = r.permutation(hidden)
+    assert not np.array_equal(np.argsort(perm), perm)
+    w = np.zeros((hidden, hidden))
+    w[np.arange(hidden), perm] = 1.0
+    tok = r.integers(0, tokens, rows)
+    got = O.pseudo_queries(x, tok, _bits(w), Hq)
+    want = x[tok][:, perm].reshape(rows, Hq, hidden // Hq).transpose(1, 0, 2)
+    assert np.array_equal(got, want)
+
+
+def test_pseudo_queries_brute_force_exact_sums():
+    # every product of two bf16 numbers and every partial sum here is exact in rational arithmetic;
+    # the result must be the bf16 nearest to the exact sum
+    from fractions import Fraction
+    r = rng(91)
+    tokens, hidden, Hq, d, rows = 5, 9, 2, 4, 6
+    x = W.to_bf16_bits(r.standard_normal((tokens, hidden)))
+    w = W.to_bf16_bits(r.standard_normal((Hq * d, hidden)))
+    tok = [4, 0, 0, -1, 2, 3]
+    got = O.bf16_bits_to_f64(O.pseudo_queries(x, tok, w, Hq))
+    xf, wf = W.from_bf16_bits(x).astype(np.float64), W.from_bf16_bits(w).astype(np.float64)
+    for row in range(rows):
+        for h in range(Hq):
+            for c in range(d):
+                exact = Fraction(0)
+                if tok[row] >= 0:
+                    for t in range(hidden):
+                        exact += Fraction(float(xf[tok[row], t])) * Fraction(float(wf[h * d + c, t]))
+                if exact == 0:
+                    assert got[h, row, c] == 0.0
+                    continue
+                e = math.frexp(float(abs(exact)))[1]          # |exact| in [2^(e-1), 2^e)
+                ulp = Fraction(2) ** (e - 8)                  # spacing of bf16 there (8 significant bits)
+                k = abs(exact) / ulp
+                lo = k.numerator // k.denominator
+                rem = k - lo
+                n = lo + 1 if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and lo % 2 == 1) else lo
+                want = float(n * ulp) * (1 if exact > 0 else -1)
+                assert got[h, row, c] == want, (row, h, c)
+
+
+def test_pseudo_queries_round_once_from_the_exact_sum():
+    # 1 + 2^-8 is halfway between two bf16 numbers; the 2^-30 on top decides it upwards.  Rounding the
+    # sum to float32 first would lose the 2^-30 and then fall to the even neighbour 1.0.
+    x = _bits([[1.0, 2.0 ** -8, 2.0 ** -30]])
+    w = _bits([[1.0, 1.0, 1.0], [1.0, 1.0, 0.0]])
+    got = O.bf16_bits_to_f64(O.pseudo_queries(x, [0], w, 1))
+    assert got[0, 0].tolist() == [1.0 + 2.0 ** -7, 1.0]
+
+
+def test_pseudo_queries_positions_and_layout():
+    r = rng(92)
+    tokens, hidden, Hq, d, rows = 13, 16, 4, 8, 5
+    x = W.to_bf16_bits(r.standard_normal((tokens, hidden)))
+    w = W.to_bf16_bits(r.standard_normal((Hq * d, hidden)) / 4.0)
+    tok = r.integers(0, tokens, rows)
+    pre = O.pseudo_queries(x, tok, w, Hq)
+    assert pre.shape == (Hq, rows, d) and pre.dtype == np.uint16
+    # position 0 is no rotation; rows that copy the same token differ only by their positions
+    assert np.array_equal(O.pseudo_queries(x, tok, w, Hq, positions=np.zeros(rows, dtype=np.int64)), pre)
+    same = O.pseudo_queries(x, [3, 3], w, Hq, positions=[100, 101])
+    assert not np.array_equal(same[:, 0], same[:, 1])
+    assert np.array_equal(O.pseudo_queries(x, [3, 3], w, Hq)[:, 0], O.pseudo_queries(x, [3, 3], w, Hq)[:, 1])
+    # the rotation is the one rope_apply does on the rounded projection, per head, and keeps each pair's norm
+    pos = np.array([7, 1000, 32768, 5, 131071])
+    q = O.bf16_bits_to_f64(O.pseudo_queries(x, tok, w, Hq, positions=pos))
+    p = O.bf16_bits_to_f64(pre)
+    n_q = np.hypot(q[..., : d // 2], q[..., d // 2:])
+    n_p = np.hypot(p[..., : d // 2], p[..., d // 2:])
+    assert np.allclose(n_q, n_p, rtol=2.0 ** -7, atol=1e-3)
+    # torch's float64 matmul, rounded by torch, agrees on the projection
+    xt = torch.from_numpy(W.from_bf16_bits(x).astype(np.float64))
+    wt = torch.from_numpy(W.from_bf16_bits(w).astype(np.float64))
+    want = (xt[torch.from_numpy(tok)] @ wt.T).to(torch.float32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    agree = (want.reshape(rows, Hq, d).transpose(1, 0, 2) == pre).mean()
+    assert agree > 0.99          # float32 in between may flip a halfway case, nothing else
