@@ -96,6 +96,39 @@ int dapq_rope_apply(const void* x_in, void* x_out, const int32_t* pos, int64_t r
 int dapq_pseudo_tokens(const dapq_shape* shape, int32_t first_m, int32_t last_n, int32_t* token_idx,
                        int32_t* positions, void* stream);
 
+/* Sec. 4.1 — the queries of the pseudo tokens.  The model runs the pseudo tokens only to obtain their queries;
+ * pseudo token r copies prompt token token_idx[r] (dapq_pseudo_tokens), so for every layer its row of the
+ * query projection's input is that token's row, and
+ *   q_out[layer][head][r][c] = RoPE_{positions[r]}( bf16( sum_t x[layer][token_idx[r]][t] * w_q[layer][head*head_dim + c][t] ) )
+ * with fp32 accumulation, one rounding to bf16 (nearest even) and then the rotation of dapq_rope_apply.
+ *   x          device, bf16: the input rows of the query projection (the layer's normalised hidden states),
+ *              element (layer, token, t) at layer*x_stride_layer + token*x_stride_token + t; x_stride_layer may
+ *              be 0 (one set of rows for all layers); one layer must span less than 4 GiB
+ *   token_idx  device, int32 [rows]: packed prompt token each pseudo token copies; a negative entry has no
+ *              source and yields a zero query; entries >= total_tokens read as zero rows
+ *   w_q        device, bf16: query weights, one row of `hidden` inputs per output feature,
+ *              element (layer, f, t) at layer*w_stride_layer + f*w_stride_row + t, f = head*head_dim + c
+ *   positions  device, int32 [rows] (L_p + i of the row's sequence), or NULL: no rotation (theta, pairing unused)
+ *   q_out      device, bf16, element (layer, head, r, c) at layer*q_stride_layer + head*q_stride_head +
+ *              r*q_stride_row + c; with r = seq*N + i this is the Q layout of dapq_score when
+ *              q_stride_seq = N*q_stride_row
+ * hidden must be a multiple of 64, head_dim a multiple of 8 (even), strides multiples of 8 elements, bases
+ * 16-byte aligned.  The weight is streamed once per sweep of 64 rows; the kernel is built for the few rows of
+ * a pseudo segment (batch * N up to a few hundred), not for prompt-sized products. */
+typedef struct dapq_qproj {
+  int32_t n_layers;
+  int32_t rows;          /* pseudo tokens of all sequences: batch * N */
+  int32_t hidden;        /* inputs of the projection */
+  int32_t n_q_heads;     /* H_q */
+  int32_t head_dim;      /* d_k; the projection has H_q * d_k output features */
+  int64_t total_tokens;  /* rows of x per layer */
+  int64_t x_stride_layer, x_stride_token;
+  int64_t w_stride_layer, w_stride_row;
+  int64_t q_stride_layer, q_stride_head, q_stride_row;
+} dapq_qproj;
+int dapq_pseudo_queries(const dapq_qproj* desc, const void* x, const int32_t* token_idx, const void* w_q,
+                        const int32_t* positions, double theta, int32_t pairing, void* q_out, void* stream);
+
 /* Sec. 4.2, importance score — S(j) = sum_i Attention(q_i, k_j), summed also over the query heads
  * that share the KV head; Attention is the softmax over the L_p prompt keys of one sequence
  * (App. C.1).  Two streaming passes over K, no N x L_p matrix is stored.

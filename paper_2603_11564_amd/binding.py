@@ -14,7 +14,7 @@ _LIB_PATH = os.path.join(_PKG, "libdapq.so")
 _lib = None
 
 EXPORTS = (
-    "dapq_workspace_bytes", "dapq_last_error", "dapq_rope_apply", "dapq_pseudo_tokens", "dapq_score", "dapq_score_stats",
+    "dapq_workspace_bytes", "dapq_last_error", "dapq_rope_apply", "dapq_pseudo_tokens", "dapq_pseudo_queries", "dapq_score", "dapq_score_stats",
     "dapq_score_accumulate", "dapq_score_stats_extend", "dapq_pool", "dapq_topk", "dapq_pool_topk", "dapq_gather", "dapq_recall", "dapq_decode_attention",
 )
 
@@ -41,6 +41,17 @@ class Shape(C.Structure):
     ]
 
 
+class Qproj(C.Structure):
+    """Mirror of `dapq_qproj`."""
+    _fields_ = [
+        ("n_layers", C.c_int32), ("rows", C.c_int32), ("hidden", C.c_int32), ("n_q_heads", C.c_int32),
+        ("head_dim", C.c_int32), ("total_tokens", C.c_int64),
+        ("x_stride_layer", C.c_int64), ("x_stride_token", C.c_int64),
+        ("w_stride_layer", C.c_int64), ("w_stride_row", C.c_int64),
+        ("q_stride_layer", C.c_int64), ("q_stride_head", C.c_int64), ("q_stride_row", C.c_int64),
+    ]
+
+
 def lib_path() -> str:
     return _LIB_PATH
 
@@ -62,6 +73,7 @@ def load_library():
     lib.dapq_last_error.argtypes = []
     lib.dapq_rope_apply.argtypes = [vp, vp, vp, i64, i32, i32, i64, i64, C.c_double, i32, vp]
     lib.dapq_pseudo_tokens.argtypes = [sp, i32, i32, vp, vp, vp]
+    lib.dapq_pseudo_queries.argtypes = [C.POINTER(Qproj), vp, vp, vp, vp, C.c_double, i32, vp, vp]
     lib.dapq_score.argtypes = [sp, vp, vp, vp, vp, sz, vp]
     lib.dapq_score_stats.argtypes = [sp, vp, vp, vp, vp, sz, vp]
     lib.dapq_score_accumulate.argtypes = [sp, vp, vp, vp, vp, vp, sz, vp]
@@ -179,3 +191,8 @@ def dapq_decode_attention(shape, q_decode, k_cache, v_cache, count, budget, out,
 def dapq_pseudo_tokens(shape, first_m, last_n, token_idx, positions, stream=None):
     _check(load_library().dapq_pseudo_tokens(C.byref(shape), first_m, last_n, _ptr(token_idx), _ptr(positions),
                                              _stream(stream)))
+
+
+def dapq_pseudo_queries(desc, x, token_idx, w_q, positions, theta, pairing, q_out, stream=None):
+    _check(load_library().dapq_pseudo_queries(C.byref(desc), _ptr(x), _ptr(token_idx), _ptr(w_q), _ptr(positions),
+                                              float(theta), int(pairing), _ptr(q_out), _stream(stream)))

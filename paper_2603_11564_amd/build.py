@@ -10,7 +10,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libdapq.so")
-SOURCES = ["common.hip", "rope.hip", "score.hip", "pool.hip", "topk.hip", "gather.hip", "recall.hip", "decode.hip"]
+SOURCES = ["common.hip", "rope.hip", "score.hip", "pool.hip", "topk.hip", "gather.hip", "recall.hip", "decode.hip", "qproj.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
     # packed fp32 VALU forms are kept out of the generated code on purpose

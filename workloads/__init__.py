@@ -23,7 +23,7 @@ from typing import List, Optional, Tuple
 
 import numpy as np
 
-_KIND_Q, _KIND_K, _KIND_V, _KIND_NEEDLE, _KIND_HEAVY, _KIND_LEN, _KIND_FILL = range(7)
+_KIND_Q, _KIND_K, _KIND_V, _KIND_NEEDLE, _KIND_HEAVY, _KIND_LEN, _KIND_FILL, _KIND_X, _KIND_WQ = range(9)
 
 
 @dataclass(frozen=True)
@@ -121,6 +121,19 @@ def q_pre(w: Workload, seed: int, layer: int, seq: int) -> np.ndarray:
         out[h] = to_bf16_bits(_rng(seed, _KIND_Q, layer, seq, h).standard_normal(
             (w.n_pseudo, w.head_dim), dtype=np.float32))
     return out
+
+
+def projection_rows(seed: int, layer: int, tokens: int, hidden: int) -> np.ndarray:
+    """Input rows of one layer's query projection (the normalised hidden states of the prompt tokens):
+    bf16 bits [tokens, hidden], N(0,1) -- unit RMS, as a normalisation layer leaves them."""
+    return to_bf16_bits(_rng(seed, _KIND_X, layer).standard_normal((tokens, hidden), dtype=np.float32))
+
+
+def query_weight(seed: int, layer: int, features: int, hidden: int) -> np.ndarray:
+    """Query weight of one layer, one row per output feature: bf16 bits [features, hidden], N(0, 1/hidden),
+    so that the projected queries are N(0,1) like q_pre()."""
+    w = _rng(seed, _KIND_WQ, layer).standard_normal((features, hidden), dtype=np.float32)
+    return to_bf16_bits(w / np.float32(np.sqrt(hidden)))
 
 
 def needle_plan(w: Workload, seed: int, layer: int, seq: int, kv_head: int, L: int):
