@@ -196,6 +196,23 @@ def time_extras(ctx, reps):
     if w.budget <= 8192:
         calls["decode_attention"] = lambda: D.dapq_decode_attention(ctx.shape, qd, ctx.k_out, ctx.v_out, ctx.count, w.budget,
                                                                     dec, stream)
+    # the queries of the pseudo tokens from the rows of the tokens they copy (first 4 + last N-4 of each prompt):
+    # model width H_q * d, one weight per layer, 2048 stand-in rows of projection input per layer
+    hidden, T = Hq * d, 2048
+    xin = torch.randn((nl, T, hidden), generator=g, device=dev).to(torch.bfloat16)
+    wq = torch.empty((nl, Hq * d, hidden), dtype=torch.bfloat16, device=dev)
+    for li in range(nl):
+        wq[li].copy_(torch.randn((Hq * d, hidden), generator=g, device=dev) * hidden ** -0.5)
+    src = torch.cat([torch.arange(4), torch.arange(T - (N - 4), T)]).to(torch.int32).repeat(B).to(dev)
+    desc = D.Qproj(n_layers=nl, rows=B * N, hidden=hidden, n_q_heads=Hq, head_dim=d, total_tokens=T,
+                   x_stride_layer=T * hidden, x_stride_token=hidden, w_stride_layer=Hq * d * hidden, w_stride_row=hidden,
+                   q_stride_layer=Hq * B * N * d, q_stride_head=B * N * d, q_stride_row=d)
+    qout = torch.empty((nl, Hq, B, N, d), dtype=torch.bfloat16, device=dev)
+    pos = ctx.q_pos.reshape(-1).contiguous()
+    pws = torch.empty(max(D.pseudo_queries_workspace_bytes(desc), 16), dtype=torch.uint8, device=dev)
+    calls["pseudo_queries"] = lambda: D.dapq_pseudo_queries(desc, xin, src, wq, pos, w.theta, 0, qout, pws, stream)
+    calls["pseudo_queries_no_rotation"] = lambda: D.dapq_pseudo_queries(desc, xin, src, wq, None, w.theta, 0, qout, pws,
+                                                                        stream)
     res = {}
     for name, fn in calls.items():
         fn()

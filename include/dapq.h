@@ -112,6 +112,10 @@ int dapq_pseudo_tokens(const dapq_shape* shape, int32_t first_m, int32_t last_n,
  *   q_out      device, bf16, element (layer, head, r, c) at layer*q_stride_layer + head*q_stride_head +
  *              r*q_stride_row + c; with r = seq*N + i this is the Q layout of dapq_score when
  *              q_stride_seq = N*q_stride_row
+ *   workspace  device scratch of at least dapq_pseudo_queries_workspace_bytes(desc), 16-byte aligned; may be NULL
+ *              when that is 0.  It is needed when the call is too small to fill the chip with one wave per
+ *              weight tile (a single layer, say): the hidden axis is then split over several waves whose fp32
+ *              sums meet there and are added in a fixed order.
  * hidden must be a multiple of 64, head_dim a multiple of 8 (even), strides multiples of 8 elements, bases
  * 16-byte aligned.  The weight is streamed once per sweep of 64 rows; the kernel is built for the few rows of
  * a pseudo segment (batch * N up to a few hundred), not for prompt-sized products. */
@@ -127,7 +131,12 @@ typedef struct dapq_qproj {
   int64_t q_stride_layer, q_stride_head, q_stride_row;
 } dapq_qproj;
 int dapq_pseudo_queries(const dapq_qproj* desc, const void* x, const int32_t* token_idx, const void* w_q,
-                        const int32_t* positions, double theta, int32_t pairing, void* q_out, void* stream);
+                        const int32_t* positions, double theta, int32_t pairing, void* q_out, void* workspace,
+                        size_t workspace_bytes, void* stream);
+
+/* Bytes of device workspace dapq_pseudo_queries needs for this description (0 for most multi-layer calls, and
+ * 0 if the description is invalid: the call itself then reports why). */
+size_t dapq_pseudo_queries_workspace_bytes(const dapq_qproj* desc);
 
 /* Sec. 4.2, importance score — S(j) = sum_i Attention(q_i, k_j), summed also over the query heads
  * that share the KV head; Attention is the softmax over the L_p prompt keys of one sequence

@@ -14,7 +14,7 @@ _LIB_PATH = os.path.join(_PKG, "libdapq.so")
 _lib = None
 
 EXPORTS = (
-    "dapq_workspace_bytes", "dapq_last_error", "dapq_rope_apply", "dapq_pseudo_tokens", "dapq_pseudo_queries", "dapq_score", "dapq_score_stats",
+    "dapq_workspace_bytes", "dapq_last_error", "dapq_rope_apply", "dapq_pseudo_tokens", "dapq_pseudo_queries", "dapq_pseudo_queries_workspace_bytes", "dapq_score", "dapq_score_stats",
     "dapq_score_accumulate", "dapq_score_stats_extend", "dapq_pool", "dapq_topk", "dapq_pool_topk", "dapq_gather", "dapq_recall", "dapq_decode_attention",
 )
 
@@ -73,7 +73,8 @@ def load_library():
     lib.dapq_last_error.argtypes = []
     lib.dapq_rope_apply.argtypes = [vp, vp, vp, i64, i32, i32, i64, i64, C.c_double, i32, vp]
     lib.dapq_pseudo_tokens.argtypes = [sp, i32, i32, vp, vp, vp]
-    lib.dapq_pseudo_queries.argtypes = [C.POINTER(Qproj), vp, vp, vp, vp, C.c_double, i32, vp, vp]
+    lib.dapq_pseudo_queries.argtypes = [C.POINTER(Qproj), vp, vp, vp, vp, C.c_double, i32, vp, vp, sz, vp]
+    lib.dapq_pseudo_queries_workspace_bytes.argtypes = [C.POINTER(Qproj)]
     lib.dapq_score.argtypes = [sp, vp, vp, vp, vp, sz, vp]
     lib.dapq_score_stats.argtypes = [sp, vp, vp, vp, vp, sz, vp]
     lib.dapq_score_accumulate.argtypes = [sp, vp, vp, vp, vp, vp, sz, vp]
@@ -86,6 +87,7 @@ def load_library():
     lib.dapq_decode_attention.argtypes = [sp, vp, vp, vp, vp, i32, vp, vp]
     for name in EXPORTS[2:]:
         getattr(lib, name).restype = C.c_int
+    lib.dapq_pseudo_queries_workspace_bytes.restype = sz
     _lib = lib
     return lib
 
@@ -193,6 +195,12 @@ def dapq_pseudo_tokens(shape, first_m, last_n, token_idx, positions, stream=None
                                              _stream(stream)))
 
 
-def dapq_pseudo_queries(desc, x, token_idx, w_q, positions, theta, pairing, q_out, stream=None):
+def pseudo_queries_workspace_bytes(desc) -> int:
+    return int(load_library().dapq_pseudo_queries_workspace_bytes(C.byref(desc)))
+
+
+def dapq_pseudo_queries(desc, x, token_idx, w_q, positions, theta, pairing, q_out, workspace=None, stream=None):
     _check(load_library().dapq_pseudo_queries(C.byref(desc), _ptr(x), _ptr(token_idx), _ptr(w_q), _ptr(positions),
-                                              float(theta), int(pairing), _ptr(q_out), _stream(stream)))
+                                              float(theta), int(pairing), _ptr(q_out), _ptr(workspace),
+                                              0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                              _stream(stream)))

@@ -45,6 +45,8 @@ struct QprojParams {
   int64_t total_tokens;
   int32_t n_layers, rows, hidden, n_features, head_dim;
   int32_t tiles_f, sweeps;
+  int32_t k_splits, kb_per_split;  // hidden blocks are dealt to k_splits waves per tile; > 1 writes fp32 partial sums
+  float* partial;                  // [k_splits][n_layers][sweeps * 32 MB rows][tiles_f * 32 FT features]
 };
 
 constexpr int kRing = 4;          // weight slots; a unit's transfers are issued four units ahead
@@ -94,10 +96,15 @@ __global__ __launch_bounds__(64) void qproj_wave_kernel(QprojParams p) {
   const int total = gridDim.x;
   if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
   id = qp_uniform(id);
-  const int tile = id % p.tiles_f, rest = id / p.tiles_f;
-  const int sweep = qp_uniform(rest % p.sweeps), layer = qp_uniform(rest / p.sweeps);
-  const int f0 = qp_uniform(tile) * (32 * FT), m0 = sweep * (32 * MB);
-  const int n_kb = p.hidden / kBlockK;
+  // the row sweeps of one feature tile are neighbours: they run at the same time and read the tile's weights
+  // from HBM once
+  const int sweep = qp_uniform(id % p.sweeps), rest = id / p.sweeps;
+  const int tile = qp_uniform(rest % p.tiles_f), rest2 = rest / p.tiles_f;
+  const int split = qp_uniform(rest2 % p.k_splits), layer = qp_uniform(rest2 / p.k_splits);
+  const int f0 = tile * (32 * FT), m0 = sweep * (32 * MB);
+  // this wave's hidden blocks [kb0, n_kb)
+  const int kb0 = split * p.kb_per_split;
+  const int n_kb = min(p.hidden / kBlockK, kb0 + p.kb_per_split);
 
   // ---- transfer addressing: lane (r0 = lane / 8, pos = lane % 8) fills LDS chunk `pos` of row 8i + r0 of a
   // tile with the logical chunk pos ^ (((8i + r0) >> 1) & 7) = pos ^ (r0 >> 1) ^ 4 (i & 1)
@@ -148,21 +155,22 @@ __global__ __launch_bounds__(64) void qproj_wave_kernel(QprojParams p) {
                                                (int)voff_x[i], (int)((unsigned)(kb + 1) * 128u), 0, 0);
   };
 
-  // ---- prologue: x rows of block 0, then the first kRing units
-#pragma unroll
-  for (int i = 0; i < XT; ++i)
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(n_kb > 0 ? rsrc_x : rsrc_none,
-                                             (__attribute__((address_space(3))) void*)(xbuf + i * 64), 16, (int)voff_x[i],
-                                             0, 0, 0);
+  // ---- prologue: x rows of the first block, then the first kRing units
   {
+    u32x4* const xb = xbuf + (kb0 % NXB) * (MB * kTileVec);
+#pragma unroll
+    for (int i = 0; i < XT; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(kb0 < n_kb ? rsrc_x : rsrc_none,
+                                               (__attribute__((address_space(3))) void*)(xb + i * 64), 16, (int)voff_x[i],
+                                               (int)((unsigned)kb0 * 128u), 0, 0);
     constexpr int kAhead = kRing / FT;  // hidden blocks the ring spans
 #pragma unroll
     for (int a = 0; a < kAhead; ++a) {
-      issue(a, std::integral_constant<int, 0>{});
-      if constexpr (FT > 1) issue(a, std::integral_constant<int, 1>{});
+      issue(kb0 + a, std::integral_constant<int, 0>{});
+      if constexpr (FT > 1) issue(kb0 + a, std::integral_constant<int, 1>{});
       if constexpr (FT > 2) {
-        issue(a, std::integral_constant<int, 2>{});
-        issue(a, std::integral_constant<int, 3>{});
+        issue(kb0 + a, std::integral_constant<int, 2>{});
+        issue(kb0 + a, std::integral_constant<int, 3>{});
       }
     }
   }
@@ -204,7 +212,7 @@ __global__ __launch_bounds__(64) void qproj_wave_kernel(QprojParams p) {
     issue(kb + kRing / FT, tile_c);
   };
 
-  for (int kb = 0; kb < n_kb; ++kb) {
+  for (int kb = kb0; kb < n_kb; ++kb) {
     unit(kb, std::integral_constant<int, 0>{});
     if constexpr (FT > 1) unit(kb, std::integral_constant<int, 1>{});
     if constexpr (FT > 2) {
@@ -215,6 +223,21 @@ __global__ __launch_bounds__(64) void qproj_wave_kernel(QprojParams p) {
   qp_wait_vm<0>();
 
   // ---- epilogue: accumulator register v of lane (n, h) is feature 8 (v / 4) + 4 h + v % 4 of the tile, row n
+  if (p.partial != nullptr) {
+    // one of several waves of this tile: the fp32 sums go to this split's plane, padding included
+    const int64_t rows_pad = (int64_t)p.sweeps * (32 * MB), feat_pad = (int64_t)p.tiles_f * (32 * FT);
+    float* plane = p.partial + ((int64_t)split * p.n_layers + layer) * rows_pad * feat_pad;
+#pragma unroll
+    for (int rb = 0; rb < MB; ++rb)
+#pragma unroll
+      for (int t = 0; t < FT; ++t)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          float4 o = make_float4(acc[t][rb][4 * g], acc[t][rb][4 * g + 1], acc[t][rb][4 * g + 2], acc[t][rb][4 * g + 3]);
+          *reinterpret_cast<float4*>(plane + (int64_t)(m0 + 32 * rb + n) * feat_pad + f0 + 32 * t + 8 * g + 4 * h) = o;
+        }
+    return;
+  }
 #pragma unroll
   for (int rb = 0; rb < MB; ++rb) {
     const int row = m0 + 32 * rb + n;
@@ -236,32 +259,83 @@ __global__ __launch_bounds__(64) void qproj_wave_kernel(QprojParams p) {
   }
 }
 
+// Adds the planes of the hidden splits in split order (the same order every run), rounds to bf16 once and
+// writes the head layout.  One thread per run of four features of one row.
+__global__ void qproj_reduce_kernel(QprojParams p, int rows_pad, int feat_pad) {
+  const int quads = p.n_features / 4;  // head_dim is a multiple of 8
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t per_layer = (int64_t)p.rows * quads;
+  if (gid >= per_layer * p.n_layers) return;
+  const int layer = (int)(gid / per_layer);
+  const int row = (int)((gid - layer * per_layer) / quads), f = (int)(gid % quads) * 4;
+  const int64_t plane = (int64_t)p.n_layers * rows_pad * feat_pad;
+  const float* src = p.partial + ((int64_t)layer * rows_pad + row) * feat_pad + f;
+  float4 sum = *reinterpret_cast<const float4*>(src);
+  for (int k = 1; k < p.k_splits; ++k) {
+    const float4 v = *reinterpret_cast<const float4*>(src + k * plane);
+    sum.x += v.x;
+    sum.y += v.y;
+    sum.z += v.z;
+    sum.w += v.w;
+  }
+  if (p.token_idx[row] < 0) sum = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+  const int head = f / p.head_dim, c = f - head * p.head_dim;
+  bf16x4 o;
+  o[0] = (__bf16)sum.x;
+  o[1] = (__bf16)sum.y;
+  o[2] = (__bf16)sum.z;
+  o[3] = (__bf16)sum.w;
+  *reinterpret_cast<bf16x4*>(p.q + (int64_t)layer * p.q_stride_layer + (int64_t)head * p.q_stride_head +
+                             (int64_t)row * p.q_stride_row + c) = o;
+}
+
 template <int FT, int MB>
 void launch_qproj(const QprojParams& p, hipStream_t stream) {
-  const int64_t grid = (int64_t)p.tiles_f * p.sweeps * p.n_layers;
+  const int64_t grid = (int64_t)p.tiles_f * p.sweeps * p.k_splits * p.n_layers;
   hipLaunchKernelGGL((qproj_wave_kernel<FT, MB>), dim3((unsigned)grid), dim3(64), 0, stream, p);
 }
 
-}  // namespace
-}  // namespace dapq
+// How a call is cut into waves; a pure function of the description so that the workspace query and the
+// launcher agree.
+struct QprojPlan {
+  int ft, mb, tiles_f, sweeps, k_splits, kb_per_split;
+  size_t workspace_bytes;
+};
 
-using namespace dapq;
+QprojPlan make_qproj_plan(const dapq_qproj& s) {
+  QprojPlan pl;
+  const int64_t features = (int64_t)s.n_q_heads * s.head_dim;
+  // two row blocks per wave unless 32 rows are all there is
+  pl.mb = s.rows > 32 ? 2 : 1;
+  pl.sweeps = (int)(((int64_t)s.rows + 32 * pl.mb - 1) / (32 * pl.mb));
+  // four feature tiles per wave while that still fills the chip (1024 SIMDs), two otherwise
+  const int64_t waves4 = (features + 127) / 128 * pl.sweeps * s.n_layers;
+  pl.ft = waves4 >= 768 ? 4 : 2;
+  pl.tiles_f = (int)((features + 32 * pl.ft - 1) / (32 * pl.ft));
+  // still too few waves: several waves per tile, each with a share of the hidden blocks (at least 8 per wave,
+  // so that the ring's start-up is paid a few times at most), and one pass that adds their sums
+  const int n_kb = s.hidden / kBlockK;
+  const int64_t waves = (int64_t)pl.tiles_f * pl.sweeps * s.n_layers;
+  pl.k_splits = 1;
+  while (pl.k_splits < 16 && waves * pl.k_splits < 768 && n_kb / (pl.k_splits * 2) >= 8) pl.k_splits *= 2;
+  pl.kb_per_split = (n_kb + pl.k_splits - 1) / pl.k_splits;
+  pl.workspace_bytes = pl.k_splits == 1 ? 0
+                                        : (size_t)pl.k_splits * s.n_layers * ((size_t)pl.sweeps * 32 * pl.mb) *
+                                              ((size_t)pl.tiles_f * 32 * pl.ft) * sizeof(float);
+  return pl;
+}
 
-extern "C" DAPQ_API int dapq_pseudo_queries(const dapq_qproj* desc, const void* x, const int32_t* token_idx,
-                                            const void* w_q, const int32_t* positions, double theta, int32_t pairing,
-                                            void* q_out, void* stream) {
+int check_qproj(const dapq_qproj* desc) {
   DAPQ_REQUIRE(desc != nullptr, DAPQ_ERR_INVALID_ARG, "desc must not be NULL");
   const dapq_qproj& s = *desc;
   DAPQ_REQUIRE(s.n_layers >= 1 && s.rows >= 0 && s.hidden >= 1 && s.n_q_heads >= 1 && s.head_dim >= 1 &&
                    s.total_tokens >= 0,
                DAPQ_ERR_INVALID_ARG, "n_layers (%d), hidden (%d), n_q_heads (%d), head_dim (%d) must be >= 1, rows (%d) and total_tokens (%lld) >= 0",
                s.n_layers, s.hidden, s.n_q_heads, s.head_dim, s.rows, (long long)s.total_tokens);
-  DAPQ_REQUIRE(x != nullptr && token_idx != nullptr && w_q != nullptr && q_out != nullptr, DAPQ_ERR_INVALID_ARG,
-               "x, token_idx, w_q and q_out must not be NULL");
   DAPQ_REQUIRE(s.hidden % kBlockK == 0, DAPQ_ERR_UNSUPPORTED, "hidden (%d) must be a multiple of %d", s.hidden, kBlockK);
   DAPQ_REQUIRE(s.head_dim % 8 == 0, DAPQ_ERR_UNSUPPORTED, "head_dim (%d) must be a multiple of 8", s.head_dim);
-  const int64_t features = (int64_t)s.n_q_heads * s.head_dim;
-  DAPQ_REQUIRE(features < ((int64_t)1 << 24), DAPQ_ERR_UNSUPPORTED, "n_q_heads * head_dim is too large");
+  DAPQ_REQUIRE((int64_t)s.n_q_heads * s.head_dim < ((int64_t)1 << 24), DAPQ_ERR_UNSUPPORTED,
+               "n_q_heads * head_dim is too large");
   DAPQ_REQUIRE(s.x_stride_token >= s.hidden && s.w_stride_row >= s.hidden && s.x_stride_layer >= 0 && s.w_stride_layer >= 0,
                DAPQ_ERR_INVALID_ARG, "x_stride_token and w_stride_row must cover hidden, layer strides must be >= 0");
   DAPQ_REQUIRE(s.q_stride_row >= s.head_dim && s.q_stride_head >= s.head_dim && s.q_stride_layer >= 0, DAPQ_ERR_INVALID_ARG,
@@ -270,16 +344,44 @@ extern "C" DAPQ_API int dapq_pseudo_queries(const dapq_qproj* desc, const void* 
                    s.w_stride_layer % 8 == 0 && s.q_stride_row % 8 == 0 && s.q_stride_head % 8 == 0 &&
                    s.q_stride_layer % 8 == 0,
                DAPQ_ERR_UNSUPPORTED, "strides must be multiples of 8 elements");
-  DAPQ_REQUIRE(((uintptr_t)x | (uintptr_t)w_q | (uintptr_t)q_out) % 16 == 0, DAPQ_ERR_UNSUPPORTED,
-               "x, w_q and q_out must be 16-byte aligned");
   // lane offsets inside one layer of x and inside one 32-row weight tile are 32-bit byte offsets
   DAPQ_REQUIRE(s.total_tokens * s.x_stride_token * 2 < ((int64_t)1 << 32), DAPQ_ERR_UNSUPPORTED,
                "one layer of x (total_tokens * x_stride_token * 2 bytes) must be smaller than 4 GiB");
   DAPQ_REQUIRE(s.w_stride_row * 2 * 32 + (int64_t)s.hidden * 2 < ((int64_t)1 << 31), DAPQ_ERR_UNSUPPORTED,
                "w_stride_row is too large");
+  return DAPQ_OK;
+}
+
+}  // namespace
+}  // namespace dapq
+
+using namespace dapq;
+
+extern "C" DAPQ_API size_t dapq_pseudo_queries_workspace_bytes(const dapq_qproj* desc) {
+  if (check_qproj(desc) != DAPQ_OK) return 0;
+  return make_qproj_plan(*desc).workspace_bytes;
+}
+
+extern "C" DAPQ_API int dapq_pseudo_queries(const dapq_qproj* desc, const void* x, const int32_t* token_idx,
+                                            const void* w_q, const int32_t* positions, double theta, int32_t pairing,
+                                            void* q_out, void* workspace, size_t workspace_bytes, void* stream) {
+  const int rc = check_qproj(desc);
+  if (rc != DAPQ_OK) return rc;
+  const dapq_qproj& s = *desc;
+  DAPQ_REQUIRE(x != nullptr && token_idx != nullptr && w_q != nullptr && q_out != nullptr, DAPQ_ERR_INVALID_ARG,
+               "x, token_idx, w_q and q_out must not be NULL");
+  DAPQ_REQUIRE(((uintptr_t)x | (uintptr_t)w_q | (uintptr_t)q_out) % 16 == 0, DAPQ_ERR_UNSUPPORTED,
+               "x, w_q and q_out must be 16-byte aligned");
   if (positions != nullptr) {
     DAPQ_REQUIRE(s.head_dim % 2 == 0 && (pairing == 0 || pairing == 1) && theta > 0.0 && theta < INFINITY,
                  DAPQ_ERR_INVALID_ARG, "rotation needs an even head_dim, pairing 0 or 1 and a finite theta > 0");
+  }
+  const QprojPlan pl = make_qproj_plan(s);
+  if (pl.workspace_bytes > 0) {
+    DAPQ_REQUIRE(workspace != nullptr && workspace_bytes >= pl.workspace_bytes, DAPQ_ERR_WORKSPACE,
+                 "workspace of %zu bytes needed (dapq_pseudo_queries_workspace_bytes), %zu given", pl.workspace_bytes,
+                 workspace != nullptr ? workspace_bytes : (size_t)0);
+    DAPQ_REQUIRE((uintptr_t)workspace % 16 == 0, DAPQ_ERR_UNSUPPORTED, "workspace must be 16-byte aligned");
   }
   if (s.rows == 0) return DAPQ_OK;
 
@@ -299,23 +401,27 @@ extern "C" DAPQ_API int dapq_pseudo_queries(const dapq_qproj* desc, const void* 
   p.n_layers = s.n_layers;
   p.rows = s.rows;
   p.hidden = s.hidden;
-  p.n_features = (int32_t)features;
+  p.n_features = s.n_q_heads * s.head_dim;
   p.head_dim = s.head_dim;
-
-  // Variant: two row blocks per wave unless 32 rows are all there is; four feature tiles per wave while
-  // that still leaves at least one wave per SIMD, two otherwise.
-  const int mb = s.rows > 32 ? 2 : 1;
-  p.sweeps = (s.rows + 32 * mb - 1) / (32 * mb);
-  const int64_t waves4 = (features + 127) / 128 * p.sweeps * s.n_layers;
-  const int ft = waves4 >= 1024 ? 4 : 2;
-  p.tiles_f = (int32_t)((features + 32 * ft - 1) / (32 * ft));
-  DAPQ_REQUIRE((int64_t)p.tiles_f * p.sweeps * s.n_layers < ((int64_t)1 << 31), DAPQ_ERR_UNSUPPORTED, "too many tiles");
+  p.tiles_f = pl.tiles_f;
+  p.sweeps = pl.sweeps;
+  p.k_splits = pl.k_splits;
+  p.kb_per_split = pl.kb_per_split;
+  p.partial = pl.k_splits > 1 ? static_cast<float*>(workspace) : nullptr;
+  DAPQ_REQUIRE((int64_t)p.tiles_f * p.sweeps * p.k_splits * s.n_layers < ((int64_t)1 << 31), DAPQ_ERR_UNSUPPORTED,
+               "too many tiles");
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (ft == 4 && mb == 2) launch_qproj<4, 2>(p, st);
-  else if (ft == 4) launch_qproj<4, 1>(p, st);
-  else if (mb == 2) launch_qproj<2, 2>(p, st);
+  if (pl.ft == 4 && pl.mb == 2) launch_qproj<4, 2>(p, st);
+  else if (pl.ft == 4) launch_qproj<4, 1>(p, st);
+  else if (pl.mb == 2) launch_qproj<2, 2>(p, st);
   else launch_qproj<2, 1>(p, st);
   DAPQ_HIP_LAUNCH_CHECK("qproj_wave_kernel");
+  if (pl.k_splits > 1) {
+    const int64_t work = (int64_t)s.n_layers * s.rows * (p.n_features / 4);
+    hipLaunchKernelGGL(qproj_reduce_kernel, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, st, p,
+                       pl.sweeps * 32 * pl.mb, pl.tiles_f * 32 * pl.ft);
+    DAPQ_HIP_LAUNCH_CHECK("qproj_reduce_kernel");
+  }
 
   if (positions != nullptr) {
     // rotation in place, the same kernel dapq_rope_apply runs: one call if the layers nest as extra heads
@@ -325,9 +431,9 @@ extern "C" DAPQ_API int dapq_pseudo_queries(const dapq_qproj* desc, const void* 
     }
     for (int l = 0; l < s.n_layers; ++l) {
       uint16_t* ql = p.q + (int64_t)l * s.q_stride_layer;
-      const int rc = dapq_rope_apply(ql, ql, positions, s.rows, s.n_q_heads, s.head_dim, s.q_stride_row, s.q_stride_head,
-                                     theta, pairing, stream);
-      if (rc != DAPQ_OK) return rc;
+      const int rc2 = dapq_rope_apply(ql, ql, positions, s.rows, s.n_q_heads, s.head_dim, s.q_stride_row, s.q_stride_head,
+                                      theta, pairing, stream);
+      if (rc2 != DAPQ_OK) return rc2;
     }
   }
   return DAPQ_OK;

@@ -134,23 +134,37 @@ def test_invalid_arguments_of_the_pseudo_query_projection(lib):
         return C.byref(D.Qproj(**f))
     call = lib.dapq_pseudo_queries
     dbl = C.c_double
-    assert call(None, FAKE, FAKE, FAKE, None, dbl(5e5), 0, FAKE, None) == ERR_INVALID
-    assert call(desc(), None, FAKE, FAKE, None, dbl(5e5), 0, FAKE, None) == ERR_INVALID
-    assert call(desc(), FAKE, None, FAKE, None, dbl(5e5), 0, FAKE, None) == ERR_INVALID
-    assert call(desc(), FAKE, FAKE, FAKE, None, dbl(5e5), 0, None, None) == ERR_INVALID
-    assert call(desc(n_layers=0), FAKE, FAKE, FAKE, None, dbl(5e5), 0, FAKE, None) == ERR_INVALID
-    assert call(desc(rows=-1), FAKE, FAKE, FAKE, None, dbl(5e5), 0, FAKE, None) == ERR_INVALID
-    assert call(desc(hidden=4000), FAKE, FAKE, FAKE, None, dbl(5e5), 0, FAKE, None) == ERR_UNSUPPORTED     # not a multiple of 64
+    assert call(None, FAKE, FAKE, FAKE, None, dbl(5e5), 0, FAKE, None, 0, None) == ERR_INVALID
+    assert call(desc(), None, FAKE, FAKE, None, dbl(5e5), 0, FAKE, None, 0, None) == ERR_INVALID
+    assert call(desc(), FAKE, None, FAKE, None, dbl(5e5), 0, FAKE, None, 0, None) == ERR_INVALID
+    assert call(desc(), FAKE, FAKE, FAKE, None, dbl(5e5), 0, None, None, 0, None) == ERR_INVALID
+    assert call(desc(n_layers=0), FAKE, FAKE, FAKE, None, dbl(5e5), 0, FAKE, None, 0, None) == ERR_INVALID
+    assert call(desc(rows=-1), FAKE, FAKE, FAKE, None, dbl(5e5), 0, FAKE, None, 0, None) == ERR_INVALID
+    assert call(desc(hidden=4000), FAKE, FAKE, FAKE, None, dbl(5e5), 0, FAKE, None, 0, None) == ERR_UNSUPPORTED     # not a multiple of 64
     assert b"hidden" in lib.dapq_last_error()
-    assert call(desc(head_dim=12, q_stride_row=16, q_stride_head=1024), FAKE, FAKE, FAKE, None, dbl(5e5), 0, FAKE, None) == ERR_UNSUPPORTED
-    assert call(desc(x_stride_token=2048), FAKE, FAKE, FAKE, None, dbl(5e5), 0, FAKE, None) == ERR_INVALID  # rows overlap
-    assert call(desc(w_stride_row=4100), FAKE, FAKE, FAKE, None, dbl(5e5), 0, FAKE, None) == ERR_UNSUPPORTED  # not 16-byte rows
-    assert call(desc(q_stride_row=64), FAKE, FAKE, FAKE, None, dbl(5e5), 0, FAKE, None) == ERR_INVALID
-    assert call(desc(), FAKE + 2, FAKE, FAKE, None, dbl(5e5), 0, FAKE, None) == ERR_UNSUPPORTED             # misaligned x
-    assert call(desc(total_tokens=1 << 20), FAKE, FAKE, FAKE, None, dbl(5e5), 0, FAKE, None) == ERR_UNSUPPORTED  # 8 GiB layer
+    assert call(desc(head_dim=12, q_stride_row=16, q_stride_head=1024), FAKE, FAKE, FAKE, None, dbl(5e5), 0, FAKE, None, 0, None) == ERR_UNSUPPORTED
+    assert call(desc(x_stride_token=2048), FAKE, FAKE, FAKE, None, dbl(5e5), 0, FAKE, None, 0, None) == ERR_INVALID  # rows overlap
+    assert call(desc(w_stride_row=4100), FAKE, FAKE, FAKE, None, dbl(5e5), 0, FAKE, None, 0, None) == ERR_UNSUPPORTED  # not 16-byte rows
+    assert call(desc(q_stride_row=64), FAKE, FAKE, FAKE, None, dbl(5e5), 0, FAKE, None, 0, None) == ERR_INVALID
+    assert call(desc(), FAKE + 2, FAKE, FAKE, None, dbl(5e5), 0, FAKE, None, 0, None) == ERR_UNSUPPORTED             # misaligned x
+    assert call(desc(total_tokens=1 << 20), FAKE, FAKE, FAKE, None, dbl(5e5), 0, FAKE, None, 0, None) == ERR_UNSUPPORTED  # 8 GiB layer
     assert b"4 GiB" in lib.dapq_last_error()
-    assert call(desc(), FAKE, FAKE, FAKE, FAKE, dbl(0.0), 0, FAKE, None) == ERR_INVALID                       # theta
-    assert call(desc(), FAKE, FAKE, FAKE, FAKE, dbl(5e5), 2, FAKE, None) == ERR_INVALID                       # pairing
+    # a single layer is split along the hidden axis and needs the workspace; all 32 layers at once do not
+    one = dict(n_layers=1)
+    need = D.pseudo_queries_workspace_bytes(D.Qproj(**{**dict(n_layers=1, rows=64, hidden=4096, n_q_heads=32, head_dim=128,
+                                                              total_tokens=1000, x_stride_layer=0, x_stride_token=4096,
+                                                              w_stride_layer=0, w_stride_row=4096, q_stride_layer=0,
+                                                              q_stride_head=64 * 128, q_stride_row=128)}))
+    assert need == 8 * 64 * 4096 * 4                      # eight hidden splits of fp32 sums
+    assert call(desc(**one), FAKE, FAKE, FAKE, None, dbl(5e5), 0, FAKE, None, 0, None) == ERR_WORKSPACE
+    assert call(desc(**one), FAKE, FAKE, FAKE, None, dbl(5e5), 0, FAKE, FAKE, need - 1, None) == ERR_WORKSPACE
+    assert D.pseudo_queries_workspace_bytes(D.Qproj(n_layers=32, rows=64, hidden=4096, n_q_heads=32, head_dim=128,
+                                                    total_tokens=1000, x_stride_layer=0, x_stride_token=4096,
+                                                    w_stride_layer=0, w_stride_row=4096, q_stride_layer=0,
+                                                    q_stride_head=64 * 128, q_stride_row=128)) == 0
+    assert D.pseudo_queries_workspace_bytes(D.Qproj(n_layers=1, rows=64, hidden=100)) == 0   # invalid: the call says why
+    assert call(desc(), FAKE, FAKE, FAKE, FAKE, dbl(0.0), 0, FAKE, None, 0, None) == ERR_INVALID                       # theta
+    assert call(desc(), FAKE, FAKE, FAKE, FAKE, dbl(5e5), 2, FAKE, None, 0, None) == ERR_INVALID                       # pairing
 
 
 def test_score_plan_covers_every_shape(lib):

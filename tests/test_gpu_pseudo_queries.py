@@ -59,7 +59,8 @@ def run_case(H, seed, layers, tokens, hidden, Hq, d, tok, positions=None, pairin
                      x_stride_layer=0 if shared_x else tokens * xs, x_stride_token=xs,
                      w_stride_layer=F * wsr, w_stride_row=wsr,
                      q_stride_layer=Hq * q_rows * d, q_stride_head=q_rows * d, q_stride_row=d)
-    H.D.dapq_pseudo_queries(desc, x_t, tok_t, w_t, pos_t, theta, pairing, q_t)
+    ws = torch.empty(max(H.D.pseudo_queries_workspace_bytes(desc), 16), dtype=torch.uint8, device="cuda")
+    H.D.dapq_pseudo_queries(desc, x_t, tok_t, w_t, pos_t, theta, pairing, q_t, ws)
     torch.cuda.synchronize()
     got = H.host_bits(q_t)
     assert (got[:, :, rows:] == 0x7FC1).all(), "rows past `rows` were written"
@@ -101,6 +102,9 @@ SHAPES = [
     (1, 300, 1024, 4, 128, 130),  # three sweeps; head_dim 128
     (1, 31, 320, 2, 128, 32),     # exactly one row block (one-block variant)
     (2, 64, 64, 8, 16, 1),        # a single row
+    (1, 40, 1088, 2, 64, 40),     # 17 hidden blocks dealt to two waves per tile (9 + 8), sums added from the workspace
+    (1, 100, 4096, 8, 128, 64),   # one layer of a 4096-wide model: eight waves per tile
+    (2, 30, 2048, 1, 72, 7),      # 72 features: a tile with 8 live features, four-way split
 ]
 
 
@@ -203,7 +207,8 @@ def test_queries_feed_the_score_path(H):
     desc = H.D.Qproj(n_layers=1, rows=N, hidden=hidden, n_q_heads=Hq, head_dim=d, total_tokens=L, x_stride_layer=0,
                      x_stride_token=hidden, w_stride_layer=0, w_stride_row=hidden, q_stride_layer=Hq * N * d,
                      q_stride_head=N * d, q_stride_row=d)
-    H.D.dapq_pseudo_queries(desc, H.dev_bf16(x_bits), tok, H.dev_bf16(w_bits), pos, 500000.0, 0, prob.q)
+    ws = torch.empty(max(H.D.pseudo_queries_workspace_bytes(desc), 16), dtype=torch.uint8, device="cuda")
+    H.D.dapq_pseudo_queries(desc, H.dev_bf16(x_bits), tok, H.dev_bf16(w_bits), pos, 500000.0, 0, prob.q, ws)
     S = prob.score().cpu().numpy().astype(np.float64)
     src, want_pos = O.pseudo_tokens(L, m, n)
     q_want = O.pseudo_queries(x_bits, src, w_bits, Hq, positions=want_pos)           # [Hq, N, d]
