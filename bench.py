@@ -175,6 +175,37 @@ class Context:
         mark(5)
 
 
+class pseudo_query_problem:
+    """The queries of the pseudo tokens for the benchmark's workload (Sec. 4.1 upstream of the step): model width
+    H_q * d, one N(0, 1/hidden) query weight per layer, 2048 stand-in rows of N(0,1) projection input per layer, and
+    pseudo tokens that copy the first 4 and the last N - 4 of them in every sequence."""
+
+    def __init__(self, ctx, rows_per_layer=2048):
+        import torch
+        D, w, dev = ctx.D, ctx.w, ctx.dev
+        d, Hq, N, nl, B = w.head_dim, w.n_q_heads, w.n_pseudo, w.n_layers, w.batch
+        self.ctx, self.hidden, self.T = ctx, Hq * d, rows_per_layer
+        hidden, T = self.hidden, self.T
+        g = torch.Generator(device=dev).manual_seed(2)
+        self.x = torch.randn((nl, T, hidden), generator=g, device=dev).to(torch.bfloat16)
+        self.w_q = torch.empty((nl, Hq * d, hidden), dtype=torch.bfloat16, device=dev)
+        for li in range(nl):
+            self.w_q[li].copy_(torch.randn((Hq * d, hidden), generator=g, device=dev) * hidden ** -0.5)
+        first = min(4, N)
+        self.src = torch.cat([torch.arange(first), torch.arange(T - (N - first), T)]).to(torch.int32).repeat(B).to(dev)
+        self.desc = D.Qproj(n_layers=nl, rows=B * N, hidden=hidden, n_q_heads=Hq, head_dim=d, total_tokens=T,
+                            x_stride_layer=T * hidden, x_stride_token=hidden, w_stride_layer=Hq * d * hidden,
+                            w_stride_row=hidden, q_stride_layer=Hq * B * N * d, q_stride_head=B * N * d, q_stride_row=d)
+        self.q = torch.empty((nl, Hq, B, N, d), dtype=torch.bfloat16, device=dev)
+        self.pos = ctx.q_pos.reshape(-1).contiguous()
+        self.ws = torch.empty(max(D.pseudo_queries_workspace_bytes(self.desc), 16), dtype=torch.uint8, device=dev)
+
+    def run(self, rotate=True):
+        ctx = self.ctx
+        ctx.D.dapq_pseudo_queries(self.desc, self.x, self.src, self.w_q, self.pos if rotate else None, ctx.w.theta, 0,
+                                  self.q, self.ws, ctx.stream)
+
+
 def time_extras(ctx, reps):
     """Event-timed averages of the entry points that sit around the eviction step, on the step's own outputs."""
     import torch
@@ -196,23 +227,9 @@ def time_extras(ctx, reps):
     if w.budget <= 8192:
         calls["decode_attention"] = lambda: D.dapq_decode_attention(ctx.shape, qd, ctx.k_out, ctx.v_out, ctx.count, w.budget,
                                                                     dec, stream)
-    # the queries of the pseudo tokens from the rows of the tokens they copy (first 4 + last N-4 of each prompt):
-    # model width H_q * d, one weight per layer, 2048 stand-in rows of projection input per layer
-    hidden, T = Hq * d, 2048
-    xin = torch.randn((nl, T, hidden), generator=g, device=dev).to(torch.bfloat16)
-    wq = torch.empty((nl, Hq * d, hidden), dtype=torch.bfloat16, device=dev)
-    for li in range(nl):
-        wq[li].copy_(torch.randn((Hq * d, hidden), generator=g, device=dev) * hidden ** -0.5)
-    src = torch.cat([torch.arange(4), torch.arange(T - (N - 4), T)]).to(torch.int32).repeat(B).to(dev)
-    desc = D.Qproj(n_layers=nl, rows=B * N, hidden=hidden, n_q_heads=Hq, head_dim=d, total_tokens=T,
-                   x_stride_layer=T * hidden, x_stride_token=hidden, w_stride_layer=Hq * d * hidden, w_stride_row=hidden,
-                   q_stride_layer=Hq * B * N * d, q_stride_head=B * N * d, q_stride_row=d)
-    qout = torch.empty((nl, Hq, B, N, d), dtype=torch.bfloat16, device=dev)
-    pos = ctx.q_pos.reshape(-1).contiguous()
-    pws = torch.empty(max(D.pseudo_queries_workspace_bytes(desc), 16), dtype=torch.uint8, device=dev)
-    calls["pseudo_queries"] = lambda: D.dapq_pseudo_queries(desc, xin, src, wq, pos, w.theta, 0, qout, pws, stream)
-    calls["pseudo_queries_no_rotation"] = lambda: D.dapq_pseudo_queries(desc, xin, src, wq, None, w.theta, 0, qout, pws,
-                                                                        stream)
+    pq = pseudo_query_problem(ctx)
+    calls["pseudo_queries"] = lambda: pq.run(rotate=True)
+    calls["pseudo_queries_no_rotation"] = lambda: pq.run(rotate=False)
     res = {}
     for name, fn in calls.items():
         fn()

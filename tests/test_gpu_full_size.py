@@ -139,3 +139,41 @@ def test_full_size_ragged_batch(env):
         assert np.array_equal(H.host_bits(ctx.k_out[li, b, kv]), k[keep])
         assert np.array_equal(H.host_bits(ctx.v_out[li, b, kv]), v[keep])
         announce(f"full size C3: layer {li} seq {b} head {kv}: max rel err {worst:.2e}, set {cls}")
+
+
+def test_full_size_pseudo_queries(env):
+    """The queries of the pseudo tokens at the benchmark's shape (32 layers of a 4096-wide model, 64 pseudo tokens),
+    in the configuration bench.py times: three layers against the oracle element by element, every layer against
+    a property that holds at any size (the rotation keeps each channel pair's norm)."""
+    bench, H = env
+    w = W.workload("C2")
+    announce("full size C2: queries of the pseudo tokens")
+    ctx = bench.Context(w, 3, torch.device("cuda:0"))
+    pq = bench.pseudo_query_problem(ctx)
+    assert H.D.pseudo_queries_workspace_bytes(pq.desc) == 0          # the launch the benchmark times needs no split
+    pq.run(rotate=False)
+    torch.cuda.synchronize()
+    pre = pq.q.clone()
+    pq.run(rotate=True)
+    torch.cuda.synchronize()
+    rot = pq.q
+    d, Hq, N = w.head_dim, w.n_q_heads, w.n_pseudo
+    src = pq.src.cpu().numpy()
+    pos = pq.pos.cpu().numpy()
+    assert torch.isfinite(pre.float()).all() and torch.isfinite(rot.float()).all()
+    # any size: per channel pair the rotation keeps the norm (up to the two bf16 roundings)
+    p, r = pre.float(), rot.float()
+    n_p = torch.hypot(p[..., : d // 2], p[..., d // 2:])
+    n_r = torch.hypot(r[..., : d // 2], r[..., d // 2:])
+    assert ((n_p - n_r).abs() <= 2.0 ** -7 * n_p + 1e-3).all()
+    for layer in (0, 13, 31):
+        x_bits = H.host_bits(pq.x[layer])
+        w_bits = H.host_bits(pq.w_q[layer])
+        want_pre = O.pseudo_queries(x_bits, src, w_bits, Hq)                        # [Hq, rows, d]
+        got_pre = H.host_bits(pre[layer]).reshape(Hq, -1, d)
+        assert (got_pre == want_pre).mean() > 0.99
+        g, e = O.bf16_bits_to_f64(got_pre), O.bf16_bits_to_f64(want_pre)
+        assert (np.abs(g - e) <= 2.0 ** -7 * np.abs(e) + 1e-4).all()               # one bf16 step at most
+        want_rot = O.pseudo_queries(x_bits, src, w_bits, Hq, positions=pos, theta=w.theta)
+        got_rot = H.host_bits(rot[layer]).reshape(Hq, -1, d)
+        assert (got_rot == want_rot).mean() > 0.98
