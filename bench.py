@@ -175,6 +175,24 @@ class Context:
         mark(5)
 
 
+def stream_copy_gbs(dev, n_bytes=1 << 30, reps=10):
+    """Bytes per second (read + write) of torch's device-to-device copy of a 1 GiB tensor: the practical ceiling of a
+    pure stream on this machine, reported beside the 8 TB/s data-sheet peak."""
+    import torch
+    a = torch.empty(n_bytes, dtype=torch.uint8, device=dev)
+    b = torch.empty_like(a)
+    a.zero_()
+    b.copy_(a)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        b.copy_(a)
+    e1.record()
+    torch.cuda.synchronize()
+    return 2.0 * n_bytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+
 class pseudo_query_problem:
     """The queries of the pseudo tokens for the benchmark's workload (Sec. 4.1 upstream of the step): model width
     H_q * d, one N(0, 1/hidden) query weight per layer, 2048 stand-in rows of N(0,1) projection input per layer, and
@@ -318,6 +336,12 @@ def main():
         "design_frac_of_peak": step_design / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "mfma_frac_of_peak": {n: flops_pass / (per[n] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS for n in bytes_pass},
     }
+
+    # what a plain device copy moves on this machine, for scale next to the data-sheet peak (outside the timed region)
+    copy_gbs = stream_copy_gbs(dev)
+    step_hbm["stream_copy_gbs"] = copy_gbs
+    step_hbm["design_frac_of_stream_copy"] = step_hbm["design_gbs"] / copy_gbs
+    roofline["hbm_frac_of_stream_copy"] = hbm_gbs / copy_gbs
 
     out = {
         "metric": "prompt keys scored+evicted/sec (all layers x KV heads)", "value": value, "unit": "keys/s",
