@@ -2,14 +2,16 @@
 // uses only the compressed cache): out = softmax(q K_c^T / sqrt(d_k)) V_c per query head, over the first
 // count rows of the KV head's compact cache as dapq_gather wrote it.
 //
-// One workgroup of 256 threads per (layer, sequence, KV head); it serves the query heads of the group
+// One workgroup of 1024 threads per (layer, sequence, KV head); it serves the query heads of the group
 // four at a time, so the cache rows are read once per four query heads.  The cache of a head is at
-// most a few thousand rows: the step is a matrix-vector product bound by reading K_c and V_c.
+// most a few thousand rows: the step is a matrix-vector product bound by reading K_c and V_c, and with
+// one workgroup per head what matters is how many rows a compute unit has in flight: sixteen waves, one
+// row per thread in phase 1, four rows per thread and trip in phase 3.
 //   phase 1  a thread takes cache rows in turn: logits = q_h . k for the four heads (bf16 products, fp32
 //            accumulation), kept in LDS
 //   phase 2  weights 2^(c*logit - max) in LDS, their sums
-//   phase 3  a thread owns two channels and a quarter of the rows: acc_h += weight_h * v, rows of V read
-//            as contiguous 256-byte lines by each wave; the four partial sums meet in LDS
+//   phase 3  a thread owns two channels and a sixteenth of the rows: acc_h += weight_h * v, rows of V read
+//            as contiguous 256-byte lines by each wave; the sixteen partial sums meet in LDS
 #include <math.h>
 
 #include "dapq_internal.h"
@@ -17,7 +19,8 @@
 namespace dapq {
 namespace {
 
-constexpr int kDecodeThreads = 256;
+constexpr int kDecodeThreads = 1024;
+constexpr int kDecodeWaves = kDecodeThreads / 64;
 constexpr int kDecodeMaxRows = 8192;  // logits of four query heads in LDS (128 KB)
 constexpr int kDecodeHeads = 4;       // query heads served per sweep over the cache
 
@@ -34,7 +37,7 @@ struct DecodeParams {
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xFFFF0000u); }
 
-// Maximum or sum over the workgroup of one value per head; red: [4 waves][kDecodeHeads].
+// Maximum or sum over the workgroup of one value per head; red: [kDecodeWaves][kDecodeHeads].
 template <bool IS_MAX>
 __device__ __forceinline__ void block_reduce(float (&v)[kDecodeHeads], float* red) {
 #pragma unroll
@@ -56,7 +59,7 @@ __device__ __forceinline__ void block_reduce(float (&v)[kDecodeHeads], float* re
   for (int h = 0; h < kDecodeHeads; ++h) {
     float r = red[h];
 #pragma unroll
-    for (int w = 1; w < kDecodeThreads / 64; ++w) r = IS_MAX ? fmaxf(r, red[w * kDecodeHeads + h]) : r + red[w * kDecodeHeads + h];
+    for (int w = 1; w < kDecodeWaves; ++w) r = IS_MAX ? fmaxf(r, red[w * kDecodeHeads + h]) : r + red[w * kDecodeHeads + h];
     v[h] = r;
   }
 }
@@ -64,9 +67,9 @@ __device__ __forceinline__ void block_reduce(float (&v)[kDecodeHeads], float* re
 __global__ __launch_bounds__(kDecodeThreads) void decode_attention_kernel(DecodeParams p) {
   extern __shared__ float lds[];
   float* qs = lds;                                  // [4][128] the queries in fp32
-  float* red = qs + kDecodeHeads * kHeadDim;        // [4 waves][4]
-  float* part = red + 4 * kDecodeHeads;             // [4 quarters][4][128] partial outputs
-  float* w = part + 4 * kDecodeHeads * kHeadDim;    // [4][budget] logits, then weights
+  float* red = qs + kDecodeHeads * kHeadDim;                   // [waves][4]
+  float* w = red + kDecodeWaves * kDecodeHeads;                // [4][budget] logits, then weights
+  float* part = w;                                             // [waves][4][128] partial outputs, once the weights are spent
   const int tid = threadIdx.x;
   const int kv = blockIdx.x, seq = blockIdx.y, layer = blockIdx.z;
   const int g = p.n_q_heads / p.n_kv_heads;
@@ -128,11 +131,28 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_attention_kernel(Decode
     }
     block_reduce<false>(sum, red);  // its barriers also publish the weights
 
-    // phase 3: weighted sums of the value rows
-    const int c2 = tid & 63, quarter = tid >> 6;
+    // phase 3: weighted sums of the value rows; a wave takes every kDecodeWaves-th row, four rows per trip
+    const int c2 = tid & 63, part_id = tid >> 6;
     float a0[kDecodeHeads] = {0.0f, 0.0f, 0.0f, 0.0f}, a1[kDecodeHeads] = {0.0f, 0.0f, 0.0f, 0.0f};
-    for (int j = quarter; j < n; j += 4) {
-      const uint32_t u = reinterpret_cast<const uint32_t*>(vc + (int64_t)j * kHeadDim)[c2];
+    const uint32_t* vcol = reinterpret_cast<const uint32_t*>(vc) + c2;
+    int j = part_id;
+    for (; j + 3 * kDecodeWaves < n; j += 4 * kDecodeWaves) {
+      uint32_t u[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) u[r] = vcol[(int64_t)(j + r * kDecodeWaves) * (kHeadDim / 2)];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float v0 = bf16_lo(u[r]), v1 = bf16_hi(u[r]);
+#pragma unroll
+        for (int h = 0; h < kDecodeHeads; ++h) {
+          const float e = w[h * p.budget + j + r * kDecodeWaves];
+          a0[h] = fmaf(e, v0, a0[h]);
+          a1[h] = fmaf(e, v1, a1[h]);
+        }
+      }
+    }
+    for (; j < n; j += kDecodeWaves) {
+      const uint32_t u = vcol[(int64_t)j * (kHeadDim / 2)];
       const float v0 = bf16_lo(u), v1 = bf16_hi(u);
 #pragma unroll
       for (int h = 0; h < kDecodeHeads; ++h) {
@@ -141,16 +161,18 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_attention_kernel(Decode
         a1[h] = fmaf(e, v1, a1[h]);
       }
     }
+    __syncthreads();  // every wave is done with the weights: their memory takes the partial sums
 #pragma unroll
     for (int h = 0; h < kDecodeHeads; ++h) {
-      part[(quarter * kDecodeHeads + h) * kHeadDim + 2 * c2] = a0[h];
-      part[(quarter * kDecodeHeads + h) * kHeadDim + 2 * c2 + 1] = a1[h];
+      part[(part_id * kDecodeHeads + h) * kHeadDim + 2 * c2] = a0[h];
+      part[(part_id * kDecodeHeads + h) * kHeadDim + 2 * c2 + 1] = a1[h];
     }
     __syncthreads();
     for (int e = tid; e < nh * kHeadDim; e += kDecodeThreads) {
       const int h = e / kHeadDim;
-      const float o = (part[e] + part[kDecodeHeads * kHeadDim + e]) +
-                      (part[2 * kDecodeHeads * kHeadDim + e] + part[3 * kDecodeHeads * kHeadDim + e]);
+      float o = 0.0f;
+#pragma unroll
+      for (int q = 0; q < kDecodeWaves; ++q) o += part[q * kDecodeHeads * kHeadDim + e];  // fixed order
       p.out[qrow0 * kHeadDim + e] = o / sum[h];
     }
   }
@@ -185,8 +207,10 @@ extern "C" DAPQ_API int dapq_decode_attention(const dapq_shape* shape, const voi
   p.n_kv_heads = shape->n_kv_heads;
   p.budget = budget;
   p.c = shape->scale * 1.4426950408889634f;
-  const int lds_bytes = (kDecodeHeads * kHeadDim + 4 * kDecodeHeads + 4 * kDecodeHeads * kHeadDim + kDecodeHeads * budget) *
-                        (int)sizeof(float);
+  const int shared_floats = kDecodeHeads * budget > kDecodeWaves * kDecodeHeads * kHeadDim
+                                ? kDecodeHeads * budget
+                                : kDecodeWaves * kDecodeHeads * kHeadDim;  // weights, later the partial sums
+  const int lds_bytes = (kDecodeHeads * kHeadDim + kDecodeWaves * kDecodeHeads + shared_floats) * (int)sizeof(float);
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_attention_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
   if (e != hipSuccess) return fail(DAPQ_ERR_HIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));

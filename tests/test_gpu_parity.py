@@ -549,6 +549,35 @@ def test_decode_step_over_the_compact_cache(H, Hq, Hkv):
                 assert np.abs(out[l, b, hq] - full).max() <= 2 * m * vmax + 1e-5 * vmax
 
 
+@pytest.mark.parametrize("budget", [983, 2048, 8192])
+def test_decode_attention_large_caches(H, budget):
+    """The decode step on compact caches of the sizes the budgets of the workloads give (and the largest the entry
+    point takes), filled directly: full, partly filled, one-row and empty heads."""
+    announce(f"decode attention over caches of {budget} rows")
+    layers, batch, Hq, Hkv, d = 1, 2, 8, 2, 128
+    r = np.random.default_rng(budget)
+    kc = W.to_bf16_bits(r.standard_normal((layers, batch, Hkv, budget, d)))
+    vc = W.to_bf16_bits(r.standard_normal((layers, batch, Hkv, budget, d)))
+    qd = W.to_bf16_bits(r.standard_normal((layers, batch, Hq, d)) * 2.0)
+    count = np.array([[[budget, budget // 3], [1, 0]]], dtype=np.int32)
+    q0, k0, v0, cu = random_problem(1, layers, [8] * batch, Hq, Hkv, 4)
+    prob = H.Problem(q0, k0, v0, Hkv, cu, "thd")                                  # only the head counts and the scale are used
+    out = torch.full((layers, batch, Hq, d), float("nan"), dtype=torch.float32, device="cuda")
+    H.D.dapq_decode_attention(prob.shape, H.dev_bf16(qd), H.dev_bf16(kc), H.dev_bf16(vc),
+                              torch.from_numpy(count).cuda(), budget, out)
+    out = out.cpu().numpy().astype(np.float64)
+    kf, vf, qf = O.bf16_bits_to_f64(kc), O.bf16_bits_to_f64(vc), O.bf16_bits_to_f64(qd)
+    for b in range(batch):
+        for hq in range(Hq):
+            kv = hq // (Hq // Hkv)
+            n = int(count[0, b, kv])
+            if n == 0:
+                assert np.all(out[0, b, hq] == 0.0)
+                continue
+            want = O.decode_attention(qf[0, b, hq][None], kf[0, b, kv, :n], vf[0, b, kv, :n])[0]
+            assert np.all(np.abs(out[0, b, hq] - want) <= 1e-5 * np.abs(vf[0, b, kv, :n]).max() + 1e-4 * np.abs(want)), (b, hq)
+
+
 def test_pseudo_tokens_and_positions(H):
     """Sec. 4.1 positions and the first-m / last-n content choice, for a ragged and a dense batch."""
     announce("pseudo tokens (first m + last n) and their positions")
