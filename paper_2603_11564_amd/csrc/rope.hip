@@ -49,7 +49,22 @@ __global__ void rope_kernel(const uint16_t* __restrict__ x_in, uint16_t* x_out, 
   uint16_t* dst = x_out + row * stride_row;
   const int hd0 = blockIdx.y * heads_per_thread;
   const int hd1 = hd0 + heads_per_thread < heads ? hd0 + heads_per_thread : heads;
-  for (int hd = hd0; hd < hd1; ++hd) {
+  int hd = hd0;
+  for (; hd + 4 <= hd1; hd += 4) {  // four heads per trip: eight loads in flight before the first rotation
+    uint16_t ra[4], rb[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      ra[u] = src[(int64_t)(hd + u) * stride_head + ia];
+      rb[u] = src[(int64_t)(hd + u) * stride_head + ib];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const double a = bf16_to_f64(ra[u]), b = bf16_to_f64(rb[u]);
+      dst[(int64_t)(hd + u) * stride_head + ia] = f64_to_bf16(a * cs - b * sn);
+      dst[(int64_t)(hd + u) * stride_head + ib] = f64_to_bf16(b * cs + a * sn);
+    }
+  }
+  for (; hd < hd1; ++hd) {
     const double a = bf16_to_f64(src[(int64_t)hd * stride_head + ia]);
     const double b = bf16_to_f64(src[(int64_t)hd * stride_head + ib]);
     dst[(int64_t)hd * stride_head + ia] = f64_to_bf16(a * cs - b * sn);
