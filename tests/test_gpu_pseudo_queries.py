@@ -119,6 +119,29 @@ def test_projection_matches_oracle(H, case):
     assert equal > 0.99, equal
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_projection_random_shapes(H, seed):
+    """Seeded random shapes: layers, rows, hidden blocks, head counts and sizes, padded strides, missing sources,
+    one x for all layers or one per layer -- every combination of kernel variant, sweep count and hidden split that
+    small shapes can reach."""
+    r = np.random.default_rng(5000 + seed)
+    layers = int(r.integers(1, 4))
+    rows = int(r.choice([1, 2, 31, 32, 33, 63, 64, 65, 96, 129, int(r.integers(1, 200))]))
+    hidden = 64 * int(r.choice([1, 2, 3, 5, 8, 16, 17, 33, 40]))
+    Hq = int(r.integers(1, 9))
+    d = int(r.choice([8, 16, 24, 32, 64, 128]))
+    tokens = int(r.integers(1, 120))
+    tok = r.integers(-1, tokens, rows).tolist()
+    x_pad, w_pad = int(r.choice([0, 8, 64])), int(r.choice([0, 8, 72]))
+    shared = bool(r.integers(0, 2))
+    announce(f"pseudo queries random {seed}: layers {layers} rows {rows} hidden {hidden} Hq {Hq} d {d} tokens {tokens} "
+             f"pads {x_pad},{w_pad} shared_x {shared}")
+    got, x_bits, w_bits = run_case(H, 900 + seed, layers, tokens, hidden, Hq, d, tok, x_pad=x_pad, w_pad=w_pad,
+                                   shared_x=shared, q_pad_rows=int(r.integers(0, 3)))
+    equal = check_projection(got, x_bits, w_bits, tok, Hq, hidden, shared_x=shared)
+    assert equal > 0.98, equal
+
+
 def test_projection_many_waves_variants(H):
     """Grids of 1024 and more waves take the four-tile variants: 32 layers x 4096 features, 64 rows and 32 rows."""
     for rows in (64, 32, 100):
