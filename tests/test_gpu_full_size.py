@@ -73,10 +73,21 @@ def check_all_heads(ctx, w):
             assert torch.equal(dst[:, b, :, :n].view(torch.int16), want), name
 
 
-@pytest.mark.parametrize("name,samples", [("C2", [(0, 0), (17, 5), (31, 7)])])
-def test_full_size_dense_workload(env, name, samples):
+@pytest.mark.parametrize("name,layers,samples", [
+    ("C2", None, [(0, 0), (17, 5), (31, 7)]),
+    # the 70B-class shape at its full 128k prompt, 2 of its 80 layers: 512 query rows per KV head (two row groups)
+    # and heads of 131072 keys, which take the streaming selection kernel and the separate pooling kernel
+    ("C5", 2, [(0, 3), (1, 7)]),
+    # the ends of the window-size sweep at its 64k prompt, one layer each: 64 and 2048 query rows per KV head
+    ("C4:16", 1, [(0, 1)]),
+    ("C4:512", 1, [(0, 6)]),
+])
+def test_full_size_dense_workload(env, name, layers, samples):
     bench, H = env
-    w = W.workload(name)
+    from dataclasses import replace
+    w = W.workload(*((name.split(":")[0], int(name.split(":")[1])) if ":" in name else (name,)))
+    if layers is not None:
+        w = replace(w, n_layers=layers)
     seed = 0
     L = w.seq_len
     announce(f"full size {name}: building the workload")
