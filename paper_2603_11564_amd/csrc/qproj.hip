@@ -19,7 +19,12 @@
 //   * rows are 128 B apart in LDS; 16-byte chunks are XOR-swizzled by bits 1..3 of the row so that
 //     16 consecutive rows reading the same logical chunk hit 16 different bank groups.
 // The weight is the A operand (D[feature][row]): a lane ends up with runs of four consecutive
-// features of one row, stored as 8 bytes.  Nothing is shared between waves: no barrier, no workspace.
+// features of one row, stored as 8 bytes.  Nothing is shared between waves: no barrier anywhere.
+// Work items are numbered sweep -> feature tile -> hidden split -> layer and dealt to the eight XCDs in
+// contiguous ranges: the waves that read the same gathered rows share an L2, and the row sweeps of one
+// feature tile run side by side, so the tile's weights leave HBM once.
+// A call with too few tiles to fill the chip (a single layer) deals the hidden blocks of a tile to
+// several waves; their fp32 sums go to a workspace and qproj_reduce_kernel adds them in a fixed order.
 #include <math.h>
 
 #include <type_traits>
