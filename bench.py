@@ -265,7 +265,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1 "
-              "(the path shards by layer / KV head / sequence with no communication, see DESIGN.md)",
+              "(the path would shard by layer, KV head or sequence with no communication between the GPUs)",
               file=sys.stderr)
         sys.exit(2)
     import numpy as np
