@@ -197,3 +197,32 @@ def test_product_path_does_not_touch_the_oracle():
                 assert "oracle" not in text, f
     assert "oracle" not in open(os.path.join(ROOT, "include", "dapq.h")).read()
     assert "paper_2603_11564_amd" not in open(os.path.join(ROOT, "oracle", "dapq_oracle.py")).read()
+
+
+def test_header_is_plain_c_and_links_from_a_c_program(tmp_path):
+    """include/dapq.h compiles as strict C99 on its own, its structs have the sizes the ctypes mirrors assume, and
+    a C program linked against libdapq.so reaches every declared entry point (no compute call: nothing here needs
+    a GPU)."""
+    import subprocess
+    header = open(os.path.join(ROOT, "include", "dapq.h")).read()
+    names = sorted(set(re.findall(r"\b(dapq_[a-z0-9_]+)\s*\(", header)))
+    src = tmp_path / "abi.c"
+    src.write_text(
+        '#include "dapq.h"\n#include <stdio.h>\n#include <string.h>\n'
+        "int main(void) {\n"
+        "  void (*fns[])(void) = {" + ", ".join(f"(void (*)(void)){n}" for n in names) + "};\n"
+        "  size_t i, n = sizeof fns / sizeof fns[0];\n"
+        "  for (i = 0; i < n; ++i) if (!fns[i]) return 1;\n"
+        "  if (dapq_workspace_bytes(NULL) != 0) return 2;            /* invalid shape: 0, and a message */\n"
+        "  if (strlen(dapq_last_error()) == 0) return 3;\n"
+        "  if (dapq_gather(NULL, NULL, NULL, NULL, NULL, 1, NULL, NULL, NULL) != DAPQ_ERR_INVALID_ARG) return 4;\n"
+        '  printf("%zu %zu %zu\\n", n, sizeof(dapq_shape), sizeof(dapq_qproj));\n'
+        "  return 0;\n}\n")
+    exe = tmp_path / "abi"
+    libdir = os.path.dirname(binding.lib_path())
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror",
+                    "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe), "-L", libdir, "-ldapq",
+                    f"-Wl,-rpath,{libdir}", "-Wl,-rpath,/opt/rocm/lib"], check=True, capture_output=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert int(out[0]) == len(binding.EXPORTS)
+    assert int(out[1]) == C.sizeof(binding.Shape) and int(out[2]) == C.sizeof(binding.Qproj)
