@@ -356,6 +356,26 @@ def test_recall_definition():
     assert O.recall([5], [5]) == 1.0 and O.recall([5, 6], [7]) == 0.0
 
 
+def test_compress_selects_on_the_pooled_scores():
+    # one query, keys on a line: key 5 dominates, keys 0 and 10 come next, the rest are equal and small.  On the raw
+    # scores the three best are {0, 5, 10}; pooled with a window of 3 the neighbours of key 5 inherit its score and
+    # the three best are {4, 5, 6} (Sec. 1 / Sec. 5.1: selection runs on the pooled accumulated scores)
+    L, d = 12, 2
+    k = np.zeros((1, L, 1, d))
+    k[0, 5, 0, 0], k[0, 0, 0, 0], k[0, 10, 0, 0] = 8.0, 4.0, 4.0
+    q = np.zeros((1, 1, 1, 1, d))
+    q[0, 0, 0, 0, 0] = 1.0
+    qb, kb = W.to_bf16_bits(q), W.to_bf16_bits(k)
+    vb = np.arange(L * d, dtype=np.uint16).reshape(1, L, 1, d)
+    raw = O.compress(qb, kb, vb, 1, 3, width=1)
+    assert raw["idx"][0, 0, 0].tolist() == [0, 5, 10]
+    pooled = O.compress(qb, kb, vb, 1, 3, width=3)
+    assert pooled["idx"][0, 0, 0].tolist() == [4, 5, 6]
+    assert pooled["P"][0, 0, 4] == pooled["S"][0, 0, 5] == pooled["P"][0, 0, 6]
+    assert pooled["v_out"][0, 0, 0].tolist() == [[8, 9], [10, 11], [12, 13]]      # rows 4, 5, 6 of V, bit for bit
+    assert pooled["count"][0, 0, 0] == 3
+
+
 # ------------------------------------------------------------------ extended sequence (Sec. 4.1): pseudo keys in the normaliser
 def test_extended_attention_golden_two_pseudo(golden):
     g = golden("attention_extended_two_pseudo.txt")
@@ -518,6 +538,15 @@ def test_pseudo_queries_golden_two_heads(golden):
     assert pre[0].ravel().tolist() == g["q_pre_head0"] and pre[1].ravel().tolist() == g["q_pre_head1"]
     q = O.bf16_bits_to_f64(O.pseudo_queries(x, tok, w, 2, positions=[int(v) for v in g["positions"]], theta=10000.0))
     assert q[0].ravel().tolist() == g["q_head0"] and q[1].ravel().tolist() == g["q_head1"]
+
+
+def test_pseudo_queries_golden_rounding_order(golden):
+    g = golden("pseudo_queries_rounding_order.txt")
+    x, w = _bits([g["x0"]]), _bits([g["w0"], g["w1"]])
+    tok = [int(v) for v in g["token_idx"]]
+    assert O.bf16_bits_to_f64(O.pseudo_queries(x, tok, w, 1))[0, 0].tolist() == g["q_pre"]
+    q = O.bf16_bits_to_f64(O.pseudo_queries(x, tok, w, 1, positions=[int(v) for v in g["positions"]]))
+    assert q[0, 0].tolist() == g["q"]
 
 
 def test_pseudo_queries_permutation_weight_is_a_gather():
