@@ -292,6 +292,11 @@ def test_topk_margin_uses_distinct_values():
     v, gap = O.topk_margin(P, 4)
     assert v == 4.0 and abs(gap - 0.25) < 1e-15
     assert O.topk_margin(P, 5)[1] == np.inf
+    # the nearest distinct value on each side counts, not the farthest: 5.001 sits 2e-4 above the boundary 5
+    v, gap = O.topk_margin(np.array([10.0, 5.001, 5.0, 1.0]), 3)
+    assert v == 5.0 and abs(gap - 0.001 / 5.0) < 1e-12
+    v, gap = O.topk_margin(np.array([10.0, 5.0, 4.999, 1.0]), 2)
+    assert v == 5.0 and abs(gap - 0.001 / 5.0) < 1e-12
 
 
 # ------------------------------------------------------------------ gather / whole step
