@@ -37,8 +37,10 @@ MEASURED_TRAFFIC_BYTES = {    # (workload, N, kernel)
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    # the clock governor needs about 50 steps after idle to settle (a boost, a deep throttle, then the sustained
+    # clock): the defaults time the sustained rate
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", default="C2", help="C1..C5 (C2 is the configuration the metric is quoted on)")
     ap.add_argument("--n-pseudo", type=int, default=None, help="override N (the C4 sweep)")
     ap.add_argument("--layers", type=int, default=None, help="override the layer count (fits memory / quick runs)")
