@@ -39,6 +39,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     # the clock governor needs about 50 steps after idle to settle (a boost, a deep throttle, then the sustained
     # clock): the defaults time the sustained rate
+    ap.add_argument("--settle-ms", type=float, default=150.0,
+                    help="untimed steps are run for this long before the warm-up so that the timed steps see the "
+                         "sustained clock whatever --warmup is (reported as settle_steps)")
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", default="C2", help="C1..C5 (C2 is the configuration the metric is quoted on)")
@@ -288,10 +291,18 @@ def main():
     d, Hq, Hkv, N, nl, B = w.head_dim, w.n_q_heads, w.n_kv_heads, w.n_pseudo, w.n_layers, w.batch
     names = Context.names
 
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)] for _ in range(args.steps)]
+    # untimed: let the clock governor settle under this load (after idle it boosts, then throttles deeply, and reaches
+    # the sustained clock after some 60 ms), then the W warm-up steps proper
+    settle_steps = 0
+    t_settle = time.perf_counter()
+    while (time.perf_counter() - t_settle) * 1e3 < args.settle_ms:
+        for _ in range(10):
+            ctx.step()
+        torch.cuda.synchronize()
+        settle_steps += 10
     for _ in range(args.warmup):
         ctx.step()
-    torch.cuda.synchronize()
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):
@@ -347,7 +358,7 @@ def main():
 
     out = {
         "metric": "prompt keys scored+evicted/sec (all layers x KV heads)", "value": value, "unit": "keys/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "settle_steps": settle_steps, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name}: {nl} layers, {Hq} q / {Hkv} kv heads, d {d}, batch {B}, "
                                f"L_p {lens if w.ragged else lens[0]}, N {N}, budget {w.budget}, pool {w.pool_width}, "
