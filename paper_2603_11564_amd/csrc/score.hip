@@ -262,14 +262,12 @@ __device__ __forceinline__ void wait_ring_full() {
 // The instruction order is pinned with empty asm statements that take values as read-write operands:
 // what produces an operand must come before the statement, what uses it after.  One sits right
 // after the MFMA of a slice (it "redefines" the K fragment the MFMA read and the two pending
-// exponents, so the MFMA leads the slice and the vector work follows), one at the end of the slice
-// (it also names the K fragment of the next MFMA, which therefore cannot start early).
+// exponents, so the MFMA leads the slice and the vector work follows), one at the end of the slice.
 // Neither names a transcendental's result or the accumulator in flight: both would cost wait states.
+// (Naming the K fragment of the next MFMA at the slice end as well keeps that MFMA from starting
+// early, but measures 1-2 % slower per pass over a few hundred back-to-back launches.)
 #define DAPQ_WAVE_SLICE_MID(kfrag, x0, x1) asm volatile("" : "+v"(kfrag), "+v"(x0), "+v"(x1))
-#define DAPQ_WAVE_SLICE_END(prev, x0, x1, t0, t1, addr, knext) \
-  asm volatile("" : "+v"(prev), "+v"(x0), "+v"(x1), "+v"(t0), "+v"(t1), "+v"(addr), "+v"(knext))
-// pass 1 keeps its cadence without naming the next K fragment, and measures 2-3% faster that way
-#define DAPQ_WAVE_SLICE_END1(prev, x0, x1, t0, t1, addr) \
+#define DAPQ_WAVE_SLICE_END(prev, x0, x1, t0, t1, addr) \
   asm volatile("" : "+v"(prev), "+v"(x0), "+v"(x1), "+v"(t0), "+v"(t1), "+v"(addr))
 
 // One step of the four-stage vector pipeline over pairs of logits: the exponentials started two
@@ -365,11 +363,11 @@ __device__ __forceinline__ void wave_walk(u32x4* ring, const uint16_t* kbase, in
             }
             sa = sb = 0.0f;
           }
-          DAPQ_WAVE_SLICE_END(prev, x0, x1, sa, sb, fa[(s + 1) & 7], kf[(s + 1) & 7]);
+          DAPQ_WAVE_SLICE_END(prev, x0, x1, sa, sb, fa[(s + 1) & 7]);
         } else {
           if (s < 3) DAPQ_VALU_STEP_K(s, prev[2 * s], prev[2 * s + 1], off1[rb1], off1[rb1], acc[rb2], acc[rb2]);
           else DAPQ_VALU_STEP_K(s, prev[2 * s], prev[2 * s + 1], off1[rb1], off1[rb1], acc[rb1], acc[rb1]);
-          DAPQ_WAVE_SLICE_END1(prev, x0, x1, acc[rb1], acc[rb2], fa[(s + 1) & 7]);
+          DAPQ_WAVE_SLICE_END(prev, x0, x1, acc[rb1], acc[rb2], fa[(s + 1) & 7]);
         }
       }
       prev = cur;
