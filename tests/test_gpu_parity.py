@@ -596,7 +596,7 @@ def test_pseudo_tokens_and_positions(H):
 
 
 # ----------------------------------------------------------------------------------------- random shapes
-@pytest.mark.parametrize("seed", range(40))
+@pytest.mark.parametrize("seed", range(100))
 def test_chain_random_shapes(H, seed):
     """The whole step on seeded random shapes (head counts, pseudo-query counts, ragged or dense lengths
     with chunk-boundary values, both K layouts, window widths, budgets), both ways of selecting (two calls /

@@ -119,7 +119,7 @@ def test_projection_matches_oracle(H, case):
     assert equal > 0.99, equal
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(48))
 def test_projection_random_shapes(H, seed):
     """Seeded random shapes: layers, rows, hidden blocks, head counts and sizes, padded strides, missing sources,
     one x for all layers or one per layer -- every combination of kernel variant, sweep count and hidden split that
