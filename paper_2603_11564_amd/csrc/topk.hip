@@ -266,7 +266,27 @@ __global__ __launch_bounds__(kTopkThreads) void topk_stream_kernel(TopkParams p)
     for (int j = tid; j < L; j += kTopkThreads) keys[j] = order_key(src[j]);
   }
   __syncthreads();
-  auto key_at = [&](int j) -> uint32_t { return staged ? keys[j] : order_key(src[j]); };
+  // a thread takes four consecutive keys per trip (one 16-byte load when the head is 16-byte aligned): a trip is a
+  // tile of 4096 keys, thread t owning keys [4t, 4t + 4) of it.  Keys past the end read as 0 and are never candidates.
+  const bool aligned = (reinterpret_cast<uintptr_t>(src) & 15) == 0;
+  auto keys_at = [&](int j, uint32_t (&k)[4]) {
+    if (staged) {
+      if (j + 3 < L) {
+        const uint4 v = *reinterpret_cast<const uint4*>(keys + j);  // keys is 16-byte aligned, j a multiple of 4
+        k[0] = v.x; k[1] = v.y; k[2] = v.z; k[3] = v.w;
+      } else {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) k[u] = j + u < L ? keys[j + u] : 0u;
+      }
+    } else if (aligned && j + 3 < L) {
+      const float4 v = *reinterpret_cast<const float4*>(src + j);
+      k[0] = order_key(v.x); k[1] = order_key(v.y); k[2] = order_key(v.z); k[3] = order_key(v.w);
+    } else {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) k[u] = j + u < L ? order_key(src[j + u]) : 0u;
+    }
+  };
+  constexpr int kTile = 4 * kTopkThreads;
 
   // ---- radix select: threshold T = the keep-th largest key, need = how many keys == T to take
   uint32_t prefix = 0, mask = 0;
@@ -274,17 +294,21 @@ __global__ __launch_bounds__(kTopkThreads) void topk_stream_kernel(TopkParams p)
   for (int shift = 24; shift >= 0; shift -= 8) {
     if (tid < 256) hist[tid] = 0;
     __syncthreads();
-    for (int jb = 0; jb < L; jb += kTopkThreads) {  // the trip count is the same for every thread
-      const int j = jb + tid;
-      const uint32_t k = j < L ? key_at(j) : 0u;
-      const bool cand = j < L && (k & mask) == prefix;
-      const uint32_t d = (k >> shift) & 255u;
-      const uint64_t have = __ballot(cand);
-      if (have != 0) {
-        const uint32_t d0 = (uint32_t)__shfl((int)d, __ffsll((long long)have) - 1, 64);
-        const uint64_t same = __ballot(cand && d == d0);
-        if (cand && d != d0) atomicAdd(&hist[d], 1u);
-        if (lane == 0) atomicAdd(&hist[d0], (uint32_t)__popcll(same));
+    for (int jb = 0; jb < L; jb += kTile) {  // the trip count is the same for every thread
+      const int j = jb + 4 * tid;
+      uint32_t k[4];
+      keys_at(j, k);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const bool cand = j + u < L && (k[u] & mask) == prefix;
+        const uint32_t d = (k[u] >> shift) & 255u;
+        const uint64_t have = __ballot(cand);
+        if (have != 0) {
+          const uint32_t d0 = (uint32_t)__shfl((int)d, __ffsll((long long)have) - 1, 64);
+          const uint64_t same = __ballot(cand && d == d0);
+          if (cand && d != d0) atomicAdd(&hist[d], 1u);
+          if (lane == 0) atomicAdd(&hist[d0], (uint32_t)__popcll(same));
+        }
       }
     }
     __syncthreads();
@@ -297,32 +321,51 @@ __global__ __launch_bounds__(kTopkThreads) void topk_stream_kernel(TopkParams p)
   }
   const uint32_t T = prefix;
 
-  // ---- ordered compaction, one block of 1024 keys at a time
-  uint32_t base_gt = 0, base_eq = 0;  // keys > T / == T before the current block (same in all threads)
-  for (int j0 = 0; j0 < L; j0 += kTopkThreads) {
-    const int j = j0 + tid;
-    const uint32_t k = j < L ? key_at(j) : 0u;
-    const bool gt = j < L && k > T;
-    const bool eq = j < L && k == T;
-    const uint64_t m_gt = __ballot(gt), m_eq = __ballot(eq);
-    const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-    const uint32_t w_gt = __popcll(m_gt), w_eq = __popcll(m_eq);
-    if (lane == 0) wave_tot[wave] = (w_gt << 16) | w_eq;
+  // ---- ordered compaction, one tile of 4096 keys at a time: per-thread counts of (greater, equal), an inclusive
+  // scan inside the wave, wave totals through LDS, then every thread writes its survivors in key order
+  uint32_t base_gt = 0, base_eq = 0;  // keys > T / == T before the current tile (same in all threads)
+  const uint32_t un = (uint32_t)need;
+  for (int jb = 0; jb < L; jb += kTile) {
+    const int j = jb + 4 * tid;
+    uint32_t k[4];
+    keys_at(j, k);
+    uint32_t my = 0;  // (greater << 16) | equal over this thread's four keys
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (j + u < L) my += (k[u] > T ? 0x10000u : 0u) + (k[u] == T ? 1u : 0u);
+    }
+    uint32_t inc = my;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const uint32_t o = __shfl_up(inc, d, 64);
+      if (lane >= d) inc += o;
+    }
+    if (lane == 63) wave_tot[wave] = inc;
     __syncthreads();
-    uint32_t pre_gt = base_gt, pre_eq = base_eq, blk_gt = 0, blk_eq = 0;
+    uint32_t pre = inc - my, blk = 0;  // packed counts before this thread inside the tile / of the whole tile
 #pragma unroll
     for (int w = 0; w < kTopkWaves; ++w) {
       const uint32_t t = wave_tot[w];
-      if (w < wave) { pre_gt += t >> 16; pre_eq += t & 0xFFFFu; }
-      blk_gt += t >> 16;
-      blk_eq += t & 0xFFFFu;
+      if (w < wave) pre += t;
+      blk += t;
     }
-    pre_gt += __popcll(m_gt & below);
-    pre_eq += __popcll(m_eq & below);
-    const uint32_t un = (uint32_t)need;
-    if (gt || (eq && pre_eq < un)) out[pre_gt + (pre_eq < un ? pre_eq : un)] = j;
-    base_gt += blk_gt;
-    base_eq += blk_eq;
+    uint32_t pre_gt = base_gt + (pre >> 16), pre_eq = base_eq + (pre & 0xFFFFu);
+    if (my != 0) {
+      uint32_t pos = pre_gt + (pre_eq < un ? pre_eq : un);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (j + u < L) {
+          if (k[u] > T) {
+            out[pos++] = j + u;
+          } else if (k[u] == T) {
+            if (pre_eq < un) out[pos++] = j + u;
+            ++pre_eq;
+          }
+        }
+      }
+    }
+    base_gt += blk >> 16;
+    base_eq += blk & 0xFFFFu;
     __syncthreads();
   }
 }
