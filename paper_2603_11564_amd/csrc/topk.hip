@@ -444,12 +444,16 @@ extern "C" DAPQ_API int dapq_topk(const dapq_shape* shape, const float* pooled, 
   const int64_t reg_max = variant.max_len();
   p.min_len = 0;
   p.max_len = (int32_t)reg_max;
-  launch_reg<0>(variant, grid, st, p);
-  DAPQ_HIP_LAUNCH_CHECK("topk_reg_kernel");
+  if (shape->cu_seqlens != nullptr || mean <= reg_max) {  // (a dense batch of longer heads has nothing for it)
+    launch_reg<0>(variant, grid, st, p);
+    DAPQ_HIP_LAUNCH_CHECK("topk_reg_kernel");
+  }
   if (longest > reg_max) {
     p.min_len = (int32_t)reg_max + 1;
     p.max_len = INT32_MAX;
-    const int lds_bytes = (320 + kTopkLdsKeys) * (int)sizeof(uint32_t);
+    // heads of up to kTopkLdsKeys keys are staged in LDS; if none of this launch can be that short the staging
+    // area is left out
+    const int lds_bytes = (320 + (p.min_len <= kTopkLdsKeys ? kTopkLdsKeys : 0)) * (int)sizeof(uint32_t);
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(topk_stream_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return fail(DAPQ_ERR_HIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
