@@ -16,6 +16,8 @@
  *   - Arguments are validated on the host before anything is enqueued; a failing call enqueues
  *     nothing.  Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default
  *     stream) and the call returns without synchronising.
+ *   - Calls may be in flight on several streams at once as long as they share no output buffer and no
+ *     workspace: a workspace belongs to one call until the work of that call has finished on its stream.
  *   - Results are deterministic: the same inputs give the same bits on every run.
  *   - bf16 tensors are passed as void* (16-bit patterns).  head_dim must be 128.
  *

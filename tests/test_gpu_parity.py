@@ -696,3 +696,27 @@ def test_step_replays_from_a_hip_graph(H):
             assert torch.equal(out[name].view(torch.int16) if out[name].dtype == torch.bfloat16 else out[name],
                                want[name].view(torch.int16) if want[name].dtype == torch.bfloat16 else want[name]), \
                 (name, replay)
+
+
+def test_calls_on_two_streams_do_not_disturb_each_other(H):
+    """Two problems scored at the same time on two streams, each with its own workspace and outputs, give the
+    bits they give when run one after the other (the library keeps no state between or across calls)."""
+    announce("two streams at once")
+    D = H.D
+    probs = []
+    for seed, lens in ((201, [3000, 700]), (202, [2500, 2500])):
+        q, k, v, cu = random_problem(seed, 2, lens, 8, 2, 32)
+        probs.append(H.Problem(q, k, v, 2, cu, "thd"))
+    alone = [p.score().clone() for p in probs]
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = [torch.zeros_like(a) for a in alone]
+    for rep in range(3):
+        for p, s, o in zip(probs, streams, outs):
+            o.zero_()
+            s.wait_stream(torch.cuda.current_stream())
+        for p, s, o in zip(probs, streams, outs):
+            D.dapq_score(p.shape, p.q, p.k, o, p.ws, s)
+        torch.cuda.synchronize()
+        for a, o in zip(alone, outs):
+            assert torch.equal(a, o), rep
