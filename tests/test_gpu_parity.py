@@ -720,3 +720,32 @@ def test_calls_on_two_streams_do_not_disturb_each_other(H):
         torch.cuda.synchronize()
         for a, o in zip(alone, outs):
             assert torch.equal(a, o), rep
+
+
+@pytest.mark.parametrize("ragged", [False, True])
+def test_batch_of_empty_prompts(H, ragged):
+    """total_tokens = 0: every entry point accepts the shape, writes count = 0 and lse2 = 0, and touches nothing else
+    (the buffers that would hold keys are one dummy row, never read)."""
+    announce(f"all prompts empty, ragged={ragged}")
+    D = H.D
+    layers, B, Hq, Hkv, N, d, budget = 2, 2, 4, 2, 8, 128, 5
+    cu = torch.zeros(B + 1, dtype=torch.int32, device="cuda") if ragged else None
+    shape = D.make_shape(n_layers=layers, batch=B, n_q_heads=Hq, n_kv_heads=Hkv, n_pseudo=N, total_tokens=0, cu_seqlens=cu,
+                         k_strides=(0, 0, d, Hkv * d), v_strides=(0, 0, d, Hkv * d),
+                         q_strides=(B * Hq * N * d, Hq * N * d, N * d, d))
+    q = torch.randn((layers, B, Hq, N, d), device="cuda").to(torch.bfloat16)
+    k = torch.full((1, Hkv, d), float("nan"), device="cuda").to(torch.bfloat16)
+    ws = torch.empty(max(D.workspace_bytes(shape), 256), dtype=torch.uint8, device="cuda")
+    S = torch.full((layers, Hkv, 1), 7.0, dtype=torch.float32, device="cuda")
+    lse = torch.full((layers, B, Hq, N), 7.0, dtype=torch.float32, device="cuda")
+    D.dapq_score_stats(shape, q, k, lse, ws)
+    D.dapq_score(shape, q, k, S, ws)
+    idx = torch.full((layers, B, Hkv, budget), -7, dtype=torch.int32, device="cuda")
+    count = torch.full((layers, B, Hkv), -7, dtype=torch.int32, device="cuda")
+    D.dapq_pool_topk(shape, S, 7, budget, None, idx, count, None)
+    ko = torch.full((layers, B, Hkv, budget, d), 3.0, device="cuda").to(torch.bfloat16)
+    vo = ko.clone()
+    D.dapq_gather(shape, k, k, idx, count, budget, ko, vo)
+    torch.cuda.synchronize()
+    assert (lse == 0).all() and (count == 0).all()
+    assert (S == 7.0).all() and (idx == -7).all() and (ko == 3.0).all() and (vo == 3.0).all()
