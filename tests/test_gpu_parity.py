@@ -749,3 +749,33 @@ def test_batch_of_empty_prompts(H, ragged):
     torch.cuda.synchronize()
     assert (lse == 0).all() and (count == 0).all()
     assert (S == 7.0).all() and (idx == -7).all() and (ko == 3.0).all() and (vo == 3.0).all()
+
+
+def test_chain_many_short_sequences(H):
+    """A ragged batch of 300 short prompts (0 to 200 keys): per-sequence chunking, pooling that never crosses a
+    sequence boundary, budgets clipped to the prompt lengths."""
+    announce("300 short sequences")
+    r = np.random.default_rng(77)
+    lens = [int(v) for v in r.integers(0, 200, 300)]
+    lens[5], lens[17] = 0, 1
+    q, k, v, cu = random_problem(78, 1, lens, 4, 2, 8)
+    prob = H.Problem(q, k, v, 2, cu, "thd")
+    budget = 24
+    S = prob.score()
+    idx, count, _ = prob.pool_topk(S, 7, budget, None, False)
+    ko, vo = prob.gather(idx, count, budget)
+    want = O.compress(q, k, v, 2, budget, cu, 7)
+    H.assert_scores_close(S.cpu().numpy(), want["S"], "many sequences")
+    idx, count = idx.cpu().numpy(), count.cpu().numpy()
+    assert np.array_equal(count, want["count"])
+    kob, vob = H.host_bits(ko), H.host_bits(vo)
+    exact = 0
+    for b, L in enumerate(lens):
+        for kv in range(2):
+            n = count[0, b, kv]
+            res = H.check_retained(want["P"][0, kv, cu[b]:cu[b + 1]], idx[0, b, kv], budget) if L > 0 else "exact"
+            exact += res == "exact"
+            keep = idx[0, b, kv, :n]
+            assert np.array_equal(kob[0, b, kv, :n], k[0, cu[b]:cu[b + 1], kv][keep])
+            assert np.array_equal(vob[0, b, kv, :n], v[0, cu[b]:cu[b + 1], kv][keep])
+    assert exact > 500
