@@ -152,16 +152,27 @@ __device__ __forceinline__ bf16x8 lds_read16(unsigned lane_addr, int const_off) 
   return __builtin_bit_cast(bf16x8, *(lds_vec_ptr)(uintptr_t)(lane_addr + const_off));
 }
 
-// Per-sequence prefix of chunk counts for ragged batches (tiny, one block).
+// Per-sequence prefix of chunk counts for ragged batches: one wave, 64 sequences per trip (a scan by shuffles
+// inside the wave, the running total carried from trip to trip).
 __global__ void score_chunk_prefix_kernel(const int32_t* cu_seqlens, int32_t* cu_chunks, int batch, int chunk_keys) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) {
-    int acc = 0;
-    cu_chunks[0] = 0;
-    for (int b = 0; b < batch; ++b) {
+  const int lane = threadIdx.x;  // launched with exactly 64 threads
+  if (lane == 0) cu_chunks[0] = 0;
+  int carry = 0;
+  for (int b0 = 0; b0 < batch; b0 += 64) {
+    const int b = b0 + lane;
+    int mine = 0;
+    if (b < batch) {
       const int L = cu_seqlens[b + 1] - cu_seqlens[b];
-      acc += L > 0 ? (L + chunk_keys - 1) / chunk_keys : 0;
-      cu_chunks[b + 1] = acc;
+      mine = L > 0 ? (L + chunk_keys - 1) / chunk_keys : 0;
     }
+    int inc = mine;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int o = __shfl_up(inc, d, 64);
+      if (lane >= d) inc += o;
+    }
+    if (b < batch) cu_chunks[b + 1] = carry + inc;
+    carry += __shfl(inc, 63, 64);
   }
 }
 
