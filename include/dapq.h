@@ -149,6 +149,21 @@ size_t dapq_pseudo_queries_workspace_bytes(const dapq_qproj* desc);
 int dapq_score(const dapq_shape* shape, const void* q, const void* k, float* scores, void* workspace,
                size_t workspace_bytes, void* stream);
 
+/* dapq_score for callers that cannot allocate device memory or hand over a workspace: code recorded into a HIP
+ * graph, tight serving loops, harnesses that forbid hipMalloc.  Same inputs, same kernels and bit-identical
+ * scores; the workspace of the two passes is an array of DAPQ_STATIC_SCRATCH_BYTES that the library holds in
+ * device memory (one copy on every GPU it runs on, until the process ends).  The call allocates and frees
+ * nothing and calls no allocating routine; its first call on a device looks up that device's copy of the array.
+ *   DAPQ_ERR_WORKSPACE   dapq_workspace_bytes(shape) exceeds DAPQ_STATIC_SCRATCH_BYTES (the limit covers the
+ *                        Llama-3-8B shape at L_p = 32768, N = 64, all 32 layers: 2.4 MB)
+ * Every call on a GPU uses that GPU's one array, which keeps the contents of the previous call (nothing in it has
+ * to be cleared: the first pass writes everything the second reads).  Two calls in flight on the same GPU at the
+ * same time -- different streams, or host threads -- race on it: serialise them, or use dapq_score with
+ * separate workspaces.  dapq_score_static_capacity() returns DAPQ_STATIC_SCRATCH_BYTES as built. */
+#define DAPQ_STATIC_SCRATCH_BYTES ((size_t)4 << 20)
+int dapq_score_static(const dapq_shape* shape, const void* q, const void* k, float* scores, void* stream);
+size_t dapq_score_static_capacity(void);
+
 /* First pass of dapq_score: for every pseudo query row, lse2 = log2 sum_j 2^(c*l_j) with
  * l_j = q.k_j and c = scale*log2(e), i.e. the softmax normaliser of App. C.1 Step 1 in log2 form.
  *   lse2   out, fp32 [n_layers][batch][n_q_heads][n_pseudo] */

@@ -16,6 +16,7 @@ _lib = None
 EXPORTS = (
     "dapq_workspace_bytes", "dapq_last_error", "dapq_rope_apply", "dapq_pseudo_tokens", "dapq_pseudo_queries", "dapq_pseudo_queries_workspace_bytes", "dapq_score", "dapq_score_stats",
     "dapq_score_accumulate", "dapq_score_stats_extend", "dapq_pool", "dapq_topk", "dapq_pool_topk", "dapq_gather", "dapq_recall", "dapq_decode_attention",
+    "dapq_score_static", "dapq_score_static_capacity",
 )
 
 
@@ -85,9 +86,12 @@ def load_library():
     lib.dapq_gather.argtypes = [sp, vp, vp, vp, vp, i32, vp, vp, vp]
     lib.dapq_recall.argtypes = [sp, vp, vp, i32, vp, vp, i32, vp, vp, vp]
     lib.dapq_decode_attention.argtypes = [sp, vp, vp, vp, vp, i32, vp, vp]
+    lib.dapq_score_static.argtypes = [sp, vp, vp, vp, vp]
+    lib.dapq_score_static_capacity.argtypes = []
     for name in EXPORTS[2:]:
         getattr(lib, name).restype = C.c_int
     lib.dapq_pseudo_queries_workspace_bytes.restype = sz
+    lib.dapq_score_static_capacity.restype = sz
     _lib = lib
     return lib
 
@@ -137,6 +141,14 @@ def dapq_score(shape, q, k, scores, workspace, stream=None):
     _check(load_library().dapq_score(C.byref(shape), _ptr(q), _ptr(k), _ptr(scores), _ptr(workspace),
                                      0 if workspace is None else workspace.numel() * workspace.element_size(),
                                      _stream(stream)))
+
+
+def dapq_score_static(shape, q, k, scores, stream=None):
+    _check(load_library().dapq_score_static(C.byref(shape), _ptr(q), _ptr(k), _ptr(scores), _stream(stream)))
+
+
+def score_static_capacity() -> int:
+    return int(load_library().dapq_score_static_capacity())
 
 
 def dapq_score_stats(shape, q, k, lse2, workspace, stream=None):

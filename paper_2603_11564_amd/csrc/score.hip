@@ -34,6 +34,8 @@
 
 #include <math.h>
 
+#include <mutex>
+
 #include "dapq_internal.h"
 
 namespace dapq {
@@ -879,4 +881,57 @@ extern "C" DAPQ_API int dapq_score_stats_extend(const dapq_shape* shape, const v
   else hipLaunchKernelGGL(score_wave_pseudo_kernel<8>, grid, dim3(64), kSubBytes, st, p, pp);
   DAPQ_HIP_LAUNCH_CHECK("score_wave_pseudo_kernel");
   return DAPQ_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// dapq_score for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops):
+// the workspace of the two passes lives in a file-scope device array instead of a caller buffer.
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+constexpr size_t kStaticScratchBytes = DAPQ_STATIC_SCRATCH_BYTES;
+// One copy per GPU the library runs on, held until the process ends.  In host code this name is only a handle
+// for hipGetSymbolAddress: the device address it stands for is looked up once per device and kept below.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int scratch_of_current_device(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(DAPQ_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+  DAPQ_REQUIRE(dev >= 0 && dev < kMaxDevices, DAPQ_ERR_UNSUPPORTED, "device index %d is beyond the %d this library tracks",
+               dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || ptr == nullptr)
+      return fail(DAPQ_ERR_HIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return DAPQ_OK;
+}
+
+}  // namespace
+
+extern "C" DAPQ_API size_t dapq_score_static_capacity(void) { return kStaticScratchBytes; }
+
+extern "C" DAPQ_API int dapq_score_static(const dapq_shape* shape, const void* q, const void* k, float* scores,
+                                          void* stream) {
+  int rc = check_shape(shape, true, true, false);
+  if (rc != DAPQ_OK) return rc;
+  ScorePlan plan;
+  if ((rc = make_score_plan(shape, &plan)) != DAPQ_OK) return rc;
+  DAPQ_REQUIRE(plan.total_bytes <= kStaticScratchBytes, DAPQ_ERR_WORKSPACE,
+               "this shape needs %zu bytes of workspace, the built-in scratch array holds %zu: use dapq_score with a "
+               "caller workspace", plan.total_bytes, kStaticScratchBytes);
+  void* ptr = nullptr;
+  if ((rc = scratch_of_current_device(&ptr)) != DAPQ_OK) return rc;
+  // nothing in the workspace has to start at zero: pass 1 writes every partial that the combine step reads, and
+  // the combine step writes every lse2 that pass 2 reads
+  return dapq_score(shape, q, k, scores, ptr, kStaticScratchBytes, stream);
 }
