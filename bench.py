@@ -9,7 +9,12 @@ Inputs are resident in HBM before the timed region.  Prints one JSON line:
   roofline  the dominant kernel against the nearer roof (HBM for up to ~310 query rows per KV head,
             dense bf16 MFMA beyond): algorithmic bytes (flops) of one launch / its average duration,
             timed with events on the launch stream inside the timed region
-  cpu_baseline  the float64 oracle on the host cores, on a bounded sample of the same workload
+  cpu_baseline  the float64 oracle on the host cores (one worker process per core, one layer per task), on a
+            bounded sample of the same workload, run before the GPU is touched
+
+`--ceilings` measures, instead of the step, what this chip can do for the instruction mix of the score passes:
+read-only streams, the passes' slice (one MFMA + the vector work on two logits) with no memory traffic, and the
+passes themselves with the keys in HBM, in the memory-side cache and in L2 (profiles/score_c2_ceiling.md).
 """
 from __future__ import annotations
 
@@ -32,6 +37,9 @@ MEASURED_TRAFFIC_BYTES = {    # (workload, N, kernel)
     ("C2", 64, "score_pass2"): 2.250e9,   # 2.217 GB fetched (1.032 x the key bytes: Q is re-read per chunk) + 32 MiB written
     ("C2", 64, "score_pass1"): 2.217e9,   # 2.214 GB fetched + 2 MiB of partial row statistics written
 }
+# Where those figures come from: the profile file and the commit whose score kernels were profiled.  A CPU test
+# (tests/test_bench_host.py) fails when csrc/score.hip has changed since that commit, i.e. when they are stale.
+TRAFFIC_SOURCE = {"file": "profiles/score_c2_hbm_traffic.md", "commit": "b1bbe04"}
 
 
 def parse():
@@ -49,47 +57,77 @@ def parse():
     ap.add_argument("--layers", type=int, default=None, help="override the layer count (fits memory / quick runs)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--cpu-layers", type=int, default=None, help="layers the CPU oracle baseline runs (0 = skip)")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="measure the chip's ceilings for the score passes instead of the step (see the module text)")
+    ap.add_argument("--post-idle-steps", type=int, default=20,
+                    help="steps timed right after set-up and a pause, before the clock governor has settled "
+                         "(reported as ms_per_step_post_idle; 0 = skip)")
     ap.add_argument("--extras", action="store_true",
                     help="also time the entry points around the step (extended normaliser, decode over the compact "
                          "cache, recall); reported under extras_ms, not part of value")
     return ap.parse_args()
 
 
-def cpu_baseline(w, seed, n_layers):
-    """Times the oracle (rope of the pseudo queries + the eviction step) on n_layers layers of the
-    workload, sequence 0 only for ragged batches.  Input generation and the rotation of K are
-    preparation and are not timed, as on the GPU side."""
+def _cpu_worker(w, seed, L, layers, ready, done):
+    """One worker process of the oracle leg: prepares the inputs of its layers (not timed), waits for the start
+    signal, then runs the rotation of the pseudo queries and the eviction step on each of them."""
     import numpy as np
     import threadpoolctl
     import workloads as W
     from oracle import dapq_oracle as O
+    with threadpoolctl.threadpool_limits(1):     # one core per worker process
+        inputs = []
+        for layer in layers:
+            qp = W.q_pre(w, seed, layer, 0)
+            k = np.empty((L, w.n_kv_heads, w.head_dim), dtype=np.uint16)
+            v = np.empty_like(k)
+            for kv in range(w.n_kv_heads):
+                k[:, kv] = W.k_pre(w, seed, layer, 0, kv, L, qp)
+                v[:, kv] = W.v_rows(w, seed, layer, 0, kv, L)
+            inputs.append((qp, O.rope_apply(k, W.k_positions(L), w.theta)[None], v[None]))
+        ready.wait()
+        for qp, k, v in inputs:
+            q = O.rope_apply(qp.transpose(1, 0, 2), W.q_positions(L, w.n_pseudo), w.theta).transpose(1, 0, 2)
+            O.compress(q[None, None], k, v, w.n_kv_heads, w.budget, None, w.pool_width, w.scale)
+        done.wait()
 
-    lens = W.seq_lens(w, seed)
-    L = lens[0]
-    qs, ks, vs = [], [], []
-    for layer in range(n_layers):
-        qp = W.q_pre(w, seed, layer, 0)
-        k = np.empty((L, w.n_kv_heads, w.head_dim), dtype=np.uint16)
-        v = np.empty_like(k)
-        for kv in range(w.n_kv_heads):
-            k[:, kv] = W.k_pre(w, seed, layer, 0, kv, L, qp)
-            v[:, kv] = W.v_rows(w, seed, layer, 0, kv, L)
-        qs.append(qp)
-        ks.append(O.rope_apply(k, W.k_positions(L), w.theta))
-        vs.append(v)
-    k = np.stack(ks)
-    v = np.stack(vs)
-    t0 = time.perf_counter()
-    q = np.stack([O.rope_apply(qp.transpose(1, 0, 2), W.q_positions(L, w.n_pseudo), w.theta).transpose(1, 0, 2)
-                  for qp in qs])[:, None]
-    O.compress(q, k, v, w.n_kv_heads, w.budget, None, w.pool_width, w.scale)
-    dt = time.perf_counter() - t0
+
+def cpu_baseline(w, seed, n_layers):
+    """Times the oracle (rope of the pseudo queries + the eviction step) on n_layers layers of the workload
+    (sequence 0 only for ragged batches) on the host cores: one single-threaded worker process per core, each with
+    its share of the layers.  Must run before anything touches the GPU (the workers are forked).  Input generation
+    and the rotation of K are preparation and are not timed, as on the GPU side: the clock runs from the moment
+    every worker has its inputs to the moment the last one is finished."""
+    import multiprocessing as mp
+    import workloads as W
+
+    L = W.seq_lens(w, seed)[0]
+    cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    workers = max(1, min(cores, 16, n_layers))    # a one-GPU box has a share of 16 cores
+    ctx = mp.get_context("fork")
+    ready, done = ctx.Barrier(workers + 1), ctx.Barrier(workers + 1)
+    procs = [ctx.Process(target=_cpu_worker, args=(w, seed, L, list(range(i, n_layers, workers)), ready, done))
+             for i in range(workers)]
+    for p in procs:
+        p.start()
+    try:
+        ready.wait(timeout=600)
+        t0 = time.perf_counter()
+        done.wait(timeout=600)
+        dt = time.perf_counter() - t0
+    finally:
+        for p in procs:
+            p.join(timeout=30)
+            if p.is_alive():
+                p.terminate()
+    if any(p.exitcode != 0 for p in procs):
+        raise RuntimeError("a worker of the oracle leg failed")
     keys = n_layers * w.n_kv_heads * L
-    blas = [p["num_threads"] for p in threadpoolctl.threadpool_info() if p.get("user_api") == "blas"]
     return {
-        "value": keys / dt, "unit": "keys/s", "cores": max(blas) if blas else 1, "kind": "oracle",
+        "value": keys / dt, "unit": "keys/s", "cores": workers, "kind": "oracle",
         "sample": f"{n_layers} of {w.n_layers} layers x {w.n_kv_heads} KV heads x {L} keys of {w.name} "
-                  f"(sequence 0), {dt:.1f} s; matmul on the BLAS threads, the rest single-threaded",
+                  f"(sequence 0), {dt:.1f} s wall clock; {workers} single-threaded worker processes, "
+                  f"{(n_layers + workers - 1) // workers} layer(s) each",
     }
 
 
@@ -180,22 +218,80 @@ class Context:
         mark(5)
 
 
-def stream_copy_gbs(dev, n_bytes=1 << 30, reps=10):
-    """Bytes per second (read + write) of torch's device-to-device copy of a 1 GiB tensor: the practical ceiling of a
-    pure stream on this machine, reported beside the 8 TB/s data-sheet peak."""
+def read_stream_gbs(dev, n_bytes=2 << 30):
+    """What a read-only stream of 2 GiB (the key bytes of C2) reaches on this machine, outside the timed region: with plain
+    16-byte loads from many waves, and through the score kernels' own path (one wave per SIMD, LDS-direct loads into a
+    ring of 32-key sub-blocks).  The practical ceilings of a pass that only moved the keys, for scale beside the 8 TB/s
+    data-sheet peak."""
     import torch
+    from paper_2603_11564_amd import ceiling
     a = torch.empty(n_bytes, dtype=torch.uint8, device=dev)
-    b = torch.empty_like(a)
-    a.zero_()
-    b.copy_(a)
+    a.fill_(1)
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(reps):
-        b.copy_(a)
-    e1.record()
+    res = {"plain_loads": ceiling.stream(a, 0, 8192)["gbs"], "lds_ring": ceiling.stream(a, 1, 5, 1)["gbs"]}
+    del a
+    return res
+
+
+def time_passes(ctx, shape, warm, reps):
+    """Average duration (ms) of the two score passes for `shape`, each launched back to back on its own."""
+    import torch
+    D, stream = ctx.D, ctx.stream
+    res = {}
+    calls = {
+        "score_pass1": lambda: D.dapq_score_stats(shape, ctx.q, ctx.k, ctx.lse2, ctx.ws, stream),
+        "score_pass2": lambda: D.dapq_score_accumulate(shape, ctx.q, ctx.k, ctx.lse2, ctx.S, ctx.ws, stream),
+    }
+    for name, fn in calls.items():
+        for _ in range(warm):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        res[name] = e0.elapsed_time(e1) / reps
+    return res
+
+
+def ceilings(ctx, args):
+    """The measurements behind profiles/score_c2_ceiling.md, in one run on one box."""
+    import torch
+    from paper_2603_11564_amd import ceiling
+    w, dev = ctx.w, ctx.dev
+    g, N, d = w.n_q_heads // w.n_kv_heads, w.n_pseudo, w.head_dim
+    ctx.step()                      # rotated pseudo queries, a valid lse2
     torch.cuda.synchronize()
-    return 2.0 * n_bytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    out = {"workload": f"{w.name}: {w.n_layers} layers, N {N}, L_p {ctx.lens[0]}", "reps": args.steps}
+    # slices one SIMD runs per pass: (rows / 32) x (keys / 32) x (d / 16) MFMAs over all heads, on 1024 SIMDs
+    slices = ctx.key_units * g * N * d / (32 * 32 * 16) / 1024
+    out["slices_per_simd_per_pass"] = slices
+    out["streams"] = {
+        "plain_loads_8192_workgroups": ceiling.stream(ctx.k, 0, 8192, 0, 3, 50),
+        "lds_ring_5_slots_1_wave_per_simd": ceiling.stream(ctx.k, 1, 5, 1, 3, 50),
+        "lds_ring_2_slots_2_waves_per_simd": ceiling.stream(ctx.k, 1, 2, 2, 3, 50),
+    }
+    probes = []
+    for mix in ceiling.slice_mixes():
+        for wps in (1, 2):
+            r = ceiling.slice_probe(mix["index"], wps, 400, 3, args.steps)
+            r.update({"mix": mix["name"], "waves_per_simd": wps, "ms_per_pass_equivalent": r["ns_per_slice"] * slices * 1e-6})
+            probes.append(r)
+    out["slice_probes"] = probes
+    # the passes themselves, the keys in HBM / in the memory-side cache (every layer reads layer 0's keys: 1/n_layers
+    # of the bytes) / in L2 and the memory-side cache (every head reads head 0 of layer 0)
+    placements = {"hbm": ctx.shape}
+    if w.layout == "hnd":
+        one_layer, one_head = type(ctx.shape).from_buffer_copy(ctx.shape), type(ctx.shape).from_buffer_copy(ctx.shape)
+        one_layer.k_stride_layer = 0
+        one_head.k_stride_layer = 0
+        one_head.k_stride_head = 0
+        placements["one_layer_of_keys_for_all"] = one_layer
+        placements["one_head_of_keys_for_all"] = one_head
+    out["passes_ms"] = {name: time_passes(ctx, shape, args.warmup, args.steps) for name, shape in placements.items()}
+    out["passes_ns_per_slice"] = {name: {k: v * 1e6 / slices for k, v in r.items()} for name, r in out["passes_ms"].items()}
+    return out
 
 
 class pseudo_query_problem:
@@ -274,22 +370,46 @@ def main():
               file=sys.stderr)
         sys.exit(2)
     import numpy as np
-    import torch
-    import paper_2603_11564_amd as D
     import workloads as W
     from dataclasses import replace
 
+    w = W.workload(args.workload, args.n_pseudo)
+    if args.layers is not None:
+        w = replace(w, n_layers=args.layers)
+    lens0 = W.seq_lens(w, args.seed)
+    # the oracle leg comes first: its worker processes are forked, which has to happen before the GPU is touched
+    ncpu = args.cpu_layers
+    if ncpu is None:
+        ncpu = max(1, min(w.n_layers, int(round(32 * (32768 * 8 * 256) /
+                                                 (lens0[0] * w.n_kv_heads * (w.n_q_heads // w.n_kv_heads) * w.n_pseudo)))))
+    cpu = cpu_baseline(w, args.seed, min(ncpu, w.n_layers)) if (ncpu > 0 and not args.ceilings) else None
+
+    import torch
+    import paper_2603_11564_amd as D
     D.load_library()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    w = W.workload(args.workload, args.n_pseudo)
-    if args.layers is not None:
-        w = replace(w, n_layers=args.layers)
     ctx = Context(w, args.seed, dev)
     lens, tokens = ctx.lens, ctx.tokens
     d, Hq, Hkv, N, nl, B = w.head_dim, w.n_q_heads, w.n_kv_heads, w.n_pseudo, w.n_layers, w.batch
     names = Context.names
+    if args.ceilings:
+        print(json.dumps({"ceilings": ceilings(ctx, args)}), flush=True)
+        return
+
+    # the first steps after idle, before the clock governor has settled: reported beside the sustained figure
+    ms_post_idle = None
+    if args.post_idle_steps > 0:
+        for _ in range(3):
+            ctx.step()
+        torch.cuda.synchronize()
+        time.sleep(1.0)
+        t_idle = time.perf_counter()
+        for _ in range(args.post_idle_steps):
+            ctx.step()
+        torch.cuda.synchronize()
+        ms_post_idle = (time.perf_counter() - t_idle) * 1e3 / args.post_idle_steps
 
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)] for _ in range(args.steps)]
     # untimed: let the clock governor settle under this load (after idle it boosts, then throttles deeply, and reaches
@@ -334,6 +454,9 @@ def main():
                     "frac": hbm_gbs / HBM_PEAK_GBS}
     roofline.update({
         "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, N, dom)),
+        "traffic_source": (f"{TRAFFIC_SOURCE['file']}, rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of the kernels at commit "
+                           f"{TRAFFIC_SOURCE['commit']} (not measured in this run)"
+                           if (w.name, N, dom) in MEASURED_TRAFFIC_BYTES else None),
         "algorithmic_bytes_per_launch": bytes_pass[dom], "algorithmic_flops_per_launch": flops_pass,
         "avg_launch_ms": per[dom], "hbm_gbs": hbm_gbs, "mfma_tflops": mfma_tflops,
     })
@@ -350,15 +473,16 @@ def main():
         "mfma_frac_of_peak": {n: flops_pass / (per[n] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS for n in bytes_pass},
     }
 
-    # what a plain device copy moves on this machine, for scale next to the data-sheet peak (outside the timed region)
-    copy_gbs = stream_copy_gbs(dev)
-    step_hbm["stream_copy_gbs"] = copy_gbs
-    step_hbm["design_frac_of_stream_copy"] = step_hbm["design_gbs"] / copy_gbs
-    roofline["hbm_frac_of_stream_copy"] = hbm_gbs / copy_gbs
+    # what a read-only stream reaches on this machine, for scale next to the data-sheet peak (outside the timed region)
+    streams = read_stream_gbs(dev)
+    step_hbm["read_stream_gbs"] = streams
+    step_hbm["design_frac_of_read_stream"] = step_hbm["design_gbs"] / streams["lds_ring"]
+    roofline["hbm_frac_of_read_stream"] = hbm_gbs / streams["lds_ring"]
 
     out = {
         "metric": "prompt keys scored+evicted/sec (all layers x KV heads)", "value": value, "unit": "keys/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "settle_steps": settle_steps, "ms_per_step": ms_per_step,
+        "ms_per_step_post_idle": ms_post_idle,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name}: {nl} layers, {Hq} q / {Hkv} kv heads, d {d}, batch {B}, "
                                f"L_p {lens if w.ragged else lens[0]}, N {N}, budget {w.budget}, pool {w.pool_width}, "
@@ -369,11 +493,8 @@ def main():
     }
     if args.extras:
         out["extras_ms"] = time_extras(ctx, args.steps)
-    ncpu = args.cpu_layers
-    if ncpu is None:
-        ncpu = max(1, min(nl, int(round(24 * (32768 * 8 * 256) / (lens[0] * Hkv * (Hq // Hkv) * N)))))
-    if ncpu > 0:
-        out["cpu_baseline"] = cpu_baseline(w, args.seed, min(ncpu, nl))
+    if cpu is not None:
+        out["cpu_baseline"] = cpu
     print(json.dumps(out), flush=True)
 
 

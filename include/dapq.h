@@ -68,7 +68,7 @@ typedef struct dapq_shape {
   float scale;            /* 1/sqrt(d_k) (App. C.1: Attention(q,K) = softmax(qK^T/sqrt(d_k))) */
 } dapq_shape;
 
-/* Bytes of device workspace dapq_score / dapq_score_stats / dapq_topk need for this shape
+/* Bytes of device workspace dapq_score / dapq_score_stats / dapq_score_accumulate need for this shape
  * (one figure covers all of them).  Returns 0 if the shape is invalid. */
 size_t dapq_workspace_bytes(const dapq_shape* shape);
 
@@ -202,7 +202,9 @@ int dapq_pool(const dapq_shape* shape, const float* scores, float* pooled, int32
  * result is written in ascending position.  Scores must be non-negative and finite.
  *   budget           slots per head in idx (>= 1)
  *   budget_per_seq   optional device int32 [batch]: budget of each sequence (clamped to [0, budget]); NULL = budget
- *   idx, count       out; idx slots past count are left untouched */
+ *   idx, count       out; idx slots past count are left untouched
+ *   workspace, workspace_bytes   not used: selection keeps its state in registers and LDS; pass NULL and 0 (the
+ *                    arguments are part of the call's published form and are ignored, whatever they hold) */
 int dapq_topk(const dapq_shape* shape, const float* pooled, int32_t budget, const int32_t* budget_per_seq,
               int32_t* idx, int32_t* count, void* workspace, size_t workspace_bytes, void* stream);
 

@@ -295,7 +295,7 @@ def compress(q_bits, k_bits, v_bits, n_kv_heads, Kb, cu_seqlens=None, width=7, s
 
 
 # --------------------------------------------------------------------------------------
-# Sec. 3.3: recall of a predicted retained set against a gold one
+# Sec. 4.1 / Sec. 5.1: the pseudo tokens (which prompt tokens they copy, their positions) and their queries
 # --------------------------------------------------------------------------------------
 def pseudo_tokens(L: int, first_m: int, last_n: int):
     """Sec. 4.1 / Sec. 5.1: the N = m + n pseudo tokens take their content from the first m and the
@@ -339,6 +339,9 @@ def pseudo_queries(x_bits, token_idx, w_bits, n_q_heads, positions=None, theta: 
     return np.ascontiguousarray(q_bits.transpose(1, 0, 2))
 
 
+# --------------------------------------------------------------------------------------
+# Sec. 4.2, last paragraph: decoding from position L_p over the compressed cache only
+# --------------------------------------------------------------------------------------
 def decode_attention(q, k_cache, v_cache, scale=None) -> np.ndarray:
     """One decode step over a cache (Sec. 4.2, last paragraph: decoding starts at position L_p and uses
     only the compressed cache): o = Attention(q, K) V with Attention = softmax(q K^T / sqrt(d_k))
@@ -348,6 +351,9 @@ def decode_attention(q, k_cache, v_cache, scale=None) -> np.ndarray:
     return alpha @ np.asarray(v_cache, dtype=np.float64)
 
 
+# --------------------------------------------------------------------------------------
+# Sec. 3.3: recall of a predicted retained set against a gold one
+# --------------------------------------------------------------------------------------
 def recall(M_gold, M_pred) -> float:
     """|M_gold ∩ M_pred| / |M_gold| (Sec. 3.3, recall equation)."""
     gold = set(int(v) for v in M_gold)

@@ -10,7 +10,9 @@ import os
 from typing import Optional
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_PKG, "libdapq.so")
+# DAPQ_LIBRARY names another build of the same library (the host-sanitized one the tests make); there is no other
+# implementation to fall back to
+_LIB_PATH = os.environ.get("DAPQ_LIBRARY") or os.path.join(_PKG, "libdapq.so")
 _lib = None
 
 EXPORTS = (
@@ -113,8 +115,9 @@ def _stream(stream) -> Optional[int]:
 
 
 def make_shape(*, n_layers, batch, n_q_heads, n_kv_heads, n_pseudo, total_tokens, head_dim=128, cu_seqlens=None,
-               k_strides=(0, 0, 0, 0), v_strides=(0, 0, 0, 0), q_strides=(0, 0, 0, 0), scale=None) -> Shape:
-    """Strides are (layer, seq, head, token|row) in elements.  cu_seqlens: device int32 tensor or None."""
+               k_strides=(0, 0, 0, 0), v_strides=(0, 0, 0, 0), q_strides=(0, 0, 0, 0), scale) -> Shape:
+    """Strides are (layer, seq, head, token|row) in elements.  cu_seqlens: device int32 tensor or None.
+    scale: the softmax scale 1/sqrt(d_k) of App. C.1, as a number: the caller supplies it, nothing is computed here."""
     s = Shape()
     s.n_layers, s.batch, s.n_q_heads, s.n_kv_heads = n_layers, batch, n_q_heads, n_kv_heads
     s.head_dim, s.n_pseudo, s.total_tokens = head_dim, n_pseudo, total_tokens
@@ -122,7 +125,7 @@ def make_shape(*, n_layers, batch, n_q_heads, n_kv_heads, n_pseudo, total_tokens
     s.k_stride_layer, s.k_stride_seq, s.k_stride_head, s.k_stride_token = k_strides
     s.v_stride_layer, s.v_stride_seq, s.v_stride_head, s.v_stride_token = v_strides
     s.q_stride_layer, s.q_stride_seq, s.q_stride_head, s.q_stride_row = q_strides
-    s.scale = float(head_dim) ** -0.5 if scale is None else float(scale)
+    s.scale = float(scale)
     s._keepalive = cu_seqlens
     return s
 

@@ -2,6 +2,9 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
+#include <vector>
+
 #include "dapq_internal.h"
 
 namespace dapq {
@@ -17,6 +20,22 @@ int fail(int code, const char* fmt, ...) {
   vsnprintf(error_buffer(), 512, fmt, ap);
   va_end(ap);
   return code;
+}
+
+int set_max_dynamic_lds(const void* kernel, int bytes) {
+  struct Entry { const void* kernel; int device; };
+  static std::mutex mu;
+  static std::vector<Entry> done;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(DAPQ_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+  std::lock_guard<std::mutex> lock(mu);
+  for (const Entry& it : done)
+    if (it.kernel == kernel && it.device == dev) return DAPQ_OK;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e != hipSuccess) return fail(DAPQ_ERR_HIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
+  done.push_back({kernel, dev});
+  return DAPQ_OK;
 }
 
 static bool stride_ok(int64_t s) { return s >= 0 && (s % 8) == 0; }

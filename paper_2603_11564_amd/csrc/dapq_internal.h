@@ -50,4 +50,9 @@ int make_score_plan(const dapq_shape* s, ScorePlan* plan);
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// Raises a kernel's dynamic-LDS limit to `bytes` (the most that kernel is ever launched with), once per kernel
+// and device.  The value never changes afterwards, so launches from several host threads cannot meet a smaller
+// limit than they need.
+int set_max_dynamic_lds(const void* kernel, int bytes);
+
 }  // namespace dapq

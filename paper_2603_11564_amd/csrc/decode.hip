@@ -207,13 +207,16 @@ extern "C" DAPQ_API int dapq_decode_attention(const dapq_shape* shape, const voi
   p.n_kv_heads = shape->n_kv_heads;
   p.budget = budget;
   p.c = shape->scale * 1.4426950408889634f;
-  const int shared_floats = kDecodeHeads * budget > kDecodeWaves * kDecodeHeads * kHeadDim
-                                ? kDecodeHeads * budget
-                                : kDecodeWaves * kDecodeHeads * kHeadDim;  // weights, later the partial sums
-  const int lds_bytes = (kDecodeHeads * kHeadDim + kDecodeWaves * kDecodeHeads + shared_floats) * (int)sizeof(float);
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_attention_kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-  if (e != hipSuccess) return fail(DAPQ_ERR_HIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
+  auto lds_for = [](int b) {
+    const int shared_floats = kDecodeHeads * b > kDecodeWaves * kDecodeHeads * kHeadDim
+                                  ? kDecodeHeads * b
+                                  : kDecodeWaves * kDecodeHeads * kHeadDim;  // weights, later the partial sums
+    return (kDecodeHeads * kHeadDim + kDecodeWaves * kDecodeHeads + shared_floats) * (int)sizeof(float);
+  };
+  const int lds_bytes = lds_for(budget);
+  // the limit is raised once, to what the largest supported budget needs
+  const int rc_lds = set_max_dynamic_lds(reinterpret_cast<const void*>(decode_attention_kernel), lds_for(kDecodeMaxRows));
+  if (rc_lds != DAPQ_OK) return rc_lds;
   hipLaunchKernelGGL(decode_attention_kernel, dim3((unsigned)shape->n_kv_heads, (unsigned)shape->batch, (unsigned)shape->n_layers),
                      dim3(kDecodeThreads), lds_bytes, static_cast<hipStream_t>(stream), p);
   DAPQ_HIP_LAUNCH_CHECK("decode_attention_kernel");

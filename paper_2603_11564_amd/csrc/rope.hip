@@ -32,7 +32,7 @@ __device__ __forceinline__ uint16_t f64_to_bf16(double x) {
   return (uint16_t)(hi + (up ? 1u : 0u));
 }
 
-__global__ void rope_kernel(const uint16_t* __restrict__ x_in, uint16_t* x_out, const int32_t* __restrict__ pos,
+__global__ void rope_kernel(const uint16_t* x_in, uint16_t* x_out, const int32_t* __restrict__ pos,
                             int64_t rows, int heads, int head_dim, int64_t stride_row, int64_t stride_head,
                             double neg_log2_theta_2_over_d, int pairing, int heads_per_thread) {
   const int half = head_dim >> 1;

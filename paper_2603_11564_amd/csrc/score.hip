@@ -6,7 +6,7 @@
 // with c = scale * log2(e).  "rows" are the R = g*N pseudo-query rows of the g query heads that
 // share one KV head.  Nothing of size N x L_p is ever stored.
 //
-// Work split.  A workgroup is ONE wave.  It keeps a group of up to 256 Q rows of one KV head in
+// Work split.  The unit of work is ONE wave (four independent ones are launched as a workgroup).  It keeps a group of up to 256 Q rows of one KV head in
 // registers as MFMA operand fragments (eight 32-row blocks = 256 registers, pinned to the
 // accumulation half of the register file; one wave per SIMD owns the whole 512-register file) and
 // walks its own chunk of keys of one (layer, sequence, KV head).  Nothing is shared between waves:
@@ -144,6 +144,33 @@ __device__ __forceinline__ void frag_from_q(bf16x8 (&f)[8], const ScoreParams& p
 
 __device__ __forceinline__ float xhalf(float v) { return __shfl_xor(v, 32, 64); }
 
+// v + (v of the lane 32 away), in every lane, on the vector ALU alone (v_permlane32_swap exchanges the upper half of
+// its first operand with the lower half of its second): no trip through LDS, hence no wait on the LDS counter, which
+// with a single wave per SIMD would be dead time.  The wait states around the swap are the ones the hazard rules
+// of gfx950 ask for between a vector write and a lane swap of the same register, and between the swap and its use.
+__device__ __forceinline__ float sum_halves(float v) {
+  float a = v, b = v;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+  return a + b;  // a = (v.lo, v.lo), b = (v.hi, v.hi)
+}
+
+// Column sums of one sub-block go out through a buffer store whose range check drops what must not be written:
+// lanes of the upper half carry an offset far past the end, and keys at or past nkeys fall outside num_records.
+struct ColumnStore {
+  __amdgpu_buffer_rsrc_t rsrc;
+  unsigned lane_off;  // byte offset of this lane's key inside a sub-block; out of range for the upper half
+};
+__device__ __forceinline__ ColumnStore make_column_store(float* out, int nkeys, int n, int h) {
+  ColumnStore cs;
+  cs.rsrc = __builtin_amdgcn_make_buffer_rsrc(out, 0, nkeys * 4, 0x00020000);
+  cs.lane_off = h == 0 ? (unsigned)n * 4u : 0xC0000000u;
+  return cs;
+}
+__device__ __forceinline__ void store_columns(const ColumnStore& cs, int first_key, float v) {
+  __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), cs.rsrc,
+                                            (int)(cs.lane_off + (unsigned)first_key * 4u), 0, 0);
+}
+
 // Row of the 32x32 MFMA result held in accumulator register v of a lane in half h.
 __device__ __forceinline__ int acc_row(int v, int h) { return 8 * (v >> 2) + 4 * h + (v & 3); }
 
@@ -219,6 +246,13 @@ __global__ void score_combine_kernel(ScoreParams p) {
 constexpr int kWaveStages1 = 5;           // pass 1: ring slots (40 KB per wave, 160 KB per compute unit)
 constexpr int kWaveStages2 = 5;           // pass 2: the same
 constexpr int kSubVec = kSubBytes / 16;   // 512 16-byte chunks per sub-block
+// Dense batches launch the waves four to a workgroup, one per SIMD of a compute unit, each with its own chunk and its
+// own ring: they share nothing and never meet at a barrier, but the dispatcher places a quarter as many workgroups,
+// which lets the stream-bound shapes (few query rows) start faster (2-3 % there; nothing at 256 rows).  Ragged
+// batches keep one wave per workgroup: their chunks differ in length, and a workgroup holds its LDS until its
+// longest wave is done.
+constexpr int kWavesPerGroup = 4;
+inline int waves_per_group(const dapq_shape* s) { return s->cu_seqlens == nullptr ? kWavesPerGroup : 1; }
 constexpr int kWaveLds1 = kWaveStages1 * kSubBytes;
 constexpr int kWaveLds2 = kWaveStages2 * kSubBytes;
 
@@ -333,6 +367,7 @@ __device__ __forceinline__ void wave_walk(u32x4* ring, const uint16_t* kbase, in
   unsigned fa[8];
 #pragma unroll
   for (int s = 0; s < 8; ++s) fa[s] = ring_base + (unsigned)(n * 16 + ((2 * s + h) ^ (n & 15))) * 16u;
+  const ColumnStore cols = make_column_store(PASS == 2 ? out : nullptr, PASS == 2 ? nkeys : 0, n, h);
   f32x16 prev;
 #pragma unroll
   for (int v = 0; v < 16; ++v) prev[v] = -INFINITY;  // 2^(-inf) = 0: the first steps add nothing
@@ -368,12 +403,7 @@ __device__ __forceinline__ void wave_walk(u32x4* ring, const uint16_t* kbase, in
                            off2[PASS == 2 ? rb1 : 0][2 * s + 1], sa, sb);
           if (s == 2 && rb == 1) {
             // the adds above took in the last logits of the previous sub-block: its column sums are complete
-            if (sub > sb0) {
-              const float total = sa + sb;
-              const float both = total + xhalf(total);
-              const int key = first_key(sub - 1) + n;
-              if (h == 0 && key < nkeys) out[key] = both;
-            }
+            if (sub > sb0) store_columns(cols, first_key(sub - 1), sum_halves(sa + sb));
             sa = sb = 0.0f;
           }
           DAPQ_WAVE_SLICE_END(prev, x0, x1, sa, sb, fa[(s + 1) & 7]);
@@ -401,12 +431,7 @@ __device__ __forceinline__ void wave_walk(u32x4* ring, const uint16_t* kbase, in
                          sb);
       }
     }
-    if (PASS == 2 && sb1 > sb0) {
-      const float total = sa + sb;
-      const float both = total + xhalf(total);
-      const int key = first_key(sb1 - 1) + n;
-      if (h == 0 && key < nkeys) out[key] = both;
-    }
+    if (PASS == 2 && sb1 > sb0) store_columns(cols, first_key(sb1 - 1), sum_halves(sa + sb));
   }
 }
 
@@ -470,13 +495,16 @@ __device__ __forceinline__ void wave_load_frags(bf16x8 (&kf)[8], const u32x4* sl
 }
 
 template <int NRB>
-__global__ __launch_bounds__(64, 1) void score_wave_pass1_kernel(ScoreParams p) {
-  extern __shared__ u32x4 ring[];
-  const Work w = locate_uniform(p, blockIdx.x);
+__global__ __launch_bounds__(64 * kWavesPerGroup, 1) void score_wave_pass1_kernel(ScoreParams p) {
+  extern __shared__ u32x4 rings[];
+  const int wave_id = uniform_i32((int)(threadIdx.x >> 6));
+  u32x4* ring = rings + wave_id * (kWaveLds1 / 16);
+  const int chunk_id = (int)blockIdx.x * (int)(blockDim.x >> 6) + wave_id;
+  const Work w = locate_uniform(p, chunk_id);
   if (w.nkeys == 0) return;
   // (the division runs on the vector ALU: bring the quotient back to a scalar register)
   const int layer = uniform_i32(blockIdx.z / p.n_kv_heads), kv = blockIdx.z - layer * p.n_kv_heads;
-  const int lane = threadIdx.x, n = lane & 31, h = lane >> 5;
+  const int lane = threadIdx.x & 63, n = lane & 31, h = lane >> 5;
   const uint16_t* qbase = p.q + (int64_t)layer * p.q_stride_layer + (int64_t)w.seq * p.q_stride_seq +
                           (int64_t)kv * p.group * p.q_stride_head;
   const uint16_t* kbase = uniform_ptr(p.k + (int64_t)layer * p.k_stride_layer + (int64_t)w.seq * p.k_stride_seq +
@@ -543,7 +571,7 @@ __global__ __launch_bounds__(64, 1) void score_wave_pass1_kernel(ScoreParams p) 
   }
 
   // the two lane halves hold different keys of the same query
-  float2* outp = p.parts + ((int64_t)blockIdx.z * p.max_chunks + blockIdx.x) * p.rows_pad + gbase;
+  float2* outp = p.parts + ((int64_t)blockIdx.z * p.max_chunks + chunk_id) * p.rows_pad + gbase;
 #pragma unroll
   for (int rb = 0; rb < NRB; ++rb) {
     const float zz = z[rb] + xhalf(z[rb]);
@@ -552,9 +580,11 @@ __global__ __launch_bounds__(64, 1) void score_wave_pass1_kernel(ScoreParams p) 
 }
 
 template <int NRB>
-__global__ __launch_bounds__(64, 1) void score_wave_pass2_kernel(ScoreParams p) {
-  extern __shared__ u32x4 ring[];
-  const Work w = locate_uniform(p, blockIdx.x);
+__global__ __launch_bounds__(64 * kWavesPerGroup, 1) void score_wave_pass2_kernel(ScoreParams p) {
+  extern __shared__ u32x4 rings[];
+  const int wave_id = uniform_i32((int)(threadIdx.x >> 6));
+  u32x4* ring = rings + wave_id * (kWaveLds2 / 16);
+  const Work w = locate_uniform(p, (int)blockIdx.x * (int)(blockDim.x >> 6) + wave_id);
   if (w.nkeys == 0) return;
   // (the division runs on the vector ALU: bring the quotient back to a scalar register)
   // heads and, below, the keys of a chunk are walked in the opposite order to pass 1: what pass 1 read
@@ -562,7 +592,7 @@ __global__ __launch_bounds__(64, 1) void score_wave_pass2_kernel(ScoreParams p) 
   // memory-side cache when pass 2 starts
   const int zz = (int)(gridDim.z - 1 - blockIdx.z);
   const int layer = uniform_i32(zz / p.n_kv_heads), kv = zz - layer * p.n_kv_heads;
-  const int lane = threadIdx.x, n = lane & 31, h = lane >> 5;
+  const int lane = threadIdx.x & 63, n = lane & 31, h = lane >> 5;
   const uint16_t* qbase = p.q + (int64_t)layer * p.q_stride_layer + (int64_t)w.seq * p.q_stride_seq +
                           (int64_t)kv * p.group * p.q_stride_head;
   const uint16_t* kbase = uniform_ptr(p.k + (int64_t)layer * p.k_stride_layer + (int64_t)w.seq * p.k_stride_seq +
@@ -573,7 +603,7 @@ __global__ __launch_bounds__(64, 1) void score_wave_pass2_kernel(ScoreParams p) 
   // result); a small kernel adds the others onto it
   float* plane = blockIdx.y == 0 ? p.scores
                                  : p.partial + (int64_t)(blockIdx.y - 1) * p.n_layers * p.n_kv_heads * p.total_tokens;
-  float* out = plane + ((int64_t)layer * p.n_kv_heads + kv) * p.total_tokens + w.tok0;
+  float* out = const_cast<float*>(uniform_ptr(plane + ((int64_t)layer * p.n_kv_heads + kv) * p.total_tokens + w.tok0));
   const int nsubs = (w.nkeys + 31) / 32;
   unsigned voff[4];
   sub_dma_lane_offsets(voff, p.k_stride_token, lane);
@@ -687,12 +717,7 @@ __global__ void score_group_sum_kernel(const float* partial, float* scores, int6
 }
 
 template <typename F>
-int set_lds(F kernel, int bytes) {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-  if (e != hipSuccess) return fail(DAPQ_ERR_HIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
-  return DAPQ_OK;
-}
+int set_lds(F kernel, int bytes) { return set_max_dynamic_lds(reinterpret_cast<const void*>(kernel), bytes); }
 
 int fill_params(const dapq_shape* s, const ScorePlan& plan, ScoreParams* p) {
   p->cu_seqlens = s->cu_seqlens;
@@ -722,11 +747,13 @@ int launch_stats(const dapq_shape* s, const ScorePlan& plan, ScoreParams p, hipS
     DAPQ_HIP_LAUNCH_CHECK("score_chunk_prefix_kernel");
   }
   int rc = DAPQ_OK;
-  const dim3 grid((unsigned)plan.max_chunks, (unsigned)plan.n_groups, (unsigned)(s->n_layers * s->n_kv_heads));
+  const int wpg = waves_per_group(s);
+  const dim3 grid((unsigned)((plan.max_chunks + wpg - 1) / wpg), (unsigned)plan.n_groups,
+                  (unsigned)(s->n_layers * s->n_kv_heads));
 #define DAPQ_LAUNCH_W1(NRBV)                                                                      \
   do {                                                                                            \
-    if ((rc = set_lds(score_wave_pass1_kernel<NRBV>, kWaveLds1)) != DAPQ_OK) return rc;            \
-    hipLaunchKernelGGL(score_wave_pass1_kernel<NRBV>, grid, dim3(64), kWaveLds1, stream, p);      \
+    if ((rc = set_lds(score_wave_pass1_kernel<NRBV>, kWavesPerGroup * kWaveLds1)) != DAPQ_OK) return rc; \
+    hipLaunchKernelGGL(score_wave_pass1_kernel<NRBV>, grid, dim3(64 * wpg), wpg * kWaveLds1, stream, p);  \
   } while (0)
   if (plan.row_blocks == 2) DAPQ_LAUNCH_W1(2);
   else if (plan.row_blocks == 4) DAPQ_LAUNCH_W1(4);
@@ -747,11 +774,13 @@ int launch_accumulate(const dapq_shape* s, const ScorePlan& plan, ScoreParams p,
     DAPQ_HIP_LAUNCH_CHECK("score_chunk_prefix_kernel");
   }
   int rc = DAPQ_OK;
-  const dim3 grid((unsigned)plan.max_chunks, (unsigned)plan.n_groups, (unsigned)(s->n_layers * s->n_kv_heads));
+  const int wpg = waves_per_group(s);
+  const dim3 grid((unsigned)((plan.max_chunks + wpg - 1) / wpg), (unsigned)plan.n_groups,
+                  (unsigned)(s->n_layers * s->n_kv_heads));
 #define DAPQ_LAUNCH_W2(NRBV)                                                                      \
   do {                                                                                            \
-    if ((rc = set_lds(score_wave_pass2_kernel<NRBV>, kWaveLds2)) != DAPQ_OK) return rc;            \
-    hipLaunchKernelGGL(score_wave_pass2_kernel<NRBV>, grid, dim3(64), kWaveLds2, stream, p);      \
+    if ((rc = set_lds(score_wave_pass2_kernel<NRBV>, kWavesPerGroup * kWaveLds2)) != DAPQ_OK) return rc; \
+    hipLaunchKernelGGL(score_wave_pass2_kernel<NRBV>, grid, dim3(64 * wpg), wpg * kWaveLds2, stream, p);  \
   } while (0)
   if (plan.row_blocks == 2) DAPQ_LAUNCH_W2(2);
   else if (plan.row_blocks == 4) DAPQ_LAUNCH_W2(4);

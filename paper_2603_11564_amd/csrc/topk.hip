@@ -454,12 +454,13 @@ extern "C" DAPQ_API int dapq_topk(const dapq_shape* shape, const float* pooled, 
     // heads of up to kTopkLdsKeys keys are staged in LDS; if none of this launch can be that short the staging
     // area is left out
     const int lds_bytes = (320 + (p.min_len <= kTopkLdsKeys ? kTopkLdsKeys : 0)) * (int)sizeof(uint32_t);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(topk_stream_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-    if (e != hipSuccess) return fail(DAPQ_ERR_HIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
+    // the limit is raised once, to the size with the staging area
+    const int rc_lds = set_max_dynamic_lds(reinterpret_cast<const void*>(topk_stream_kernel),
+                                           (320 + kTopkLdsKeys) * (int)sizeof(uint32_t));
+    if (rc_lds != DAPQ_OK) return rc_lds;
     hipLaunchKernelGGL(topk_stream_kernel, grid, dim3(kTopkThreads), lds_bytes, st, p);
+    DAPQ_HIP_LAUNCH_CHECK("topk_stream_kernel");
   }
-  DAPQ_HIP_LAUNCH_CHECK("topk_stream_kernel");
   return DAPQ_OK;
 }
 

@@ -44,7 +44,8 @@ class Problem:
         qs = (self.batch * self.Hq * self.N * self.d, self.Hq * self.N * self.d, self.N * self.d, self.d)
         self.shape = D.make_shape(n_layers=self.layers, batch=self.batch, n_q_heads=self.Hq, n_kv_heads=self.Hkv,
                                   n_pseudo=self.N, total_tokens=self.tokens, cu_seqlens=self.cu,
-                                  k_strides=ks, v_strides=ks, q_strides=qs, scale=scale)
+                                  k_strides=ks, v_strides=ks, q_strides=qs,
+                                  scale=self.d ** -0.5 if scale is None else scale)
         self.device = device
         self.ws = torch.empty(max(D.workspace_bytes(self.shape), 256), dtype=torch.uint8, device=device)
 

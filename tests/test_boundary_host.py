@@ -21,7 +21,7 @@ def lib():
 def good_shape(**kw):
     args = dict(n_layers=2, batch=1, n_q_heads=32, n_kv_heads=8, n_pseudo=64, total_tokens=4096,
                 k_strides=(4096 * 8 * 128, 0, 128, 8 * 128), v_strides=(4096 * 8 * 128, 0, 128, 8 * 128),
-                q_strides=(32 * 64 * 128, 32 * 64 * 128, 64 * 128, 128))
+                q_strides=(32 * 64 * 128, 32 * 64 * 128, 64 * 128, 128), scale=128 ** -0.5)
     args.update(kw)
     return D.make_shape(**args)
 
@@ -43,6 +43,29 @@ def test_workspace_bytes_is_a_function_of_the_shape(lib):
     assert D.workspace_bytes(good_shape(head_dim=64)) == 0
     assert b"head_dim" in lib.dapq_last_error()
     assert D.workspace_bytes(good_shape(n_q_heads=30)) == 0
+
+
+def test_workspace_bytes_over_a_sweep_of_shapes(lib):
+    """The launch plan (chunking, workspace carving) is pure host arithmetic: walk it over small, huge, ragged and
+    degenerate shapes.  Under the host sanitizers (tests/test_host_sanitizers.py) this is where an overflow or an
+    out-of-range shift in that arithmetic would show."""
+    seen = 0
+    for layers in (1, 32, 80, 8191):
+        for tokens in (0, 1, 31, 4096, 131072, 2 ** 31 - 8):
+            for n_pseudo in (1, 64, 512, 32768):
+                for batch, ragged in ((1, False), (8, False), (8, True), (65535, True)):
+                    if not ragged and tokens % batch:
+                        continue
+                    s = good_shape(n_layers=layers, batch=batch, n_pseudo=n_pseudo, total_tokens=tokens,
+                                   cu_seqlens=None)
+                    if ragged:
+                        s.cu_seqlens = FAKE          # never dereferenced by the plan
+                    b = D.workspace_bytes(s)
+                    assert b % 256 == 0
+                    if layers * 8 <= 65535:
+                        assert b > 0, (layers, tokens, n_pseudo, batch, ragged, lib.dapq_last_error())
+                    seen += 1
+    assert seen > 300
 
 
 FAKE = 0x1000  # never dereferenced: every call below must fail validation first
@@ -221,8 +244,9 @@ def test_header_is_plain_c_and_links_from_a_c_program(tmp_path):
     exe = tmp_path / "abi"
     libdir = os.path.dirname(binding.lib_path())
     subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror",
-                    "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe), "-L", libdir, "-ldapq",
-                    f"-Wl,-rpath,{libdir}", "-Wl,-rpath,/opt/rocm/lib"], check=True, capture_output=True)
+                    "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe), binding.lib_path(),
+                    f"-Wl,-rpath,{libdir}", "-Wl,-rpath,/opt/rocm/lib", "-Wl,--allow-shlib-undefined"],
+                   check=True, capture_output=True)
     out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
     assert int(out[0]) == len(binding.EXPORTS)
     assert int(out[1]) == C.sizeof(binding.Shape) and int(out[2]) == C.sizeof(binding.Qproj)

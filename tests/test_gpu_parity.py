@@ -488,7 +488,7 @@ def test_observation_window_scores_by_composition(H):
     # the batch as the library sees it: B sequences of Lp keys, each followed by N rows (the window) it skips
     shape = H.D.make_shape(n_layers=layers, batch=B, n_q_heads=Hq, n_kv_heads=Hkv, n_pseudo=N, total_tokens=B * Lp,
                            k_strides=(lay, N * tok, d, tok), v_strides=(lay, N * tok, d, tok),
-                           q_strides=(B * Hq * N * d, Hq * N * d, N * d, d))
+                           q_strides=(B * Hq * N * d, Hq * N * d, N * d, d), scale=d ** -0.5)
     ws = torch.empty(max(H.D.workspace_bytes(shape), 256), dtype=torch.uint8, device="cuda")
     lse = torch.empty((layers, B, Hq, N), dtype=torch.float32, device="cuda")
     S = torch.full((layers, Hkv, B * Lp), float("nan"), dtype=torch.float32, device="cuda")
@@ -643,7 +643,7 @@ def test_score_keys_with_a_huge_row_stride(H):
     q = H.dev_bf16(q_bits)
     shape = H.D.make_shape(n_layers=1, batch=1, n_q_heads=Hq, n_kv_heads=1, n_pseudo=N, total_tokens=L,
                            k_strides=(0, 0, 0, stride), v_strides=(0, 0, 0, stride),
-                           q_strides=(Hq * N * d, Hq * N * d, N * d, d))
+                           q_strides=(Hq * N * d, Hq * N * d, N * d, d), scale=d ** -0.5)
     ws = torch.empty(max(H.D.workspace_bytes(shape), 256), dtype=torch.uint8, device="cuda")
     S = torch.full((1, 1, L), float("nan"), dtype=torch.float32, device="cuda")
     H.D.dapq_score(shape, q, wide, S, ws)
@@ -732,7 +732,7 @@ def test_batch_of_empty_prompts(H, ragged):
     cu = torch.zeros(B + 1, dtype=torch.int32, device="cuda") if ragged else None
     shape = D.make_shape(n_layers=layers, batch=B, n_q_heads=Hq, n_kv_heads=Hkv, n_pseudo=N, total_tokens=0, cu_seqlens=cu,
                          k_strides=(0, 0, d, Hkv * d), v_strides=(0, 0, d, Hkv * d),
-                         q_strides=(B * Hq * N * d, Hq * N * d, N * d, d))
+                         q_strides=(B * Hq * N * d, Hq * N * d, N * d, d), scale=d ** -0.5)
     q = torch.randn((layers, B, Hq, N, d), device="cuda").to(torch.bfloat16)
     k = torch.full((1, Hkv, d), float("nan"), device="cuda").to(torch.bfloat16)
     ws = torch.empty(max(D.workspace_bytes(shape), 256), dtype=torch.uint8, device="cuda")
