@@ -246,13 +246,13 @@ __global__ void score_combine_kernel(ScoreParams p) {
 constexpr int kWaveStages1 = 5;           // pass 1: ring slots (40 KB per wave, 160 KB per compute unit)
 constexpr int kWaveStages2 = 5;           // pass 2: the same
 constexpr int kSubVec = kSubBytes / 16;   // 512 16-byte chunks per sub-block
-// Dense batches launch the waves four to a workgroup, one per SIMD of a compute unit, each with its own chunk and its
-// own ring: they share nothing and never meet at a barrier, but the dispatcher places a quarter as many workgroups,
-// which lets the stream-bound shapes (few query rows) start faster (2-3 % there; nothing at 256 rows).  Ragged
-// batches keep one wave per workgroup: their chunks differ in length, and a workgroup holds its LDS until its
-// longest wave is done.
+// A launch whose waves all fit the chip at once (one per SIMD: dense batches are planned that way) starts them
+// four to a workgroup, one per SIMD of a compute unit, each with its own chunk and its own ring: they share nothing
+// and never meet at a barrier, but the dispatcher places a quarter as many workgroups, which lets the stream-bound
+// shapes (few query rows) start faster (2-3 % there; nothing at 256 rows).  Every other launch keeps one wave per
+// workgroup: a workgroup holds its LDS until its last wave is done, which costs up to 30 % once workgroups queue
+// for compute units (measured with two rounds of equal chunks), and ragged chunks differ in length anyway.
 constexpr int kWavesPerGroup = 4;
-inline int waves_per_group(const dapq_shape* s) { return s->cu_seqlens == nullptr ? kWavesPerGroup : 1; }
 constexpr int kWaveLds1 = kWaveStages1 * kSubBytes;
 constexpr int kWaveLds2 = kWaveStages2 * kSubBytes;
 
@@ -719,6 +719,25 @@ __global__ void score_group_sum_kernel(const float* partial, float* scores, int6
 template <typename F>
 int set_lds(F kernel, int bytes) { return set_max_dynamic_lds(reinterpret_cast<const void*>(kernel), bytes); }
 
+// Waves per workgroup for a launch of `waves` waves (see kWavesPerGroup).
+int waves_per_group(const dapq_shape* s, int64_t waves) {
+  static std::mutex mu;
+  static int simds[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 1;
+  int have;
+  {
+    std::lock_guard<std::mutex> lock(mu);
+    if (simds[dev] == 0) {
+      int cus = 0;
+      if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 1;
+      simds[dev] = 4 * cus;
+    }
+    have = simds[dev];
+  }
+  return (s->cu_seqlens == nullptr && waves <= have) ? kWavesPerGroup : 1;
+}
+
 int fill_params(const dapq_shape* s, const ScorePlan& plan, ScoreParams* p) {
   p->cu_seqlens = s->cu_seqlens;
   p->k_stride_layer = s->k_stride_layer; p->k_stride_seq = s->k_stride_seq;
@@ -747,7 +766,7 @@ int launch_stats(const dapq_shape* s, const ScorePlan& plan, ScoreParams p, hipS
     DAPQ_HIP_LAUNCH_CHECK("score_chunk_prefix_kernel");
   }
   int rc = DAPQ_OK;
-  const int wpg = waves_per_group(s);
+  const int wpg = waves_per_group(s, plan.max_chunks * plan.n_groups * s->n_layers * s->n_kv_heads);
   const dim3 grid((unsigned)((plan.max_chunks + wpg - 1) / wpg), (unsigned)plan.n_groups,
                   (unsigned)(s->n_layers * s->n_kv_heads));
 #define DAPQ_LAUNCH_W1(NRBV)                                                                      \
@@ -774,7 +793,7 @@ int launch_accumulate(const dapq_shape* s, const ScorePlan& plan, ScoreParams p,
     DAPQ_HIP_LAUNCH_CHECK("score_chunk_prefix_kernel");
   }
   int rc = DAPQ_OK;
-  const int wpg = waves_per_group(s);
+  const int wpg = waves_per_group(s, plan.max_chunks * plan.n_groups * s->n_layers * s->n_kv_heads);
   const dim3 grid((unsigned)((plan.max_chunks + wpg - 1) / wpg), (unsigned)plan.n_groups,
                   (unsigned)(s->n_layers * s->n_kv_heads));
 #define DAPQ_LAUNCH_W2(NRBV)                                                                      \
