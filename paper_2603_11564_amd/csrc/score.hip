@@ -250,8 +250,8 @@ constexpr int kSubVec = kSubBytes / 16;   // 512 16-byte chunks per sub-block
 // four to a workgroup, one per SIMD of a compute unit, each with its own chunk and its own ring: they share nothing
 // and never meet at a barrier, but the dispatcher places a quarter as many workgroups, which lets the stream-bound
 // shapes (few query rows) start faster (2-3 % there; nothing at 256 rows).  Every other launch keeps one wave per
-// workgroup: a workgroup holds its LDS until its last wave is done, which costs up to 30 % once workgroups queue
-// for compute units (measured with two rounds of equal chunks), and ragged chunks differ in length anyway.
+// workgroup: a workgroup holds its LDS until its last wave is done, so queued workgroups and the unequal chunks of
+// a ragged batch would leave SIMDs idle.
 constexpr int kWavesPerGroup = 4;
 constexpr int kWaveLds1 = kWaveStages1 * kSubBytes;
 constexpr int kWaveLds2 = kWaveStages2 * kSubBytes;
@@ -719,8 +719,9 @@ __global__ void score_group_sum_kernel(const float* partial, float* scores, int6
 template <typename F>
 int set_lds(F kernel, int bytes) { return set_max_dynamic_lds(reinterpret_cast<const void*>(kernel), bytes); }
 
-// Waves per workgroup for a launch of `waves` waves (see kWavesPerGroup).
-int waves_per_group(const dapq_shape* s, int64_t waves) {
+// Waves per workgroup for a launch of `waves` waves in `chunks` chunks along the key axis (see kWavesPerGroup; the
+// waves of a workgroup take consecutive chunks, so the chunk count has to be a multiple or SIMDs would sit idle).
+int waves_per_group(const dapq_shape* s, int64_t waves, int64_t chunks) {
   static std::mutex mu;
   static int simds[64] = {};
   int dev = 0;
@@ -735,7 +736,7 @@ int waves_per_group(const dapq_shape* s, int64_t waves) {
     }
     have = simds[dev];
   }
-  return (s->cu_seqlens == nullptr && waves <= have) ? kWavesPerGroup : 1;
+  return (s->cu_seqlens == nullptr && waves <= have && chunks % kWavesPerGroup == 0) ? kWavesPerGroup : 1;
 }
 
 int fill_params(const dapq_shape* s, const ScorePlan& plan, ScoreParams* p) {
@@ -766,7 +767,7 @@ int launch_stats(const dapq_shape* s, const ScorePlan& plan, ScoreParams p, hipS
     DAPQ_HIP_LAUNCH_CHECK("score_chunk_prefix_kernel");
   }
   int rc = DAPQ_OK;
-  const int wpg = waves_per_group(s, plan.max_chunks * plan.n_groups * s->n_layers * s->n_kv_heads);
+  const int wpg = waves_per_group(s, plan.max_chunks * plan.n_groups * s->n_layers * s->n_kv_heads, plan.max_chunks);
   const dim3 grid((unsigned)((plan.max_chunks + wpg - 1) / wpg), (unsigned)plan.n_groups,
                   (unsigned)(s->n_layers * s->n_kv_heads));
 #define DAPQ_LAUNCH_W1(NRBV)                                                                      \
@@ -793,7 +794,7 @@ int launch_accumulate(const dapq_shape* s, const ScorePlan& plan, ScoreParams p,
     DAPQ_HIP_LAUNCH_CHECK("score_chunk_prefix_kernel");
   }
   int rc = DAPQ_OK;
-  const int wpg = waves_per_group(s, plan.max_chunks * plan.n_groups * s->n_layers * s->n_kv_heads);
+  const int wpg = waves_per_group(s, plan.max_chunks * plan.n_groups * s->n_layers * s->n_kv_heads, plan.max_chunks);
   const dim3 grid((unsigned)((plan.max_chunks + wpg - 1) / wpg), (unsigned)plan.n_groups,
                   (unsigned)(s->n_layers * s->n_kv_heads));
 #define DAPQ_LAUNCH_W2(NRBV)                                                                      \
