@@ -31,15 +31,17 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch), each scaled
-# by what the same counter reads for a copy kernel of known size in the same run (the fp32 -> bf16 conversion
-# of the input generator: 128 MiB read, 64 MiB written); profiles/score_c2_hbm_traffic.md.
+# by what the same counter reads for kernels of known size in the same run (the 2 GiB read-stream probe; the
+# fp32 -> bf16 conversion of the input generator: 128 MiB read, 64 MiB written); profiles/score_c2_hbm_traffic.md.
 MEASURED_TRAFFIC_BYTES = {    # (workload, N, kernel)
-    ("C2", 64, "score_pass2"): 2.250e9,   # 2.217 GB fetched (1.032 x the key bytes: Q is re-read per chunk) + 32 MiB written
-    ("C2", 64, "score_pass1"): 2.217e9,   # 2.214 GB fetched + 2 MiB of partial row statistics written
+    ("C2", 64, "score_pass2"): 2.203e9,   # 2.170 GB fetched (keys + the pseudo queries once per head) + 32 MiB written
+    ("C2", 64, "score_pass1"): 2.170e9,   # 2.168 GB fetched + 2 MiB of partial row statistics written
+    ("C2", 32, "score_pass2"): 2.190e9,   # 2.156 GB fetched + 32 MiB written
+    ("C2", 32, "score_pass1"): 2.157e9,   # 2.156 GB fetched + 1 MiB written
 }
 # Where those figures come from: the profile file and the commit whose score kernels were profiled.  A CPU test
 # (tests/test_bench_host.py) fails when csrc/score.hip has changed since that commit, i.e. when they are stale.
-TRAFFIC_SOURCE = {"file": "profiles/score_c2_hbm_traffic.md", "commit": "b1bbe04"}
+TRAFFIC_SOURCE = {"file": "profiles/score_c2_hbm_traffic.md", "commit": "cf15f37"}
 
 
 def parse():
@@ -233,8 +235,22 @@ def read_stream_gbs(dev, n_bytes=2 << 30):
     return res
 
 
+def shader_clock_mhz():
+    """The shader clock the driver reports right now (the starred level of pp_dpm_sclk), or None."""
+    import glob
+    for path in sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk")):
+        try:
+            for line in open(path):
+                if "*" in line:
+                    return float(line.split(":")[1].lower().replace("mhz", "").replace("*", "").strip())
+        except (OSError, ValueError, IndexError):
+            continue
+    return None
+
+
 def time_passes(ctx, shape, warm, reps):
-    """Average duration (ms) of the two score passes for `shape`, each launched back to back on its own."""
+    """Average duration (ms) of the two score passes for `shape`, each launched back to back on its own, and the
+    shader clock the driver reports while the queued launches run (<name>_mhz; None if it cannot be read)."""
     import torch
     D, stream = ctx.D, ctx.stream
     res = {}
@@ -250,8 +266,13 @@ def time_passes(ctx, shape, warm, reps):
         for _ in range(reps):
             fn()
         e1.record(stream)
+        clocks = []
+        while not e1.query():       # the launches are queued: the GPU is still working through them
+            time.sleep(0.03)
+            clocks.append(shader_clock_mhz())
         torch.cuda.synchronize()
         res[name] = e0.elapsed_time(e1) / reps
+        res[name + "_mhz"] = clocks[2:-1]       # (the first samples see the governor still settling)
     return res
 
 
@@ -290,7 +311,8 @@ def ceilings(ctx, args):
         placements["one_layer_of_keys_for_all"] = one_layer
         placements["one_head_of_keys_for_all"] = one_head
     out["passes_ms"] = {name: time_passes(ctx, shape, args.warmup, args.steps) for name, shape in placements.items()}
-    out["passes_ns_per_slice"] = {name: {k: v * 1e6 / slices for k, v in r.items()} for name, r in out["passes_ms"].items()}
+    out["passes_ns_per_slice"] = {name: {k: v * 1e6 / slices for k, v in r.items() if not k.endswith("_mhz")}
+                                  for name, r in out["passes_ms"].items()}
     return out
 
 
