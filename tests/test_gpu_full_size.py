@@ -78,6 +78,10 @@ def check_all_heads(ctx, w):
     # the 70B-class shape at its full 128k prompt, 2 of its 80 layers: 512 query rows per KV head (two row groups)
     # and heads of 131072 keys, which take the streaming selection kernel and the separate pooling kernel
     ("C5", 2, [(0, 3), (1, 7)]),
+    # the same shape as the configuration names it: all 80 layers resident (21.5 GB of keys, as much of values), so
+    # that the key, value, score and index offsets of the last layers lie far beyond 4 GiB; heads of the first, a
+    # middle and the last layer against the oracle, every head through the properties
+    ("C5", None, [(0, 2), (40, 3), (79, 7)]),
     # the ends of the window-size sweep at its 64k prompt, one layer each: 64 and 2048 query rows per KV head
     ("C4:16", 1, [(0, 1)]),
     ("C4:512", 1, [(0, 6)]),
@@ -119,6 +123,45 @@ def test_full_size_dense_workload(env, name, layers, samples):
         assert np.array_equal(H.host_bits(ctx.v_out[li, 0, kv]), v[keep])
         announce(f"full size {name}: layer {li} head {kv}: max rel err {worst:.2e}")
     announce(f"full size {name}: sampled heads {classes}")
+
+
+def test_full_size_extended_normaliser(env):
+    """The normaliser that includes the pseudo tokens' own keys (Sec. 4.1: the extended sequence is prefilled as
+    one) at the benchmark's shape, through the benchmark's buffers: pass 1, dapq_score_stats_extend, pass 2.
+    Sampled heads against the oracle element by element; every head through what holds at any size: the extra
+    keys can only take attention mass away from the prompt keys, and never all of it."""
+    bench, H = env
+    w = W.workload("C2")
+    seed, L = 0, w.seq_len
+    samples = [(0, 1), (19, 6), (31, 0)]
+    announce("full size C2, extended normaliser: building the workload")
+    host = {(li, kv): host_slice(w, seed, li, 0, kv, L) for (li, kv) in samples}
+    ctx = bench.Context(w, seed, torch.device("cuda:0"), {(li, 0, kv): (k, v) for (li, kv), (q, k, v) in host.items()})
+    D, d, Hq, Hkv, N, nl, g = ctx.D, w.head_dim, w.n_q_heads, w.n_kv_heads, w.n_pseudo, w.n_layers, w.group
+    ctx.step()                                           # rotated pseudo queries, and S over the prompt keys alone
+    torch.cuda.synchronize()
+    S_plain = ctx.S.clone()
+    gen = torch.Generator(device="cuda").manual_seed(11)
+    kp = torch.randn((nl, 1, Hkv, N, d), generator=gen, device="cuda").to(torch.bfloat16)   # the pseudo tokens' keys
+    D.dapq_score_stats(ctx.shape, ctx.q, ctx.k, ctx.lse2, ctx.ws)
+    lse_plain = ctx.lse2.clone()
+    D.dapq_score_stats_extend(ctx.shape, ctx.q, kp, (Hkv * N * d, Hkv * N * d, N * d, d), ctx.lse2)
+    D.dapq_score_accumulate(ctx.shape, ctx.q, ctx.k, ctx.lse2, ctx.S, ctx.ws)
+    torch.cuda.synchronize()
+    assert torch.isfinite(ctx.S).all() and (ctx.S > 0).all()
+    # every row sees at least its own key on top of the prompt (a row whose normaliser a needle dominates may not
+    # move by a whole fp32 step)
+    assert (ctx.lse2 >= lse_plain).all() and (ctx.lse2 > lse_plain).float().mean().item() > 0.9
+    assert (ctx.S <= S_plain * (1 + 1e-6)).all()         # ... so every prompt key gets less
+    mass = ctx.S.double().sum(dim=2)
+    assert (mass < g * N).all() and (mass > 0).all()
+    for (li, kv), (q, k, v) in host.items():
+        announce(f"full size C2, extended normaliser: oracle for layer {li} head {kv}")
+        assert np.array_equal(H.host_bits(ctx.q[li, kv * g:(kv + 1) * g, 0]), q[kv * g:(kv + 1) * g])
+        S_ref = O.score_head(O.bf16_bits_to_f64(q[kv * g:(kv + 1) * g]), O.bf16_bits_to_f64(k), w.scale,
+                             O.bf16_bits_to_f64(H.host_bits(kp[li, 0, kv])))
+        worst = H.assert_scores_close(ctx.S[li, kv].cpu().numpy(), S_ref, f"extended S[{li},{kv}]")
+        announce(f"full size C2, extended normaliser: layer {li} head {kv}: max rel err {worst:.2e}")
 
 
 def test_full_size_ragged_batch(env):
