@@ -97,8 +97,8 @@ int make_score_plan(const dapq_shape* s, ScorePlan* p) {
   // Keys per wave.  The machine runs kWaveSlots waves at a time, each for as long as its chunk; a
   // wave pays a fixed start-up (Q fragments, ring fill) worth about kStartKeys keys.  Dense batches
   // run in whole rounds of equal chunks: pick the chunk with the shortest rounds x (chunk +
-  // start-up).  Ragged batches (lengths unknown on the host) are dispatched as waves drain, so
-  // the cost is the work per slot plus one chunk of tail imbalance.
+  // start-up).  Ragged batches (lengths unknown on the host) are handed out chunk by chunk to
+  // persistent waves, so the cost is the work per slot plus one chunk of tail imbalance.
   constexpr int64_t kWaveSlots = 1024, kStartKeys = 160;
   const int64_t units_per_chunk_row = heads * p->n_groups;
   int chunk = kMinChunkKeys;
@@ -134,6 +134,8 @@ int make_score_plan(const dapq_shape* s, ScorePlan* p) {
   size_t off = 0;
   p->off_cu_chunks = off;
   off = align_up(off + sizeof(int32_t) * ((size_t)s->batch + 1), 256);
+  p->off_work = off;  // ticket counter of a ragged batch's work list
+  off += 256;
   p->off_parts = off;
   off = align_up(off + sizeof(float) * 2 * (size_t)heads * (size_t)p->max_chunks * p->rows_pad, 256);
   p->off_lse2 = off;

@@ -40,7 +40,7 @@ struct ScorePlan {
   int chunk_keys;  // keys per wave (a power of two)
   int64_t max_chunks;  // grid size along the key axis: upper bound on sum_b ceil(L_b / chunk_keys)
   // workspace carving (byte offsets)
-  size_t off_cu_chunks, off_parts, off_lse2, off_partial, total_bytes;
+  size_t off_cu_chunks, off_work, off_parts, off_lse2, off_partial, total_bytes;
 };
 
 // Validates the fields every entry point relies on.  need_q / need_k / need_v say which stride

@@ -50,6 +50,7 @@ struct ScoreParams {
   const uint16_t* k;
   const int32_t* cu_seqlens;  // NULL = dense
   int32_t* cu_chunks;         // [batch+1] prefix of per-sequence chunk counts (ragged only)
+  unsigned* work;             // ragged only: the next (head, row group, chunk) item to hand out; zeroed with cu_chunks
   float2* parts;              // [layer*Hkv][max_chunks][rows_pad] (reference, sum) in the log2 domain
   float* lse2;                // [layer][batch][Hq][N]
   float* scores;              // [layer][Hkv][total_tokens]
@@ -76,6 +77,7 @@ struct Work {
 // The same for a wave-uniform chunk index, with the result pinned to scalar registers: everything
 // derived from it (key base pointer, buffer descriptors, trip counts) then stays scalar too.
 __device__ __forceinline__ int uniform_i32(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ unsigned uniform_u32(unsigned v) { return (unsigned)__builtin_amdgcn_readfirstlane((int)v); }
 template <typename T>
 __device__ __forceinline__ const T* uniform_ptr(const T* ptr) {
   const unsigned long long v = (unsigned long long)(uintptr_t)ptr;
@@ -183,9 +185,13 @@ __device__ __forceinline__ bf16x8 lds_read16(unsigned lane_addr, int const_off) 
 
 // Per-sequence prefix of chunk counts for ragged batches: one wave, 64 sequences per trip (a scan by shuffles
 // inside the wave, the running total carried from trip to trip).
-__global__ void score_chunk_prefix_kernel(const int32_t* cu_seqlens, int32_t* cu_chunks, int batch, int chunk_keys) {
+__global__ void score_chunk_prefix_kernel(const int32_t* cu_seqlens, int32_t* cu_chunks, unsigned* work,
+                                         int batch, int chunk_keys) {
   const int lane = threadIdx.x;  // launched with exactly 64 threads
-  if (lane == 0) cu_chunks[0] = 0;
+  if (lane == 0) {
+    cu_chunks[0] = 0;
+    *work = 0u;  // the pass that follows hands its items out from here
+  }
   int carry = 0;
   for (int b0 = 0; b0 < batch; b0 += 64) {
     const int b = b0 + lane;
@@ -250,8 +256,8 @@ constexpr int kSubVec = kSubBytes / 16;   // 512 16-byte chunks per sub-block
 // four to a workgroup, one per SIMD of a compute unit, each with its own chunk and its own ring: they share nothing
 // and never meet at a barrier, but the dispatcher places a quarter as many workgroups, which lets the stream-bound
 // shapes (few query rows) start faster (2-3 % there; nothing at 256 rows).  Every other launch keeps one wave per
-// workgroup: a workgroup holds its LDS until its last wave is done, so queued workgroups and the unequal chunks of
-// a ragged batch would leave SIMDs idle.
+// workgroup: a workgroup holds its LDS until its last wave is done, so queued workgroups would leave SIMDs idle.
+// (Ragged batches: see the DYN form of the kernels.)
 constexpr int kWavesPerGroup = 4;
 constexpr int kWaveLds1 = kWaveStages1 * kSubBytes;
 constexpr int kWaveLds2 = kWaveStages2 * kSubBytes;
@@ -494,32 +500,70 @@ __device__ __forceinline__ void wave_load_frags(bf16x8 (&kf)[8], const u32x4* sl
   for (int s = 0; s < 8; ++s) kf[s] = __builtin_bit_cast(bf16x8, slot[lds_chunk_index(n, 2 * s + h)]);
 }
 
-template <int NRB>
-__global__ __launch_bounds__(64 * kWavesPerGroup, 1) void score_wave_pass1_kernel(ScoreParams p) {
-  extern __shared__ u32x4 rings[];
-  const int wave_id = uniform_i32((int)(threadIdx.x >> 6));
-  u32x4* ring = rings + wave_id * (kWaveLds1 / 16);
-  const int chunk_id = (int)blockIdx.x * (int)(blockDim.x >> 6) + wave_id;
+// The next item of a ragged batch's work list (see the kernels below): lane 0 takes a ticket, everybody gets it.
+__device__ __forceinline__ unsigned take_item(unsigned* work, int lane) {
+  unsigned v = 0;
+  if (lane == 0) v = atomicAdd(work, 1u);
+  return (unsigned)uniform_i32((int)v);
+}
+
+// The work list of a ragged batch: item = (head * row groups + group) * chunks + chunk, so that consecutive items
+// share the KV head, the row group and mostly the sequence.  (The host launches this form only if the item count
+// fits 31 bits whatever the lengths are.)
+struct Item {
+  int head, group, chunk, seq, nkeys;
+};
+struct ItemList {
+  unsigned chunks, per_head, heads, total;
+  // `reversed`: heads and chunks from the far end (pass 2)
+  __device__ __forceinline__ Item at(const ScoreParams& p, unsigned item, bool reversed) const {
+    const unsigned head = uniform_u32(item / per_head), rest = item - head * per_head;
+    const unsigned group = uniform_u32(rest / chunks), chunk = rest - group * chunks;
+    Item it;
+    it.head = (int)(reversed ? heads - 1 - head : head);
+    it.group = (int)group;
+    it.chunk = (int)(reversed ? chunks - 1 - chunk : chunk);
+    const Work w = locate_uniform(p, it.chunk);
+    it.seq = w.seq;
+    it.nkeys = w.nkeys;
+    return it;
+  }
+};
+__device__ __forceinline__ ItemList item_list(const ScoreParams& p) {
+  ItemList l;
+  l.chunks = (unsigned)uniform_i32(p.cu_chunks[p.batch]);
+  l.per_head = l.chunks * (unsigned)p.n_groups;
+  l.heads = (unsigned)(p.n_layers * p.n_kv_heads);
+  l.total = l.per_head * l.heads;
+  return l;
+}
+
+// Pass 1 of one chunk: `head` = layer * n_kv_heads + KV head, `group` = row group, `chunk_id` = chunk along the packed
+// key axis.  LOAD_Q: fetch the query fragments first (otherwise qf holds them already: same head, row group and
+// sequence as the wave's last chunk).  If `work` is not NULL the ticket for the wave's next item is taken while the
+// chunk drains (so its round trip costs nothing) and returned.  The chunk must have keys.
+template <int NRB, bool LOAD_Q>
+__device__ __forceinline__ unsigned pass1_item(const ScoreParams& p, u32x4* ring, int chunk_id, int group, int head,
+                                               bf16x8 (&qf)[NRB][8], const unsigned (&voff)[4], int lane,
+                                               unsigned* work) {
   const Work w = locate_uniform(p, chunk_id);
-  if (w.nkeys == 0) return;
   // (the division runs on the vector ALU: bring the quotient back to a scalar register)
-  const int layer = uniform_i32(blockIdx.z / p.n_kv_heads), kv = blockIdx.z - layer * p.n_kv_heads;
-  const int lane = threadIdx.x & 63, n = lane & 31, h = lane >> 5;
+  const int layer = uniform_i32(head / p.n_kv_heads), kv = head - layer * p.n_kv_heads;
+  const int n = lane & 31, h = lane >> 5;
   const uint16_t* qbase = p.q + (int64_t)layer * p.q_stride_layer + (int64_t)w.seq * p.q_stride_seq +
                           (int64_t)kv * p.group * p.q_stride_head;
   const uint16_t* kbase = uniform_ptr(p.k + (int64_t)layer * p.k_stride_layer + (int64_t)w.seq * p.k_stride_seq +
                                       (int64_t)kv * p.k_stride_head + w.tok0 * p.k_stride_token);
-  const int gbase = blockIdx.y * (NRB * 32);  // first row of this wave's row group
+  const int gbase = group * (NRB * 32);  // first row of this wave's row group
   const int nsubs = (w.nkeys + 31) / 32, nfull = w.nkeys / 32;
-  unsigned voff[4];
-  sub_dma_lane_offsets(voff, p.k_stride_token, lane);
   // the ring is filled whether the sub-blocks exist or not (sub_dma): the waits count operations
 #pragma unroll
   for (int i = 0; i < kWaveStages1; ++i) sub_dma(ring + i * kSubVec, kbase, p.k_stride_token, i * 32, w.nkeys, voff);
-  bf16x8 qf[NRB][8];
+  if (LOAD_Q) {
 #pragma unroll
-  for (int rb = 0; rb < NRB; ++rb) frag_from_q(qf[rb], p, qbase, gbase + rb * 32 + n, h);
-  if (NRB == 8) pin_q_in_agprs<NRB>(qf);
+    for (int rb = 0; rb < NRB; ++rb) frag_from_q(qf[rb], p, qbase, gbase + rb * 32 + n, h);
+    if (NRB == 8) pin_q_in_agprs<NRB>(qf);
+  }
 
   float ref[NRB], z[NRB];
 #pragma unroll
@@ -546,9 +590,11 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 1) void score_wave_pass1_kerne
 #pragma unroll
       for (int rb = 0; rb < NRB; ++rb) z[rb] += zs[rb];
     }
-    if (nfull < nsubs && nfull >= 1)  // the partial last sub-block; its fragments are in kf
-      wave_sub_simple<NRB, false, false>(kf, qf, p.c, ref, z, nfull * 32, w.nkeys, h);
   }
+  // (no counted wait follows: the ticket's round trip overlaps what is left of the chunk)
+  const unsigned next = work != nullptr ? take_item(work, lane) : 0u;
+  if (nsubs > 1 && nfull < nsubs && nfull >= 1)  // the partial last sub-block; its fragments are in kf
+    wave_sub_simple<NRB, false, false>(kf, qf, p.c, ref, z, nfull * 32, w.nkeys, h);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
   // a sum that is not finite means a logit sat more than ~127 binades above the reference: redo
@@ -567,76 +613,107 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 1) void score_wave_pass1_kerne
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       wave_load_frags<NRB>(kf, ring, n, h);
       wave_sub_simple<NRB, true, false>(kf, qf, p.c, ref, z, sub * 32, w.nkeys, h);
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the fragments are out of the slot before it is refilled
     }
   }
 
   // the two lane halves hold different keys of the same query
-  float2* outp = p.parts + ((int64_t)blockIdx.z * p.max_chunks + chunk_id) * p.rows_pad + gbase;
+  float2* outp = p.parts + ((int64_t)head * p.max_chunks + chunk_id) * p.rows_pad + gbase;
 #pragma unroll
   for (int rb = 0; rb < NRB; ++rb) {
     const float zz = z[rb] + xhalf(z[rb]);
     if (h == 0) outp[rb * 32 + n] = make_float2(ref[rb], zz);
   }
+  return next;
 }
 
-template <int NRB>
-__global__ __launch_bounds__(64 * kWavesPerGroup, 1) void score_wave_pass2_kernel(ScoreParams p) {
+// DYN = false (dense batches): the grid names the items, one per wave: (chunk, row group, layer x KV head).
+// DYN = true (ragged batches, whose lengths the host does not know): one persistent wave per SIMD takes items from a
+// work list in device memory until it is empty.  Items are numbered so that consecutive ones share the KV head, the
+// row group and mostly the sequence -- a wave that takes several in a row loads its query fragments once -- and a short
+// chunk costs a ticket and a ring refill instead of a workgroup launch; the hand-out also evens out the ragged tail.
+template <int NRB, bool DYN>
+__global__ __launch_bounds__(64 * kWavesPerGroup, 1) void score_wave_pass1_kernel(ScoreParams p) {
   extern __shared__ u32x4 rings[];
   const int wave_id = uniform_i32((int)(threadIdx.x >> 6));
-  u32x4* ring = rings + wave_id * (kWaveLds2 / 16);
-  const Work w = locate_uniform(p, (int)blockIdx.x * (int)(blockDim.x >> 6) + wave_id);
-  if (w.nkeys == 0) return;
+  u32x4* ring = rings + wave_id * (kWaveLds1 / 16);
+  const int lane = threadIdx.x & 63;
+  unsigned voff[4];
+  sub_dma_lane_offsets(voff, p.k_stride_token, lane);
+  bf16x8 qf[NRB][8];
+  if (!DYN) {
+    const int chunk_id = (int)blockIdx.x * (int)(blockDim.x >> 6) + wave_id;
+    if (locate_uniform(p, chunk_id).nkeys == 0) return;
+    pass1_item<NRB, true>(p, ring, chunk_id, (int)blockIdx.y, (int)blockIdx.z, qf, voff, lane, nullptr);
+    return;
+  }
+  const ItemList items = item_list(p);
+  unsigned item = take_item(p.work, lane);
+  while (item < items.total) {  // every wave leaves: the tickets only grow
+    const Item a = items.at(p, item, false);
+    if (a.nkeys == 0) {  // (no chunk of the list is empty; if one were, it would only cost its ticket)
+      item = take_item(p.work, lane);
+      continue;
+    }
+    item = pass1_item<NRB, true>(p, ring, a.chunk, a.group, a.head, qf, voff, lane, p.work);
+    while (item < items.total) {  // the run of items that use the same queries
+      const Item b = items.at(p, item, false);
+      if (b.head != a.head || b.group != a.group || b.seq != a.seq || b.nkeys == 0) break;
+      item = pass1_item<NRB, false>(p, ring, b.chunk, b.group, b.head, qf, voff, lane, p.work);
+    }
+  }
+}
+
+// Pass 2 of one chunk (arguments as pass1_item).
+template <int NRB, bool LOAD_Q>
+__device__ __forceinline__ unsigned pass2_item(const ScoreParams& p, u32x4* ring, int chunk_id, int group, int head,
+                                               bf16x8 (&qf)[NRB][8], float (&off2)[NRB][16],
+                                               const unsigned (&voff)[4], int lane, unsigned* work) {
+  const Work w = locate_uniform(p, chunk_id);
   // (the division runs on the vector ALU: bring the quotient back to a scalar register)
-  // heads and, below, the keys of a chunk are walked in the opposite order to pass 1: what pass 1 read
-  // last (the ends of the chunks in flight, the heads of the last round) is still in the 256 MB
-  // memory-side cache when pass 2 starts
-  const int zz = (int)(gridDim.z - 1 - blockIdx.z);
-  const int layer = uniform_i32(zz / p.n_kv_heads), kv = zz - layer * p.n_kv_heads;
-  const int lane = threadIdx.x & 63, n = lane & 31, h = lane >> 5;
+  const int layer = uniform_i32(head / p.n_kv_heads), kv = head - layer * p.n_kv_heads;
+  const int n = lane & 31, h = lane >> 5;
   const uint16_t* qbase = p.q + (int64_t)layer * p.q_stride_layer + (int64_t)w.seq * p.q_stride_seq +
                           (int64_t)kv * p.group * p.q_stride_head;
   const uint16_t* kbase = uniform_ptr(p.k + (int64_t)layer * p.k_stride_layer + (int64_t)w.seq * p.k_stride_seq +
                                       (int64_t)kv * p.k_stride_head + w.tok0 * p.k_stride_token);
   const float* lse = p.lse2 + (((int64_t)layer * p.batch + w.seq) * p.n_q_heads + (int64_t)kv * p.group) * p.n_pseudo;
-  const int gbase = blockIdx.y * (NRB * 32);  // first row of this wave's row group
+  const int gbase = group * (NRB * 32);  // first row of this wave's row group
   // with several row groups each writes its own plane of column sums (group 0 straight into the
   // result); a small kernel adds the others onto it
-  float* plane = blockIdx.y == 0 ? p.scores
-                                 : p.partial + (int64_t)(blockIdx.y - 1) * p.n_layers * p.n_kv_heads * p.total_tokens;
+  float* plane = group == 0 ? p.scores : p.partial + (int64_t)(group - 1) * p.n_layers * p.n_kv_heads * p.total_tokens;
   float* out = const_cast<float*>(uniform_ptr(plane + ((int64_t)layer * p.n_kv_heads + kv) * p.total_tokens + w.tok0));
   const int nsubs = (w.nkeys + 31) / 32;
-  unsigned voff[4];
-  sub_dma_lane_offsets(voff, p.k_stride_token, lane);
 #pragma unroll
   for (int i = 0; i < kWaveStages2; ++i)
     sub_dma(ring + i * kSubVec, kbase, p.k_stride_token, (nsubs - 1 - i) * 32, w.nkeys, voff);
-  bf16x8 qf[NRB][8];
+  if (LOAD_Q) {
 #pragma unroll
-  for (int rb = 0; rb < NRB; ++rb) frag_from_q(qf[rb], p, qbase, gbase + rb * 32 + n, h);
-  if (NRB == 8) pin_q_in_agprs<NRB>(qf);
-  // -lse2 of the rows this lane's accumulator registers hold; -inf for padding rows, which then add 0
-  float off2[NRB][16];
-  if ((reinterpret_cast<uintptr_t>(lse) & 15) == 0 && (p.rows & 3) == 0) {
-    // the four rows of an accumulator quad are consecutive: one 16-byte load each
+    for (int rb = 0; rb < NRB; ++rb) frag_from_q(qf[rb], p, qbase, gbase + rb * 32 + n, h);
+    if (NRB == 8) pin_q_in_agprs<NRB>(qf);
+    // -lse2 of the rows this lane's accumulator registers hold; -inf for padding rows, which then add 0
+    if ((reinterpret_cast<uintptr_t>(lse) & 15) == 0 && (p.rows & 3) == 0) {
+      // the four rows of an accumulator quad are consecutive: one 16-byte load each
 #pragma unroll
-    for (int rb = 0; rb < NRB; ++rb)
+      for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
-      for (int b = 0; b < 4; ++b) {
-        const int row = gbase + rb * 32 + acc_row(4 * b, h);
-        const float4 v = row < p.rows ? *reinterpret_cast<const float4*>(lse + row) : make_float4(INFINITY, INFINITY, INFINITY, INFINITY);
-        off2[rb][4 * b] = -v.x;
-        off2[rb][4 * b + 1] = -v.y;
-        off2[rb][4 * b + 2] = -v.z;
-        off2[rb][4 * b + 3] = -v.w;
-      }
-  } else {
+        for (int b = 0; b < 4; ++b) {
+          const int row = gbase + rb * 32 + acc_row(4 * b, h);
+          const float4 v = row < p.rows ? *reinterpret_cast<const float4*>(lse + row) : make_float4(INFINITY, INFINITY, INFINITY, INFINITY);
+          off2[rb][4 * b] = -v.x;
+          off2[rb][4 * b + 1] = -v.y;
+          off2[rb][4 * b + 2] = -v.z;
+          off2[rb][4 * b + 3] = -v.w;
+        }
+    } else {
 #pragma unroll
-    for (int rb = 0; rb < NRB; ++rb)
+      for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = gbase + rb * 32 + acc_row(v, h);
-        off2[rb][v] = row < p.rows ? -lse[row] : -INFINITY;
-      }
+        for (int v = 0; v < 16; ++v) {
+          const int row = gbase + rb * 32 + acc_row(v, h);
+          off2[rb][v] = row < p.rows ? -lse[row] : -INFINITY;
+        }
+    }
   }
   bf16x8 kf[8];
   wait_subblocks(kWaveStages2 - 1);
@@ -646,7 +723,45 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 1) void score_wave_pass2_kerne
   for (int rb = 0; rb < NRB; ++rb) unused_off[rb] = 0.0f;
   wave_walk<NRB, 2, kWaveStages2, true>(ring, kbase, p.k_stride_token, w.nkeys, 0, nsubs, kf, qf, p.c, unused_off, off2,
                                         unused_acc, out, voff, n, h, nsubs - 1);
+  const unsigned next = work != nullptr ? take_item(work, lane) : 0u;
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  return next;
+}
+
+// (DYN as in pass 1.)  Heads and, inside a chunk, the keys are walked in the opposite order to pass 1: what pass 1
+// read last (the ends of the chunks in flight, the heads of the last round) is still in the 256 MB memory-side cache
+// when pass 2 starts.
+template <int NRB, bool DYN>
+__global__ __launch_bounds__(64 * kWavesPerGroup, 1) void score_wave_pass2_kernel(ScoreParams p) {
+  extern __shared__ u32x4 rings[];
+  const int wave_id = uniform_i32((int)(threadIdx.x >> 6));
+  u32x4* ring = rings + wave_id * (kWaveLds2 / 16);
+  const int lane = threadIdx.x & 63;
+  unsigned voff[4];
+  sub_dma_lane_offsets(voff, p.k_stride_token, lane);
+  bf16x8 qf[NRB][8];
+  float off2[NRB][16];
+  if (!DYN) {
+    const int chunk_id = (int)blockIdx.x * (int)(blockDim.x >> 6) + wave_id;
+    if (locate_uniform(p, chunk_id).nkeys == 0) return;
+    pass2_item<NRB, true>(p, ring, chunk_id, (int)blockIdx.y, (int)(gridDim.z - 1 - blockIdx.z), qf, off2, voff, lane, nullptr);
+    return;
+  }
+  const ItemList items = item_list(p);
+  unsigned item = take_item(p.work, lane);
+  while (item < items.total) {
+    const Item a = items.at(p, item, true);
+    if (a.nkeys == 0) {
+      item = take_item(p.work, lane);
+      continue;
+    }
+    item = pass2_item<NRB, true>(p, ring, a.chunk, a.group, a.head, qf, off2, voff, lane, p.work);
+    while (item < items.total) {
+      const Item b = items.at(p, item, true);
+      if (b.head != a.head || b.group != a.group || b.seq != a.seq || b.nkeys == 0) break;
+      item = pass2_item<NRB, false>(p, ring, b.chunk, b.group, b.head, qf, off2, voff, lane, p.work);
+    }
+  }
 }
 
 // The causal block of the pseudo tokens' own keys (Sec. 4.1: they are prefilled in-sequence): one wave
@@ -719,24 +834,25 @@ __global__ void score_group_sum_kernel(const float* partial, float* scores, int6
 template <typename F>
 int set_lds(F kernel, int bytes) { return set_max_dynamic_lds(reinterpret_cast<const void*>(kernel), bytes); }
 
-// Waves per workgroup for a launch of `waves` waves in `chunks` chunks along the key axis (see kWavesPerGroup; the
-// waves of a workgroup take consecutive chunks, so the chunk count has to be a multiple or SIMDs would sit idle).
-int waves_per_group(const dapq_shape* s, int64_t waves, int64_t chunks) {
+// SIMDs of the current device (4 per compute unit); 4 if the device cannot be asked.
+int simd_count() {
   static std::mutex mu;
   static int simds[64] = {};
   int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 1;
-  int have;
-  {
-    std::lock_guard<std::mutex> lock(mu);
-    if (simds[dev] == 0) {
-      int cus = 0;
-      if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 1;
-      simds[dev] = 4 * cus;
-    }
-    have = simds[dev];
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 4;
+  std::lock_guard<std::mutex> lock(mu);
+  if (simds[dev] == 0) {
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 1;
+    simds[dev] = 4 * cus;
   }
-  return (s->cu_seqlens == nullptr && waves <= have && chunks % kWavesPerGroup == 0) ? kWavesPerGroup : 1;
+  return simds[dev];
+}
+
+// Waves per workgroup for a launch of `waves` waves in `chunks` chunks along the key axis (see kWavesPerGroup; the
+// waves of a workgroup take consecutive chunks, so the chunk count has to be a multiple or SIMDs would sit idle).
+int waves_per_group(const dapq_shape* s, int64_t waves, int64_t chunks) {
+  return (s->cu_seqlens == nullptr && waves <= simd_count() && chunks % kWavesPerGroup == 0) ? kWavesPerGroup : 1;
 }
 
 int fill_params(const dapq_shape* s, const ScorePlan& plan, ScoreParams* p) {
@@ -762,18 +878,28 @@ int aligned16(const void* ptr, const char* name) {
 
 int launch_stats(const dapq_shape* s, const ScorePlan& plan, ScoreParams p, hipStream_t stream) {
   if (s->cu_seqlens != nullptr) {
-    hipLaunchKernelGGL(score_chunk_prefix_kernel, dim3(1), dim3(64), 0, stream, s->cu_seqlens, p.cu_chunks, s->batch,
-                       plan.chunk_keys);
+    hipLaunchKernelGGL(score_chunk_prefix_kernel, dim3(1), dim3(64), 0, stream, s->cu_seqlens, p.cu_chunks, p.work,
+                       s->batch, plan.chunk_keys);
     DAPQ_HIP_LAUNCH_CHECK("score_chunk_prefix_kernel");
   }
   int rc = DAPQ_OK;
-  const int wpg = waves_per_group(s, plan.max_chunks * plan.n_groups * s->n_layers * s->n_kv_heads, plan.max_chunks);
+  const int64_t waves = plan.max_chunks * plan.n_groups * s->n_layers * s->n_kv_heads;
+  const int wpg = waves_per_group(s, waves, plan.max_chunks);
+  // ragged: persistent waves, one per SIMD, take their chunks from a work list (32-bit tickets)
+  const bool dyn = s->cu_seqlens != nullptr && waves < ((int64_t)1 << 31);
+  const int simds = simd_count();
+  const dim3 dyn_grid((unsigned)(waves < simds ? waves : simds));
   const dim3 grid((unsigned)((plan.max_chunks + wpg - 1) / wpg), (unsigned)plan.n_groups,
                   (unsigned)(s->n_layers * s->n_kv_heads));
-#define DAPQ_LAUNCH_W1(NRBV)                                                                      \
-  do {                                                                                            \
-    if ((rc = set_lds(score_wave_pass1_kernel<NRBV>, kWavesPerGroup * kWaveLds1)) != DAPQ_OK) return rc; \
-    hipLaunchKernelGGL(score_wave_pass1_kernel<NRBV>, grid, dim3(64 * wpg), wpg * kWaveLds1, stream, p);  \
+#define DAPQ_LAUNCH_W1(NRBV)                                                                                        \
+  do {                                                                                                              \
+    if (dyn) {                                                                                                      \
+      if ((rc = set_lds(score_wave_pass1_kernel<NRBV, true>, kWaveLds1)) != DAPQ_OK) return rc;                      \
+      hipLaunchKernelGGL((score_wave_pass1_kernel<NRBV, true>), dyn_grid, dim3(64), kWaveLds1, stream, p);           \
+    } else {                                                                                                        \
+      if ((rc = set_lds(score_wave_pass1_kernel<NRBV, false>, kWavesPerGroup * kWaveLds1)) != DAPQ_OK) return rc;    \
+      hipLaunchKernelGGL((score_wave_pass1_kernel<NRBV, false>), grid, dim3(64 * wpg), wpg * kWaveLds1, stream, p);  \
+    }                                                                                                               \
   } while (0)
   if (plan.row_blocks == 2) DAPQ_LAUNCH_W1(2);
   else if (plan.row_blocks == 4) DAPQ_LAUNCH_W1(4);
@@ -789,18 +915,28 @@ int launch_stats(const dapq_shape* s, const ScorePlan& plan, ScoreParams p, hipS
 int launch_accumulate(const dapq_shape* s, const ScorePlan& plan, ScoreParams p, hipStream_t stream) {
   if (s->cu_seqlens != nullptr) {
     // pass 2 can be called on its own: rebuild the chunk prefix it walks
-    hipLaunchKernelGGL(score_chunk_prefix_kernel, dim3(1), dim3(64), 0, stream, s->cu_seqlens, p.cu_chunks, s->batch,
-                       plan.chunk_keys);
+    hipLaunchKernelGGL(score_chunk_prefix_kernel, dim3(1), dim3(64), 0, stream, s->cu_seqlens, p.cu_chunks, p.work,
+                       s->batch, plan.chunk_keys);
     DAPQ_HIP_LAUNCH_CHECK("score_chunk_prefix_kernel");
   }
   int rc = DAPQ_OK;
-  const int wpg = waves_per_group(s, plan.max_chunks * plan.n_groups * s->n_layers * s->n_kv_heads, plan.max_chunks);
+  const int64_t waves = plan.max_chunks * plan.n_groups * s->n_layers * s->n_kv_heads;
+  const int wpg = waves_per_group(s, waves, plan.max_chunks);
+  // ragged: persistent waves, one per SIMD, take their chunks from a work list (32-bit tickets)
+  const bool dyn = s->cu_seqlens != nullptr && waves < ((int64_t)1 << 31);
+  const int simds = simd_count();
+  const dim3 dyn_grid((unsigned)(waves < simds ? waves : simds));
   const dim3 grid((unsigned)((plan.max_chunks + wpg - 1) / wpg), (unsigned)plan.n_groups,
                   (unsigned)(s->n_layers * s->n_kv_heads));
-#define DAPQ_LAUNCH_W2(NRBV)                                                                      \
-  do {                                                                                            \
-    if ((rc = set_lds(score_wave_pass2_kernel<NRBV>, kWavesPerGroup * kWaveLds2)) != DAPQ_OK) return rc; \
-    hipLaunchKernelGGL(score_wave_pass2_kernel<NRBV>, grid, dim3(64 * wpg), wpg * kWaveLds2, stream, p);  \
+#define DAPQ_LAUNCH_W2(NRBV)                                                                                        \
+  do {                                                                                                              \
+    if (dyn) {                                                                                                      \
+      if ((rc = set_lds(score_wave_pass2_kernel<NRBV, true>, kWaveLds2)) != DAPQ_OK) return rc;                      \
+      hipLaunchKernelGGL((score_wave_pass2_kernel<NRBV, true>), dyn_grid, dim3(64), kWaveLds2, stream, p);           \
+    } else {                                                                                                        \
+      if ((rc = set_lds(score_wave_pass2_kernel<NRBV, false>, kWavesPerGroup * kWaveLds2)) != DAPQ_OK) return rc;    \
+      hipLaunchKernelGGL((score_wave_pass2_kernel<NRBV, false>), grid, dim3(64 * wpg), wpg * kWaveLds2, stream, p);  \
+    }                                                                                                               \
   } while (0)
   if (plan.row_blocks == 2) DAPQ_LAUNCH_W2(2);
   else if (plan.row_blocks == 4) DAPQ_LAUNCH_W2(4);
@@ -848,6 +984,7 @@ extern "C" DAPQ_API int dapq_score_stats(const dapq_shape* shape, const void* q,
   p.q = static_cast<const uint16_t*>(q);
   p.k = static_cast<const uint16_t*>(k);
   p.cu_chunks = reinterpret_cast<int32_t*>(ws + plan.off_cu_chunks);
+  p.work = reinterpret_cast<unsigned*>(ws + plan.off_work);
   p.parts = reinterpret_cast<float2*>(ws + plan.off_parts);
   p.lse2 = lse2;
   p.scores = nullptr;
@@ -872,6 +1009,7 @@ extern "C" DAPQ_API int dapq_score_accumulate(const dapq_shape* shape, const voi
   p.q = static_cast<const uint16_t*>(q);
   p.k = static_cast<const uint16_t*>(k);
   p.cu_chunks = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + plan.off_cu_chunks);
+  p.work = reinterpret_cast<unsigned*>(static_cast<char*>(workspace) + plan.off_work);
   p.parts = nullptr;
   p.partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + plan.off_partial);
   p.lse2 = const_cast<float*>(lse2);
@@ -915,6 +1053,7 @@ extern "C" DAPQ_API int dapq_score_stats_extend(const dapq_shape* shape, const v
   p.q = static_cast<const uint16_t*>(q);
   p.k = nullptr;
   p.cu_chunks = nullptr;
+  p.work = nullptr;
   p.parts = nullptr;
   p.partial = nullptr;
   p.scores = nullptr;
