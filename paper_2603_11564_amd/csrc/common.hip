@@ -98,7 +98,7 @@ int make_score_plan(const dapq_shape* s, ScorePlan* p) {
   // wave pays a fixed start-up (Q fragments, ring fill) worth about kStartKeys keys.  Dense batches
   // run in whole rounds of equal chunks: pick the chunk with the shortest rounds x (chunk +
   // start-up).  Ragged batches (lengths unknown on the host) are handed out chunk by chunk to
-  // persistent waves, so the cost is the work per slot plus one chunk of tail imbalance.
+  // persistent waves, so the cost is the work per slot plus half a chunk of tail imbalance on average.
   constexpr int64_t kWaveSlots = 1024, kStartKeys = 160;
   const int64_t units_per_chunk_row = heads * p->n_groups;
   int chunk = kMinChunkKeys;
@@ -113,7 +113,7 @@ int make_score_plan(const dapq_shape* s, ScorePlan* p) {
     } else {
       const int64_t chunks = (s->total_tokens + c - 1) / c + s->batch / 2;
       const int64_t units = units_per_chunk_row * chunks;
-      cost = (units_per_chunk_row * s->total_tokens + units * kStartKeys) / kWaveSlots + c;
+      cost = (units_per_chunk_row * s->total_tokens + units * kStartKeys) / kWaveSlots + c / 2;
     }
     if (cost < best) {
       best = cost;

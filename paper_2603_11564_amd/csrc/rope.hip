@@ -8,7 +8,7 @@
 // fp64 keeps the angle exact enough at positions beyond 10^5 (an fp32 product pos * omega would be
 // off by ~1e-2 rad there); the rotation is done in fp64 as well and rounded to bf16 once, which is
 // what makes the result equal to a float64 evaluation bit for bit, and what the kernel's time goes
-// into (about 35 instructions per rotated pair).
+// into (fp64 multiplies and the two conversions per rotated pair).
 #include <math.h>
 
 #include "dapq_internal.h"
@@ -18,18 +18,19 @@ namespace {
 
 __device__ __forceinline__ double bf16_to_f64(uint16_t b) { return (double)__uint_as_float((uint32_t)b << 16); }
 
-// fp64 -> bf16, round to nearest even, without an intermediate fp32 rounding: the fp32 conversion
-// truncates toward zero (the discarded fp64 bits are folded into a sticky bit), then the 16 low
-// bits are rounded.
+// fp64 -> bf16, round to nearest even, as if in one step: the value is first brought to fp32 with rounding to odd
+// (truncate toward zero, then set the last bit if anything was cut off: the cut-off part can then neither make nor
+// break a tie 16 bits further up), and the 16 low bits are rounded by the hardware conversion.  The truncation is
+// the ordinary (nearest) conversion stepped back by one unit when it went away from zero.
 __device__ __forceinline__ uint16_t f64_to_bf16(double x) {
-  float f = __double2float_rz(x);
+  const float f = (float)x;
+  const double back = (double)f;
   uint32_t u = __float_as_uint(f);
-  if ((u & 0x7F800000u) == 0x7F800000u) return (uint16_t)(u >> 16);  // inf / nan pass through
-  const bool sticky = (double)f != x;
-  const uint32_t low = u & 0xFFFFu;
-  uint32_t hi = u >> 16;
-  const bool up = low > 0x8000u || (low == 0x8000u && (sticky || (hi & 1u)));
-  return (uint16_t)(hi + (up ? 1u : 0u));
+  if (back != x) {  // inexact (also true for NaN, which stays NaN)
+    if (fabs(back) > fabs(x)) u -= 1u;
+    u |= 1u;
+  }
+  return __builtin_bit_cast(uint16_t, (__bf16)__uint_as_float(u));
 }
 
 __global__ void rope_kernel(const uint16_t* x_in, uint16_t* x_out, const int32_t* __restrict__ pos,

@@ -10,9 +10,10 @@
 // (no atomic decides an order).  Max-pooling makes runs of bit-equal scores, so the tie rule is on
 // the main path.
 //
-// Scores are positive and bunch into a few binades, so in the first pass nearly every key lands in
-// the same bin: each wave therefore counts the keys that share the digit of its first candidate
-// with a reduction and issues one atomic for them; only the others go to the histogram one by one.
+// Scores are positive and bunch into a few binades, so in the first pass all keys land in a handful of
+// neighbouring bins: there each thread counts its keys in packed byte fields and the wave issues eight atomics.
+// In the later passes each wave counts the candidates that share the digit of its first candidate with a
+// reduction and issues one atomic for them; only the others go to the histogram one by one.
 //
 // Heads of up to 65536 keys (topk_reg_kernel) are read from HBM once into registers, thread t
 // owning the consecutive keys [t*KPT, (t+1)*KPT): every pass runs out of registers and the
@@ -28,6 +29,14 @@ namespace {
 constexpr int kTopkThreads = 1024;
 constexpr int kTopkWaves = kTopkThreads / 64;
 constexpr int kTopkLdsKeys = 36864;
+constexpr int kTopkTailCap = 2048;
+
+// Orders the LDS accesses of one wave's lanes among themselves (the hardware runs a wave's LDS instructions in
+// order; this keeps the compiler from moving them).
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
 
 struct TopkParams {
   const float* pooled;        // the scores selection runs on (the register variant can pool them itself)
@@ -92,31 +101,71 @@ __device__ __forceinline__ TopkHead topk_head(const TopkParams& p) {
   return hd;
 }
 
-__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
-#pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+// Scans and reductions over the 64 lanes of a wave with data-parallel-primitive moves (a register-to-register
+// move between lanes costs a few clocks; a shuffle goes through the LDS crossbar and takes over a hundred, and a
+// scan is six of them in a chain).  A wave is four rows of 16 lanes: shifts by 1, 2, 4, 8 scan inside the rows
+// (lanes without a source take the identity), then lane 15 of a row is handed to the whole next row (rows 1 and 3),
+// then lane 31 to rows 2 and 3.
+enum : int {
+  kDppRowShr1 = 0x111, kDppRowShr2 = 0x112, kDppRowShr4 = 0x114, kDppRowShr8 = 0x118,
+  kDppRowBcast15 = 0x142, kDppRowBcast31 = 0x143
+};
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_take(uint32_t identity, uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)identity, (int)v, CTRL, ROW_MASK, 0xf, false);
+}
+struct OpAdd {
+  static constexpr uint32_t identity = 0u;
+  __device__ __forceinline__ static uint32_t apply(uint32_t a, uint32_t b) { return a + b; }
+};
+struct OpMin {
+  static constexpr uint32_t identity = 0xFFFFFFFFu;
+  __device__ __forceinline__ static uint32_t apply(uint32_t a, uint32_t b) { return a < b ? a : b; }
+};
+struct OpMax {
+  static constexpr uint32_t identity = 0u;
+  __device__ __forceinline__ static uint32_t apply(uint32_t a, uint32_t b) { return a > b ? a : b; }
+};
+// inclusive scan in lane order: lane l gets op(v[0], ..., v[l])
+template <class Op>
+__device__ __forceinline__ uint32_t wave_scan(uint32_t v) {
+  v = Op::apply(v, dpp_take<kDppRowShr1, 0xf>(Op::identity, v));
+  v = Op::apply(v, dpp_take<kDppRowShr2, 0xf>(Op::identity, v));
+  v = Op::apply(v, dpp_take<kDppRowShr4, 0xf>(Op::identity, v));
+  v = Op::apply(v, dpp_take<kDppRowShr8, 0xf>(Op::identity, v));
+  v = Op::apply(v, dpp_take<kDppRowBcast15, 0xa>(Op::identity, v));
+  v = Op::apply(v, dpp_take<kDppRowBcast31, 0xc>(Op::identity, v));
   return v;
 }
+// the reduction over all lanes, in every lane
+template <class Op>
+__device__ __forceinline__ uint32_t wave_reduce(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_readlane((int)wave_scan<Op>(v), 63);
+}
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v) { return wave_reduce<OpAdd>(v); }
 
 // After a histogram pass: wave 0 finds the digit d of T, the one with greater(d) < need <= greater(d)
-// + hist[d], and publishes (d, need - greater(d)) in bcast.
+// + hist[d], and publishes (d, need - greater(d), hist[d]) in bcast.
 __device__ __forceinline__ void topk_pick_digit(const uint32_t* hist, uint32_t* bcast, int need, int lane) {
   // lane l owns digits 4l..4l+3; suffix sums over the lanes above, then inside the lane
   const uint32_t h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
   const uint32_t mine = h0 + h1 + h2 + h3;
-  uint32_t incl = mine;  // inclusive suffix sum over lanes >= l
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const uint32_t o = __shfl_down(incl, d, 64);
-    if (lane + d < 64) incl += o;
-  }
-  const uint32_t above = incl - mine;  // keys whose digit is > 4l+3
+  const uint32_t upto = wave_scan<OpAdd>(mine);  // keys whose digit is <= 4l+3
+  const uint32_t above = (uint32_t)__builtin_amdgcn_readlane((int)upto, 63) - upto;  // keys whose digit is > 4l+3
   const uint32_t g3 = above, g2 = g3 + h3, g1 = g2 + h2, g0 = g1 + h1;  // keys with a larger digit
   const uint32_t un = (uint32_t)need;
-  if (g3 < un && un <= g3 + h3) { bcast[0] = 4 * lane + 3; bcast[1] = un - g3; }
-  if (g2 < un && un <= g2 + h2) { bcast[0] = 4 * lane + 2; bcast[1] = un - g2; }
-  if (g1 < un && un <= g1 + h1) { bcast[0] = 4 * lane + 1; bcast[1] = un - g1; }
-  if (g0 < un && un <= g0 + h0) { bcast[0] = 4 * lane + 0; bcast[1] = un - g0; }
+  if (g3 < un && un <= g3 + h3) { bcast[0] = 4 * lane + 3; bcast[1] = un - g3; bcast[2] = h3; }
+  if (g2 < un && un <= g2 + h2) { bcast[0] = 4 * lane + 2; bcast[1] = un - g2; bcast[2] = h2; }
+  if (g1 < un && un <= g1 + h1) { bcast[0] = 4 * lane + 1; bcast[1] = un - g1; bcast[2] = h1; }
+  if (g0 < un && un <= g0 + h0) { bcast[0] = 4 * lane + 0; bcast[1] = un - g0; bcast[2] = h0; }
+}
+
+// Whether a register variant brings its head in through an LDS staging area of THREADS * (KPT + 4) words (launched
+// as dynamic LDS): the variant for 8K..32K keys, which has a compute unit to itself anyway.  The short-head variants
+// share a compute unit and would lose occupancy to the area; 64 keys per thread times 1024 threads do not fit.
+constexpr bool reg_variant_is_staged(int threads, int kpt) { return threads == 1024 && kpt == 32; }
+constexpr int reg_variant_stage_bytes(int threads, int kpt) {
+  return reg_variant_is_staged(threads, kpt) ? threads * (kpt + 4) * (int)sizeof(float) : 0;
 }
 
 // ---- heads that fit in registers.  R > 0: the input is the un-pooled score and the kernel applies
@@ -124,8 +173,12 @@ __device__ __forceinline__ void topk_pick_digit(const uint32_t* hist, uint32_t* 
 template <int THREADS, int KPT, int R>
 __global__ __launch_bounds__(THREADS) void topk_reg_kernel(TopkParams p) {
   constexpr int kWaves = THREADS / 64;
-  __shared__ uint32_t hist[256];
-  __shared__ uint32_t bcast[2];
+  static_assert(KPT <= 255, "the first pass counts a thread's keys in 8-bit fields");
+  constexpr bool kStaged = reg_variant_is_staged(THREADS, KPT);
+  __shared__ uint32_t hists[2][256];  // passes alternate: the next one's is cleared while wave 0 reads this one's
+  __shared__ uint32_t bcasts[5][3];   // one row per pass (no pass waits for the readers of the one before), one for the tail
+  __shared__ uint32_t tail[kTopkTailCap];  // low halves of the candidates left after two passes
+  __shared__ uint32_t tail_n;
   __shared__ uint32_t wave_gt[kWaves], wave_eq[kWaves];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const TopkHead hd = topk_head(p);
@@ -133,28 +186,78 @@ __global__ __launch_bounds__(THREADS) void topk_reg_kernel(TopkParams p) {
   const int L = hd.L;
 
   // thread t owns keys [t*KPT, t*KPT + KPT): registers i < nvalid hold a key.  (A layout with
-  // contiguous rows per wave loads no faster here and makes the compaction twice as long.)
+  // contiguous rows per wave makes the compaction twice as long.)
   const int j0 = tid * KPT;
   const int nvalid = L - j0 < 0 ? 0 : (L - j0 > KPT ? KPT : L - j0);
   float ext[KPT + 2 * R];  // scores j0-R .. j0+KPT+R-1; -inf outside the sequence
-  if (nvalid == KPT && (reinterpret_cast<uintptr_t>(hd.src + j0) & 15) == 0) {
+  if (kStaged) {
+    // The head comes in with coalesced 16-byte loads (a thread reading its own run straight from memory makes
+    // every load instruction touch 64 cache lines, and the halo loads as many again) and is dealt out to its
+    // owners through LDS.  Row t of the staging area is thread t's run; rows are KPT + 4 words apart, which keeps
+    // them 16-byte aligned and spreads consecutive rows over the banks.
+    extern __shared__ float stage[];
+    constexpr int kRow = KPT + 4;
+    static_assert(R <= 4, "the halo of a run is read as one 16-byte piece of each neighbouring row");
+    if ((reinterpret_cast<uintptr_t>(hd.src) & 15) == 0) {
+#pragma unroll
+      for (int it = 0; it < KPT / 4; ++it) {
+        const int g = (it * THREADS + tid) * 4;
+        if (g + 4 <= L) {
+          *reinterpret_cast<float4*>(&stage[(g / KPT) * kRow + (g % KPT)]) = *reinterpret_cast<const float4*>(hd.src + g);
+        } else {
+          for (int k = 0; k < 4 && g + k < L; ++k) stage[(g / KPT) * kRow + (g % KPT) + k] = hd.src[g + k];
+        }
+      }
+    } else {
+      for (int j = tid; j < L; j += THREADS) stage[(j / KPT) * kRow + (j % KPT)] = hd.src[j];
+    }
+    __syncthreads();
+    // (words of the area that no key was written to are never selected below)
 #pragma unroll
     for (int i = 0; i < KPT; i += 4) {
-      const float4 v = *reinterpret_cast<const float4*>(hd.src + j0 + i);
-      ext[R + i] = v.x;
-      ext[R + i + 1] = v.y;
-      ext[R + i + 2] = v.z;
-      ext[R + i + 3] = v.w;
+      const float4 v = *reinterpret_cast<const float4*>(&stage[tid * kRow + i]);
+      ext[R + i] = i < nvalid ? v.x : -INFINITY;
+      ext[R + i + 1] = i + 1 < nvalid ? v.y : -INFINITY;
+      ext[R + i + 2] = i + 2 < nvalid ? v.z : -INFINITY;
+      ext[R + i + 3] = i + 3 < nvalid ? v.w : -INFINITY;
+    }
+    if (R > 0) {
+      float left[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY}, right[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+      if (tid > 0) {
+        const float4 v = *reinterpret_cast<const float4*>(&stage[(tid - 1) * kRow + KPT - 4]);
+        left[0] = v.x, left[1] = v.y, left[2] = v.z, left[3] = v.w;
+      }
+      if (tid + 1 < THREADS) {
+        const float4 v = *reinterpret_cast<const float4*>(&stage[(tid + 1) * kRow]);
+        right[0] = v.x, right[1] = v.y, right[2] = v.z, right[3] = v.w;
+      }
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        const int jl = j0 - R + r, jr = j0 + KPT + r;
+        ext[r] = (jl >= 0 && jl < L) ? left[4 - R + r] : -INFINITY;
+        ext[R + KPT + r] = jr < L ? right[r] : -INFINITY;
+      }
     }
   } else {
+    if (nvalid == KPT && (reinterpret_cast<uintptr_t>(hd.src + j0) & 15) == 0) {
 #pragma unroll
-    for (int i = 0; i < KPT; ++i) ext[R + i] = i < nvalid ? hd.src[j0 + i] : -INFINITY;
-  }
+      for (int i = 0; i < KPT; i += 4) {
+        const float4 v = *reinterpret_cast<const float4*>(hd.src + j0 + i);
+        ext[R + i] = v.x;
+        ext[R + i + 1] = v.y;
+        ext[R + i + 2] = v.z;
+        ext[R + i + 3] = v.w;
+      }
+    } else {
 #pragma unroll
-  for (int r = 0; r < R; ++r) {
-    const int jl = j0 - R + r, jr = j0 + KPT + r;
-    ext[r] = (jl >= 0 && jl < L) ? hd.src[jl] : -INFINITY;
-    ext[R + KPT + r] = jr < L ? hd.src[jr] : -INFINITY;
+      for (int i = 0; i < KPT; ++i) ext[R + i] = i < nvalid ? hd.src[j0 + i] : -INFINITY;
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int jl = j0 - R + r, jr = j0 + KPT + r;
+      ext[r] = (jl >= 0 && jl < L) ? hd.src[jl] : -INFINITY;
+      ext[R + KPT + r] = jr < L ? hd.src[jr] : -INFINITY;
+    }
   }
   uint32_t key[KPT];
 #pragma unroll
@@ -163,62 +266,151 @@ __global__ __launch_bounds__(THREADS) void topk_reg_kernel(TopkParams p) {
 #pragma unroll
     for (int t = 1; t <= 2 * R; ++t) m = fmaxf(m, ext[i + t]);
     if (p.pooled_out != nullptr && i < nvalid) p.pooled_out[(hd.src - p.pooled) + j0 + i] = m;
-    key[i] = i < nvalid ? order_key(m) : 0u;
+    // registers past the end of the head hold 0, which no key is (a key is at least 1): everything below can then
+    // tell them by value, and no per-register validity mask has to stay alive through the kernel
+    const uint32_t k = order_key(m);
+    key[i] = i < nvalid ? (k > 1u ? k : 1u) : 0u;
   }
   if (hd.done) return;
 
   // ---- radix select: threshold T = the keep-th largest key, need = how many keys == T to take
   uint32_t prefix = 0, mask = 0;
   int need = hd.keep;
-  for (int shift = 24; shift >= 0; shift -= 8) {
-    for (int e = tid; e < 256; e += THREADS) hist[e] = 0;
+  for (int e = tid; e < 256; e += THREADS) hists[0][e] = 0;
+  if (tid == 0) tail_n = 0;
+  __syncthreads();
+  // What ends a pass: wave 0 finds the digit of T among the 256 counts while the others clear the next pass's
+  // histogram (its last reader was wave 0, two barriers ago); returns how many candidates remain.
+  auto settle = [&](int pass, int shift) -> uint32_t {
     __syncthreads();
-    // the digit most keys of this wave are likely to share: that of its first candidate
+    if (wave == 0) topk_pick_digit(hists[pass & 1], bcasts[pass], need, lane);
+    else
+      for (int e = tid - 64; e < 256; e += THREADS - 64) hists[(pass + 1) & 1][e] = 0;
+    __syncthreads();
+    prefix |= bcasts[pass][0] << shift;
+    mask |= 255u << shift;
+    need = (int)bcasts[pass][1];
+    return bcasts[pass][2];
+  };
+
+  {
+    // First pass: every key is a candidate and its digit is the sign and seven exponent bits.  Scores are sums of
+    // probabilities: a wave's 64 * KPT digits fall into a handful of neighbouring bins, where one LDS atomic per
+    // key would serialise on a few addresses.  If the wave's digits span at most 8 bins, each thread counts its
+    // keys in eight 8-bit fields (KPT <= 255), the wave adds the fields up and eight lanes issue one atomic each.
+    // (A register without a key holds 0: key - 1 wraps to the largest value and never is the minimum; for a key
+    // whose low 24 bits are all 0 the minimum comes out one bin low, which only widens the span by one.)
+    uint32_t* hist = hists[0];
+    uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) {
+      kmin = key[i] - 1u < kmin ? key[i] - 1u : kmin;
+      kmax = key[i] > kmax ? key[i] : kmax;
+    }
+    const uint32_t dmin = wave_reduce<OpMin>(kmin) >> 24, dmax = wave_reduce<OpMax>(kmax) >> 24;
+    if (dmax >= dmin && dmax - dmin < 8u) {  // (uniform over the wave; dmax < dmin: the wave holds no key)
+      // the registers without a key are counted too, all in the field that digit 0 wraps to, and taken out after
+      uint64_t fields = 0;
+#pragma unroll
+      for (int i = 0; i < KPT; ++i) fields += 1ull << ((((key[i] >> 24) - dmin) * 8u) & 63u);
+      fields -= (uint64_t)(KPT - nvalid) << (((0u - dmin) * 8u) & 63u);
+      // two bins per 32-bit word, 16 bits each: a wave's count is at most 64 * KPT < 65536
+      uint32_t pair[4];
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        const uint32_t lo = (uint32_t)(fields >> (16 * b)) & 255u, hi = (uint32_t)(fields >> (16 * b + 8)) & 255u;
+        pair[b] = wave_sum(lo | (hi << 16));
+      }
+      if (lane < 8) {
+        const uint32_t w = lane < 2 ? pair[0] : (lane < 4 ? pair[1] : (lane < 6 ? pair[2] : pair[3]));
+        const uint32_t c = (lane & 1) ? (w >> 16) : (w & 0xFFFFu);
+        if (c != 0) atomicAdd(&hist[dmin + lane], c);
+      }
+    } else if (dmax >= dmin) {
+#pragma unroll
+      for (int i = 0; i < KPT; ++i)
+        if (key[i] != 0u) atomicAdd(&hist[key[i] >> 24], 1u);
+    }
+    settle(0, 24);
+  }
+
+  // The other passes.  (From here on the registers without a key are not told apart: they hold 0, can only be
+  // candidates while the prefix is 0, are then the least of all candidates, and there are always at least `need` real
+  // ones above them.)
+  for (int shift = 16; shift >= 0; shift -= 8) {
+    const int pass = (24 - shift) >> 3;
+    uint32_t* hist = hists[pass & 1];
+    // the digit most candidates of this wave are likely to share: that of its first candidate
     int first = -1;
 #pragma unroll
     for (int i = KPT - 1; i >= 0; --i)
-      if (i < nvalid && (key[i] & mask) == prefix) first = (int)((key[i] >> shift) & 255u);
+      if ((key[i] & mask) == prefix) first = (int)((key[i] >> shift) & 255u);
     const uint64_t have = __ballot(first >= 0);
     if (have != 0) {
-      const uint32_t d0 = (uint32_t)__shfl(first, __ffsll((long long)have) - 1, 64);
+      const uint32_t d0 = (uint32_t)__builtin_amdgcn_readlane(first, __ffsll((long long)have) - 1);
       uint32_t same = 0;
 #pragma unroll
       for (int i = 0; i < KPT; ++i) {
-        if (i < nvalid && (key[i] & mask) == prefix) {
-          const uint32_t d = (key[i] >> shift) & 255u;
-          if (d == d0) ++same;
-          else atomicAdd(&hist[d], 1u);
+        const bool cand = (key[i] & mask) == prefix;
+        const uint32_t d = (key[i] >> shift) & 255u;
+        same += cand && d == d0 ? 1u : 0u;
+        if (__ballot(cand && d != d0) != 0) {  // (skipped by the whole wave when nobody has one)
+          if (cand && d != d0) atomicAdd(&hist[d], 1u);
         }
       }
       same = wave_sum(same);
       if (lane == 0 && same != 0) atomicAdd(&hist[d0], same);
     }
-    __syncthreads();
-    if (wave == 0) topk_pick_digit(hist, bcast, need, lane);
-    __syncthreads();
-    prefix |= bcast[0] << shift;
-    mask |= 255u << shift;
-    need = (int)bcast[1];
-    __syncthreads();
+    const uint32_t left = settle(pass, shift);  // candidates that remain
+    if (shift == 16 && left <= (uint32_t)kTopkTailCap) {
+      // Few candidates remain (typically a few dozen): instead of two more rounds of the whole workgroup, with
+      // their barriers, their low halves go to a list and one wave finishes the selection on its own.
+#pragma unroll
+      for (int i = 0; i < KPT; ++i) {
+        const bool cand = (key[i] & mask) == prefix;
+        if (__ballot(cand) != 0) {  // rare: most waves hold no candidate at all
+          if (cand) tail[atomicAdd(&tail_n, 1u)] = key[i] & 0xFFFFu;
+        }
+      }
+      __syncthreads();
+      if (wave == 0) {
+        uint32_t pre = 0, msk = 0;
+        uint32_t* h = hists[0];
+        uint32_t* bc = bcasts[4];
+        for (int sh = 8; sh >= 0; sh -= 8) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) h[4 * lane + e] = 0;
+          wave_lds_sync();
+          for (uint32_t e = lane; e < left; e += 64) {
+            const uint32_t v = tail[e];
+            if ((v & msk) == pre) atomicAdd(&h[(v >> sh) & 255u], 1u);
+          }
+          wave_lds_sync();
+          topk_pick_digit(h, bc, need, lane);
+          wave_lds_sync();
+          pre |= bc[0] << sh;
+          msk |= 255u << sh;
+          need = (int)bc[1];
+          wave_lds_sync();
+        }
+        if (lane == 0) bc[0] = pre;  // bc[1] holds the final `need`
+      }
+      __syncthreads();
+      prefix |= bcasts[4][0];
+      need = (int)bcasts[4][1];
+      break;
+    }
   }
   const uint32_t T = prefix;
 
   // ---- ordered compaction: one exclusive scan of the per-thread (greater, equal) counts
   uint32_t my_gt = 0, my_eq = 0;
 #pragma unroll
-  for (int i = 0; i < KPT; ++i) {
-    my_gt += (i < nvalid && key[i] > T) ? 1u : 0u;
-    my_eq += (i < nvalid && key[i] == T) ? 1u : 0u;
+  for (int i = 0; i < KPT; ++i) {  // (T is a key, so T >= 1 and registers without a key count as neither)
+    my_gt += key[i] > T ? 1u : 0u;
+    my_eq += key[i] == T ? 1u : 0u;
   }
-  uint32_t inc_gt = my_gt, inc_eq = my_eq;  // inclusive scans inside the wave
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const uint32_t a = __shfl_up(inc_gt, d, 64), c = __shfl_up(inc_eq, d, 64);
-    if (lane >= d) {
-      inc_gt += a;
-      inc_eq += c;
-    }
-  }
+  const uint32_t inc_gt = wave_scan<OpAdd>(my_gt), inc_eq = wave_scan<OpAdd>(my_eq);  // inclusive, inside the wave
   if (lane == 63) {
     wave_gt[wave] = inc_gt;
     wave_eq[wave] = inc_eq;
@@ -236,14 +428,13 @@ __global__ __launch_bounds__(THREADS) void topk_reg_kernel(TopkParams p) {
   uint32_t pos = pre_gt + (pre_eq < un ? pre_eq : un);
 #pragma unroll
   for (int i = 0; i < KPT; ++i) {
-    if (i < nvalid) {
-      if (key[i] > T) {
-        hd.out[pos++] = j0 + i;
-      } else if (key[i] == T) {
-        if (pre_eq < un) hd.out[pos++] = j0 + i;
-        ++pre_eq;
-      }
+    const bool eq = key[i] == T;
+    const bool take = key[i] > T || (eq && pre_eq < un);
+    if (__ballot(take) != 0) {  // survivors are few: most of a wave's registers hold none
+      if (take) hd.out[pos] = j0 + i;
     }
+    pos += take ? 1u : 0u;
+    pre_eq += eq ? 1u : 0u;
   }
 }
 
@@ -252,7 +443,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_stream_kernel(TopkParams p)
   extern __shared__ uint32_t smem[];
   uint32_t* hist = smem;             // [256]
   uint32_t* wave_tot = smem + 256;   // [16]
-  uint32_t* bcast = smem + 256 + 16; // [2]: digit, need
+  uint32_t* bcast = smem + 256 + 16; // [3]: digit, need, population of the digit
   uint32_t* keys = smem + 320;       // [kTopkLdsKeys] staged order keys (if they fit)
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -304,7 +495,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_stream_kernel(TopkParams p)
         const uint32_t d = (k[u] >> shift) & 255u;
         const uint64_t have = __ballot(cand);
         if (have != 0) {
-          const uint32_t d0 = (uint32_t)__shfl((int)d, __ffsll((long long)have) - 1, 64);
+          const uint32_t d0 = (uint32_t)__builtin_amdgcn_readlane((int)d, __ffsll((long long)have) - 1);
           const uint64_t same = __ballot(cand && d == d0);
           if (cand && d != d0) atomicAdd(&hist[d], 1u);
           if (lane == 0) atomicAdd(&hist[d0], (uint32_t)__popcll(same));
@@ -334,12 +525,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_stream_kernel(TopkParams p)
     for (int u = 0; u < 4; ++u) {
       if (j + u < L) my += (k[u] > T ? 0x10000u : 0u) + (k[u] == T ? 1u : 0u);
     }
-    uint32_t inc = my;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-      const uint32_t o = __shfl_up(inc, d, 64);
-      if (lane >= d) inc += o;
-    }
+    const uint32_t inc = wave_scan<OpAdd>(my);
     if (lane == 63) wave_tot[wave] = inc;
     __syncthreads();
     uint32_t pre = inc - my, blk = 0;  // packed counts before this thread inside the tile / of the whole tile
@@ -393,11 +579,16 @@ RegVariant reg_variant_for(int64_t len) {
 }
 
 template <int R>
-void launch_reg(RegVariant v, dim3 grid, hipStream_t st, const TopkParams& p) {
+int launch_reg(RegVariant v, dim3 grid, hipStream_t st, const TopkParams& p) {
   if (v.threads == 256 && v.kpt == 32) hipLaunchKernelGGL((topk_reg_kernel<256, 32, R>), grid, dim3(256), 0, st, p);
   else if (v.threads == 256) hipLaunchKernelGGL((topk_reg_kernel<256, 64, R>), grid, dim3(256), 0, st, p);
-  else if (v.kpt == 32) hipLaunchKernelGGL((topk_reg_kernel<1024, 32, R>), grid, dim3(1024), 0, st, p);
-  else hipLaunchKernelGGL((topk_reg_kernel<1024, 64, R>), grid, dim3(1024), 0, st, p);
+  else if (v.kpt == 32) {
+    constexpr int kBytes = reg_variant_stage_bytes(1024, 32);
+    const int rc = set_max_dynamic_lds(reinterpret_cast<const void*>(topk_reg_kernel<1024, 32, R>), kBytes);
+    if (rc != DAPQ_OK) return rc;
+    hipLaunchKernelGGL((topk_reg_kernel<1024, 32, R>), grid, dim3(1024), kBytes, st, p);
+  } else hipLaunchKernelGGL((topk_reg_kernel<1024, 64, R>), grid, dim3(1024), 0, st, p);
+  return DAPQ_OK;
 }
 
 int topk_common_checks(const dapq_shape* shape, const float* in, int32_t budget, const int32_t* idx, const int32_t* count) {
@@ -445,7 +636,7 @@ extern "C" DAPQ_API int dapq_topk(const dapq_shape* shape, const float* pooled, 
   p.min_len = 0;
   p.max_len = (int32_t)reg_max;
   if (shape->cu_seqlens != nullptr || mean <= reg_max) {  // (a dense batch of longer heads has nothing for it)
-    launch_reg<0>(variant, grid, st, p);
+    if ((rc = launch_reg<0>(variant, grid, st, p)) != DAPQ_OK) return rc;
     DAPQ_HIP_LAUNCH_CHECK("topk_reg_kernel");
   }
   if (longest > reg_max) {
@@ -498,12 +689,13 @@ extern "C" DAPQ_API int dapq_pool_topk(const dapq_shape* shape, const float* sco
   const dim3 grid((unsigned)shape->n_kv_heads, (unsigned)shape->batch, (unsigned)shape->n_layers);
   hipStream_t st = static_cast<hipStream_t>(stream);
   switch (width / 2) {
-    case 0: launch_reg<0>(variant, grid, st, p); break;
-    case 1: launch_reg<1>(variant, grid, st, p); break;
-    case 2: launch_reg<2>(variant, grid, st, p); break;
-    case 3: launch_reg<3>(variant, grid, st, p); break;
-    default: launch_reg<4>(variant, grid, st, p); break;
+    case 0: rc = launch_reg<0>(variant, grid, st, p); break;
+    case 1: rc = launch_reg<1>(variant, grid, st, p); break;
+    case 2: rc = launch_reg<2>(variant, grid, st, p); break;
+    case 3: rc = launch_reg<3>(variant, grid, st, p); break;
+    default: rc = launch_reg<4>(variant, grid, st, p); break;
   }
+  if (rc != DAPQ_OK) return rc;
   DAPQ_HIP_LAUNCH_CHECK("topk_reg_kernel");
   return DAPQ_OK;
 }
