@@ -195,12 +195,13 @@ def test_score_plan_covers_every_shape(lib):
     def ws(**kw):
         return D.workspace_bytes(good_shape(**kw))
     lse = 2 * 1 * 32 * 64 * 4
-    # 2 layers x 8 KV heads x 4096 keys, 256 rows: 128-key chunks -> 32 chunks per head, (ref, sum) per row and chunk
-    assert ws() == 256 + 2 * 8 * 32 * 256 * 8 + lse
+    # 2 layers x 8 KV heads x 4096 keys, 256 rows: 128-key chunks -> 32 chunks per head, (ref, sum) per row and chunk;
+    # in front of them the chunk prefix of the sequences and the ticket counter of a ragged batch, 256 bytes each
+    assert ws() == 256 + 256 + 2 * 8 * 32 * 256 * 8 + lse
     # 512 rows per KV head: two row groups; one extra plane of column sums
     big = dict(n_pseudo=128, q_strides=(32 * 128 * 128, 32 * 128 * 128, 128 * 128, 128))
     lse2 = 2 * 1 * 32 * 128 * 4
-    assert ws(**big) == 256 + 2 * 8 * 32 * 512 * 8 + lse2 + 2 * 8 * 4096 * 4
+    assert ws(**big) == 256 + 256 + 2 * 8 * 32 * 512 * 8 + lse2 + 2 * 8 * 4096 * 4
     # very many rows are still planned (row groups on the grid), absurdly many are refused
     assert ws(n_pseudo=4096, q_strides=(32 * 4096 * 128, 32 * 4096 * 128, 4096 * 128, 128)) > 0
     assert ws(n_pseudo=1 << 19) == 0 and b"rows per KV head" in lib.dapq_last_error()

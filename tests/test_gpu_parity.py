@@ -267,6 +267,20 @@ def test_topk_all_equal_and_tiny_values(H):
     _topk_case(H, lens, 100, P)
 
 
+@pytest.mark.parametrize("L", [3000, 12000, 30000, 60000])
+def test_topk_both_signs_over_many_binades(H, L):
+    """Scores of both signs from 1e-30 to 1e30, with infinities: the first radix digit (sign and exponent) spreads
+    over the whole histogram, which takes the selection off its packed first-pass counting, in every kernel variant."""
+    announce(f"topk both signs, wide range, L={L}")
+    r = np.random.default_rng(L + 1)
+    P = (r.standard_normal((1, 2, L)) * 10.0 ** r.uniform(-30, 30, (1, 2, L))).astype(np.float32)
+    P[0, 0, 17] = np.inf
+    P[0, 0, 1000] = -np.inf
+    P[0, 1, ::7] = P[0, 1, 3]                                   # ties
+    for budget in (5, 983, L - 1):
+        _topk_case(H, [L], budget, P, dense=True)
+
+
 def test_topk_long_sequence_not_staged_in_lds(H):
     announce("topk L=70000 (streams from memory)")
     r = np.random.default_rng(7)
@@ -275,8 +289,8 @@ def test_topk_long_sequence_not_staged_in_lds(H):
     _topk_case(H, [70000], 2048, P, Hkv=1)
 
 
-@pytest.mark.parametrize("L,batch", [(8192, 1), (8193, 3), (16384, 2), (16385, 1), (32768, 1), (32769, 2), (50001, 1),
-                                     (65536, 1), (65537, 1)])
+@pytest.mark.parametrize("L,batch", [(8192, 1), (8193, 3), (16384, 2), (16385, 1), (20001, 2), (32767, 3), (32768, 1),
+                                     (32769, 2), (50001, 1), (65536, 1), (65537, 1)])
 def test_topk_dense_lengths_around_the_variant_limits(H, L, batch):
     """Dense batches at the lengths where the kernel variant changes (8, 32, 64 keys per thread,
     then streaming), with sequence starts that are not 16-byte aligned, heavy ties and a plateau
@@ -291,7 +305,7 @@ def test_topk_dense_lengths_around_the_variant_limits(H, L, batch):
 
 
 @pytest.mark.parametrize("width", [1, 3, 5, 7, 9, 11])
-@pytest.mark.parametrize("lens,dense", [([5000], True), ([8193] * 2, True), ([40000], True), ([70000], True),
+@pytest.mark.parametrize("lens,dense", [([5000], True), ([8193] * 2, True), ([20001] * 2, True), ([40000], True), ([70000], True),
                                         ([1, 6, 100, 1025, 0, 4097], False)])
 def test_pool_topk_one_call_equals_the_two(H, width, lens, dense):
     """dapq_pool_topk against the oracle's pool followed by its top-K, for windows the selection kernel
