@@ -30,6 +30,8 @@ constexpr int kTopkThreads = 1024;
 constexpr int kTopkWaves = kTopkThreads / 64;
 constexpr int kTopkLdsKeys = 36864;
 constexpr int kTopkTailCap = 2048;
+constexpr int kStreamTiles = 4;                            // tiles of 4096 keys the streaming kernel has in flight
+constexpr int kStreamLdsHead = 260 + kStreamTiles * 16 + 60;  // words of LDS in front of its staged keys (16-byte aligned)
 
 // Orders the LDS accesses of one wave's lanes among themselves (the hardware runs a wave's LDS instructions in
 // order; this keeps the compiler from moving them).
@@ -442,9 +444,9 @@ __global__ __launch_bounds__(THREADS) void topk_reg_kernel(TopkParams p) {
 __global__ __launch_bounds__(kTopkThreads) void topk_stream_kernel(TopkParams p) {
   extern __shared__ uint32_t smem[];
   uint32_t* hist = smem;             // [256]
-  uint32_t* wave_tot = smem + 256;   // [16]
-  uint32_t* bcast = smem + 256 + 16; // [3]: digit, need, population of the digit
-  uint32_t* keys = smem + 320;       // [kTopkLdsKeys] staged order keys (if they fit)
+  uint32_t* bcast = smem + 256;      // [3]: digit, need, population of the digit
+  uint32_t* wave_tot = smem + 260;   // [kStreamTiles][16]
+  uint32_t* keys = smem + kStreamLdsHead;  // [kTopkLdsKeys] staged order keys (if they fit)
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const TopkHead hd = topk_head(p);
@@ -478,6 +480,8 @@ __global__ __launch_bounds__(kTopkThreads) void topk_stream_kernel(TopkParams p)
     }
   };
   constexpr int kTile = 4 * kTopkThreads;
+  // kStreamTiles tiles per trip, all their loads issued before the first key is looked at: with one workgroup per
+  // head a pass is a chain of load latencies, and this is how many of them overlap
 
   // ---- radix select: threshold T = the keep-th largest key, need = how many keys == T to take
   uint32_t prefix = 0, mask = 0;
@@ -485,20 +489,24 @@ __global__ __launch_bounds__(kTopkThreads) void topk_stream_kernel(TopkParams p)
   for (int shift = 24; shift >= 0; shift -= 8) {
     if (tid < 256) hist[tid] = 0;
     __syncthreads();
-    for (int jb = 0; jb < L; jb += kTile) {  // the trip count is the same for every thread
-      const int j = jb + 4 * tid;
-      uint32_t k[4];
-      keys_at(j, k);
+    for (int jb = 0; jb < L; jb += kStreamTiles * kTile) {  // the trip count is the same for every thread
+      uint32_t k[kStreamTiles][4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const bool cand = j + u < L && (k[u] & mask) == prefix;
-        const uint32_t d = (k[u] >> shift) & 255u;
-        const uint64_t have = __ballot(cand);
-        if (have != 0) {
-          const uint32_t d0 = (uint32_t)__builtin_amdgcn_readlane((int)d, __ffsll((long long)have) - 1);
-          const uint64_t same = __ballot(cand && d == d0);
-          if (cand && d != d0) atomicAdd(&hist[d], 1u);
-          if (lane == 0) atomicAdd(&hist[d0], (uint32_t)__popcll(same));
+      for (int t = 0; t < kStreamTiles; ++t) keys_at(jb + t * kTile + 4 * tid, k[t]);
+#pragma unroll
+      for (int t = 0; t < kStreamTiles; ++t) {
+        const int j = jb + t * kTile + 4 * tid;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const bool cand = j + u < L && (k[t][u] & mask) == prefix;
+          const uint32_t d = (k[t][u] >> shift) & 255u;
+          const uint64_t have = __ballot(cand);
+          if (have != 0) {
+            const uint32_t d0 = (uint32_t)__builtin_amdgcn_readlane((int)d, __ffsll((long long)have) - 1);
+            const uint64_t same = __ballot(cand && d == d0);
+            if (cand && d != d0) atomicAdd(&hist[d], 1u);
+            if (lane == 0) atomicAdd(&hist[d0], (uint32_t)__popcll(same));
+          }
         }
       }
     }
@@ -512,46 +520,55 @@ __global__ __launch_bounds__(kTopkThreads) void topk_stream_kernel(TopkParams p)
   }
   const uint32_t T = prefix;
 
-  // ---- ordered compaction, one tile of 4096 keys at a time: per-thread counts of (greater, equal), an inclusive
-  // scan inside the wave, wave totals through LDS, then every thread writes its survivors in key order
+  // ---- ordered compaction, kStreamTiles tiles of 4096 keys at a time: per-thread counts of (greater, equal) in
+  // each tile, an inclusive scan inside the wave, wave totals through LDS, then every thread writes its survivors
+  // in key order (all keys of a tile come before those of the next)
   uint32_t base_gt = 0, base_eq = 0;  // keys > T / == T before the current tile (same in all threads)
   const uint32_t un = (uint32_t)need;
-  for (int jb = 0; jb < L; jb += kTile) {
-    const int j = jb + 4 * tid;
-    uint32_t k[4];
-    keys_at(j, k);
-    uint32_t my = 0;  // (greater << 16) | equal over this thread's four keys
+  for (int jb = 0; jb < L; jb += kStreamTiles * kTile) {
+    uint32_t k[kStreamTiles][4], my[kStreamTiles], inc[kStreamTiles];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      if (j + u < L) my += (k[u] > T ? 0x10000u : 0u) + (k[u] == T ? 1u : 0u);
-    }
-    const uint32_t inc = wave_scan<OpAdd>(my);
-    if (lane == 63) wave_tot[wave] = inc;
-    __syncthreads();
-    uint32_t pre = inc - my, blk = 0;  // packed counts before this thread inside the tile / of the whole tile
+    for (int t = 0; t < kStreamTiles; ++t) keys_at(jb + t * kTile + 4 * tid, k[t]);
 #pragma unroll
-    for (int w = 0; w < kTopkWaves; ++w) {
-      const uint32_t t = wave_tot[w];
-      if (w < wave) pre += t;
-      blk += t;
-    }
-    uint32_t pre_gt = base_gt + (pre >> 16), pre_eq = base_eq + (pre & 0xFFFFu);
-    if (my != 0) {
-      uint32_t pos = pre_gt + (pre_eq < un ? pre_eq : un);
+    for (int t = 0; t < kStreamTiles; ++t) {
+      const int j = jb + t * kTile + 4 * tid;
+      my[t] = 0;  // (greater << 16) | equal over this thread's four keys of the tile
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        if (j + u < L) {
-          if (k[u] > T) {
-            out[pos++] = j + u;
-          } else if (k[u] == T) {
-            if (pre_eq < un) out[pos++] = j + u;
-            ++pre_eq;
+        if (j + u < L) my[t] += (k[t][u] > T ? 0x10000u : 0u) + (k[t][u] == T ? 1u : 0u);
+      }
+      inc[t] = wave_scan<OpAdd>(my[t]);
+      if (lane == 63) wave_tot[t * kTopkWaves + wave] = inc[t];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < kStreamTiles; ++t) {
+      const int j = jb + t * kTile + 4 * tid;
+      uint32_t pre = inc[t] - my[t], blk = 0;  // packed counts before this thread inside the tile / of the whole tile
+#pragma unroll
+      for (int w = 0; w < kTopkWaves; ++w) {
+        const uint32_t tot = wave_tot[t * kTopkWaves + w];
+        if (w < wave) pre += tot;
+        blk += tot;
+      }
+      uint32_t pre_gt = base_gt + (pre >> 16), pre_eq = base_eq + (pre & 0xFFFFu);
+      if (my[t] != 0) {
+        uint32_t pos = pre_gt + (pre_eq < un ? pre_eq : un);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (j + u < L) {
+            if (k[t][u] > T) {
+              out[pos++] = j + u;
+            } else if (k[t][u] == T) {
+              if (pre_eq < un) out[pos++] = j + u;
+              ++pre_eq;
+            }
           }
         }
       }
+      base_gt += blk >> 16;
+      base_eq += blk & 0xFFFFu;
     }
-    base_gt += blk >> 16;
-    base_eq += blk & 0xFFFFu;
     __syncthreads();
   }
 }
@@ -644,10 +661,10 @@ extern "C" DAPQ_API int dapq_topk(const dapq_shape* shape, const float* pooled, 
     p.max_len = INT32_MAX;
     // heads of up to kTopkLdsKeys keys are staged in LDS; if none of this launch can be that short the staging
     // area is left out
-    const int lds_bytes = (320 + (p.min_len <= kTopkLdsKeys ? kTopkLdsKeys : 0)) * (int)sizeof(uint32_t);
+    const int lds_bytes = (kStreamLdsHead + (p.min_len <= kTopkLdsKeys ? kTopkLdsKeys : 0)) * (int)sizeof(uint32_t);
     // the limit is raised once, to the size with the staging area
     const int rc_lds = set_max_dynamic_lds(reinterpret_cast<const void*>(topk_stream_kernel),
-                                           (320 + kTopkLdsKeys) * (int)sizeof(uint32_t));
+                                           (kStreamLdsHead + kTopkLdsKeys) * (int)sizeof(uint32_t));
     if (rc_lds != DAPQ_OK) return rc_lds;
     hipLaunchKernelGGL(topk_stream_kernel, grid, dim3(kTopkThreads), lds_bytes, st, p);
     DAPQ_HIP_LAUNCH_CHECK("topk_stream_kernel");
