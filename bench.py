@@ -190,9 +190,12 @@ class Context:
         self.ws = torch.empty(D.workspace_bytes(self.shape), dtype=torch.uint8, device=dev)
         self.lse2 = torch.empty((nl, B, Hq, N), dtype=torch.float32, device=dev)
         self.S = torch.empty((nl, Hkv, tokens), dtype=torch.float32, device=dev)
-        # dapq_pool_topk is one kernel for windows up to 9 and heads up to 65536 keys; else it needs P as scratch
+        # dapq_pool_topk pools inside the selection kernels for windows up to 9: heads up to 65536 keys in one kernel,
+        # longer ones in pieces through a workspace of candidate lists; else it needs P as scratch
         longest = max(lens) if w.ragged is None else tokens
-        self.fused_select = w.pool_width <= 9 and longest <= 65536
+        n_topk_ws = D.topk_workspace_bytes(self.shape, w.budget)
+        self.topk_ws = torch.empty(n_topk_ws, dtype=torch.uint8, device=dev) if n_topk_ws else None
+        self.fused_select = w.pool_width <= 9 and (longest <= 65536 or self.topk_ws is not None)
         self.P = torch.empty_like(self.S) if (keep_pooled or not self.fused_select) else None
         self.idx = torch.zeros((nl, B, Hkv, w.budget), dtype=torch.int32, device=dev)
         self.count = torch.zeros((nl, B, Hkv), dtype=torch.int32, device=dev)
@@ -218,7 +221,7 @@ class Context:
         mark(2)
         D.dapq_score_accumulate(self.shape, self.q, self.k, self.lse2, self.S, self.ws, stream)
         mark(3)
-        D.dapq_pool_topk(self.shape, self.S, w.pool_width, w.budget, None, self.idx, self.count, self.P, stream)
+        D.dapq_pool_topk(self.shape, self.S, w.pool_width, w.budget, None, self.idx, self.count, self.P, stream, self.topk_ws)
         mark(4)
         D.dapq_gather(self.shape, self.k, self.v, self.idx, self.count, w.budget, self.k_out, self.v_out, stream)
         mark(5)

@@ -203,20 +203,32 @@ int dapq_pool(const dapq_shape* shape, const float* scores, float* pooled, int32
  *   budget           slots per head in idx (>= 1)
  *   budget_per_seq   optional device int32 [batch]: budget of each sequence (clamped to [0, budget]); NULL = budget
  *   idx, count       out; idx slots past count are left untouched
- *   workspace, workspace_bytes   not used: selection keeps its state in registers and LDS; pass NULL and 0 (the
- *                    arguments are part of the call's published form and are ignored, whatever they hold) */
+ *   workspace, workspace_bytes   optional device scratch of dapq_topk_workspace_bytes() bytes (256-byte aligned).
+ *                    Heads that fit in the registers of a workgroup (up to 65536 keys; fewer in a ragged batch whose
+ *                    mean length is short) never use it.  Longer heads are selected in pieces of 32768 keys whose
+ *                    survivors go to candidate lists in the workspace and are then selected among; without the
+ *                    workspace (NULL or too small) one workgroup streams such a head from memory five times, which
+ *                    gives the same result several times slower.  Contents need not be initialised and mean nothing
+ *                    after the call; calls that share a workspace must not overlap. */
 int dapq_topk(const dapq_shape* shape, const float* pooled, int32_t budget, const int32_t* budget_per_seq,
               int32_t* idx, int32_t* count, void* workspace, size_t workspace_bytes, void* stream);
 
-/* dapq_pool followed by dapq_topk as one call.  When every head has at most 65536 keys and width <= 9
- * this is a single kernel: each thread pools its run of scores in registers (window clipped at the
- * sequence ends) and the pooled scores never travel through HBM; `pooled` may then be NULL, and if it
- * is not NULL it receives the pooled scores as dapq_pool would write them.  Otherwise the two kernels
+/* Bytes of the optional workspace of dapq_topk / dapq_pool_topk for this shape and budget: 0 if no head can be long
+ * enough to go in pieces (or the shape is invalid), else 2 x 4 bytes per candidate slot (heads x pieces x budget)
+ * plus a count per piece.  Host arithmetic only. */
+size_t dapq_topk_workspace_bytes(const dapq_shape* shape, int32_t budget);
+
+/* dapq_pool followed by dapq_topk as one call.  For width <= 9 the selection kernels pool on the way in (each thread
+ * pools its run of scores in registers, window clipped at the sequence ends) and the pooled scores never travel
+ * through HBM: always when every head has at most 65536 keys, and for longer heads when the workspace of
+ * dapq_topk_workspace_bytes() is passed (their pieces pool across the piece boundaries).  `pooled` may then be NULL,
+ * and if it is not NULL it receives the pooled scores as dapq_pool would write them.  Otherwise the two kernels
  * run one after the other and `pooled` (fp32 [n_layers][n_kv_heads][total_tokens], not aliasing
  * scores) is required as the intermediate: DAPQ_ERR_UNSUPPORTED if it is NULL.  Results are identical
- * to the two separate calls in every case. */
+ * to the two separate calls in every case.  workspace, workspace_bytes: as for dapq_topk (may be NULL, 0). */
 int dapq_pool_topk(const dapq_shape* shape, const float* scores, int32_t width, int32_t budget,
-                   const int32_t* budget_per_seq, int32_t* idx, int32_t* count, float* pooled, void* stream);
+                   const int32_t* budget_per_seq, int32_t* idx, int32_t* count, float* pooled, void* workspace,
+                   size_t workspace_bytes, void* stream);
 
 /* Sec. 4.2 — cache pruning: copies the retained K and V rows, bit for bit, into the compact cache;
  * nothing of the pseudo segment is kept.  Rows past count are left untouched.

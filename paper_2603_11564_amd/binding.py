@@ -17,7 +17,7 @@ _lib = None
 
 EXPORTS = (
     "dapq_workspace_bytes", "dapq_last_error", "dapq_rope_apply", "dapq_pseudo_tokens", "dapq_pseudo_queries", "dapq_pseudo_queries_workspace_bytes", "dapq_score", "dapq_score_stats",
-    "dapq_score_accumulate", "dapq_score_stats_extend", "dapq_pool", "dapq_topk", "dapq_pool_topk", "dapq_gather", "dapq_recall", "dapq_decode_attention",
+    "dapq_score_accumulate", "dapq_score_stats_extend", "dapq_pool", "dapq_topk", "dapq_pool_topk", "dapq_topk_workspace_bytes", "dapq_gather", "dapq_recall", "dapq_decode_attention",
     "dapq_score_static", "dapq_score_static_capacity",
 )
 
@@ -84,7 +84,8 @@ def load_library():
     lib.dapq_score_stats_extend.argtypes = [sp, vp, vp, i64, i64, i64, i64, vp, vp]
     lib.dapq_pool.argtypes = [sp, vp, vp, i32, vp]
     lib.dapq_topk.argtypes = [sp, vp, i32, vp, vp, vp, vp, sz, vp]
-    lib.dapq_pool_topk.argtypes = [sp, vp, i32, i32, vp, vp, vp, vp, vp]
+    lib.dapq_pool_topk.argtypes = [sp, vp, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.dapq_topk_workspace_bytes.argtypes = [sp, i32]
     lib.dapq_gather.argtypes = [sp, vp, vp, vp, vp, i32, vp, vp, vp]
     lib.dapq_recall.argtypes = [sp, vp, vp, i32, vp, vp, i32, vp, vp, vp]
     lib.dapq_decode_attention.argtypes = [sp, vp, vp, vp, vp, i32, vp, vp]
@@ -94,6 +95,7 @@ def load_library():
         getattr(lib, name).restype = C.c_int
     lib.dapq_pseudo_queries_workspace_bytes.restype = sz
     lib.dapq_score_static_capacity.restype = sz
+    lib.dapq_topk_workspace_bytes.restype = sz
     _lib = lib
     return lib
 
@@ -184,9 +186,16 @@ def dapq_topk(shape, pooled, budget, budget_per_seq, idx, count, workspace=None,
                                     _stream(stream)))
 
 
-def dapq_pool_topk(shape, scores, width, budget, budget_per_seq, idx, count, pooled=None, stream=None):
+def dapq_pool_topk(shape, scores, width, budget, budget_per_seq, idx, count, pooled=None, stream=None, workspace=None):
     _check(load_library().dapq_pool_topk(C.byref(shape), _ptr(scores), width, budget, _ptr(budget_per_seq), _ptr(idx),
-                                         _ptr(count), _ptr(pooled), _stream(stream)))
+                                         _ptr(count), _ptr(pooled), _ptr(workspace),
+                                         0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                         _stream(stream)))
+
+
+def topk_workspace_bytes(shape, budget) -> int:
+    """Bytes of the optional workspace of dapq_topk / dapq_pool_topk (0: no head is long enough to need it)."""
+    return int(load_library().dapq_topk_workspace_bytes(C.byref(shape), budget))
 
 
 def dapq_gather(shape, k, v, idx, count, budget, k_out, v_out, stream=None):

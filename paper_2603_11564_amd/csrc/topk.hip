@@ -50,6 +50,13 @@ struct TopkParams {
   int64_t total_tokens;
   int32_t batch, n_kv_heads, budget;
   int32_t min_len, max_len;  // this launch handles the heads with min_len <= L <= max_len
+  // Long heads in pieces (cand_idx != NULL): workgroup (kv * n_segs + seg) selects among keys [seg * seg_len,
+  // (seg + 1) * seg_len) of its head and leaves its survivors (order keys and positions in the head, ascending) and
+  // their number in the candidate lists; topk_merge_kernel then selects among the candidates of a head.
+  int32_t n_segs, seg_len;
+  uint32_t* cand_key;   // [head][n_segs][budget]
+  int32_t* cand_idx;    // [head][n_segs][budget]
+  int32_t* cand_count;  // [head][n_segs]
 };
 
 // fp32 -> uint32 with the same order for all non-NaN values.
@@ -61,39 +68,61 @@ __device__ __forceinline__ uint32_t order_key(float f) {
 // What every variant needs to know about its head; heads of another launch (length outside
 // [min_len, max_len]), keep == 0 and keep == L are finished here.
 struct TopkHead {
-  const float* src;
+  const float* src;   // first score of the piece this workgroup selects from (the whole head, or a segment of it)
   int32_t* out;
-  int L, keep;
-  bool done;     // nothing left to select
-  bool foreign;  // the head belongs to another launch
+  uint32_t* out_key;  // segments: where the survivors' keys go (else NULL)
+  int L, keep;        // length of the piece, how many of it survive
+  int base, head_len; // where the piece starts in its head, and the head's length (pooling windows cross pieces)
+  bool done;          // nothing left to select
+  bool foreign;       // the head belongs to another launch
 };
 
 __device__ __forceinline__ TopkHead topk_head(const TopkParams& p) {
   TopkHead hd;
   const int tid = threadIdx.x;
-  const int kv = blockIdx.x, b = blockIdx.y, layer = blockIdx.z;
+  const bool pieces = p.cand_idx != nullptr;
+  const int nseg = pieces ? p.n_segs : 1;
+  const int kv = (int)blockIdx.x / nseg, seg = (int)blockIdx.x - kv * nseg, b = blockIdx.y, layer = blockIdx.z;
   int64_t start;
   if (p.cu_seqlens == nullptr) {
-    hd.L = (int)(p.total_tokens / p.batch);
-    start = (int64_t)b * hd.L;
+    hd.head_len = (int)(p.total_tokens / p.batch);
+    start = (int64_t)b * hd.head_len;
   } else {
     start = p.cu_seqlens[b];
-    hd.L = p.cu_seqlens[b + 1] - (int)start;
+    hd.head_len = p.cu_seqlens[b + 1] - (int)start;
   }
-  hd.foreign = hd.L < p.min_len || hd.L > p.max_len;
+  hd.base = 0;
+  hd.out_key = nullptr;
+  hd.foreign = hd.head_len < p.min_len || hd.head_len > p.max_len;
   if (hd.foreign) {
     hd.done = true;
     hd.keep = 0;
+    hd.L = 0;
     hd.out = nullptr;
     hd.src = nullptr;
     return hd;
   }
   int want = p.budget_per_seq ? p.budget_per_seq[b] : p.budget;
   want = want < 0 ? 0 : (want > p.budget ? p.budget : want);
-  hd.keep = want < hd.L ? want : hd.L;
   const int64_t head = ((int64_t)layer * p.batch + b) * p.n_kv_heads + kv;
+  const float* head_src = p.pooled + ((int64_t)layer * p.n_kv_heads + kv) * p.total_tokens + start;
+  if (pieces) {
+    hd.base = seg * p.seg_len;
+    const int left = hd.head_len - hd.base;
+    hd.L = left < 0 ? 0 : (left > p.seg_len ? p.seg_len : left);
+    hd.keep = want < hd.L ? want : hd.L;
+    const int64_t slot = head * nseg + seg;
+    hd.out = p.cand_idx + slot * p.budget;
+    hd.out_key = p.cand_key + slot * p.budget;
+    hd.src = head_src + hd.base;
+    if (tid == 0) p.cand_count[slot] = hd.keep;
+    hd.done = hd.keep == 0;  // (a piece that survives whole still goes through the selection: its keys are wanted)
+    return hd;
+  }
+  hd.L = hd.head_len;
+  hd.keep = want < hd.L ? want : hd.L;
   hd.out = p.idx + head * p.budget;
-  hd.src = p.pooled + ((int64_t)layer * p.n_kv_heads + kv) * p.total_tokens + start;
+  hd.src = head_src;
   if (tid == 0) p.count[head] = hd.keep;
   hd.done = hd.keep == 0;
   if (!hd.done && hd.keep == hd.L) {  // everything survives
@@ -166,118 +195,28 @@ __device__ __forceinline__ void topk_pick_digit(const uint32_t* hist, uint32_t* 
 // as dynamic LDS): the variant for 8K..32K keys, which has a compute unit to itself anyway.  The short-head variants
 // share a compute unit and would lose occupancy to the area; 64 keys per thread times 1024 threads do not fit.
 constexpr bool reg_variant_is_staged(int threads, int kpt) { return threads == 1024 && kpt == 32; }
-constexpr int reg_variant_stage_bytes(int threads, int kpt) {
-  return reg_variant_is_staged(threads, kpt) ? threads * (kpt + 4) * (int)sizeof(float) : 0;
+constexpr int reg_variant_stage_bytes(int threads, int kpt) {  // (two more rows: the halos of the first and last thread)
+  return reg_variant_is_staged(threads, kpt) ? (threads + 2) * (kpt + 4) * (int)sizeof(float) : 0;
 }
 
-// ---- heads that fit in registers.  R > 0: the input is the un-pooled score and the kernel applies
-// the max-pool of radius R itself (window clipped at the ends of the sequence) before selecting.
-template <int THREADS, int KPT, int R>
-__global__ __launch_bounds__(THREADS) void topk_reg_kernel(TopkParams p) {
+// ---- selection among the keys a workgroup holds in registers (KPT per thread, thread t's before thread t+1's):
+// the `keep` largest, ties to the lowest position, handed to emit(i, slot) in ascending position order (register
+// i of the calling thread is survivor number `slot`).  A register without a key holds 0 (a key is at least 1);
+// n_empty = how many of this thread's registers are empty.  keep >= 1 and at most the number of keys.
+template <int THREADS, int KPT, class Emit>
+__device__ __forceinline__ void topk_select(const uint32_t (&key)[KPT], int n_empty, int keep, Emit emit) {
   constexpr int kWaves = THREADS / 64;
   static_assert(KPT <= 255, "the first pass counts a thread's keys in 8-bit fields");
-  constexpr bool kStaged = reg_variant_is_staged(THREADS, KPT);
   __shared__ uint32_t hists[2][256];  // passes alternate: the next one's is cleared while wave 0 reads this one's
   __shared__ uint32_t bcasts[5][3];   // one row per pass (no pass waits for the readers of the one before), one for the tail
   __shared__ uint32_t tail[kTopkTailCap];  // low halves of the candidates left after two passes
   __shared__ uint32_t tail_n;
   __shared__ uint32_t wave_gt[kWaves], wave_eq[kWaves];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const TopkHead hd = topk_head(p);
-  if (hd.foreign || (hd.done && p.pooled_out == nullptr)) return;  // a finished head may still owe its pooled scores
-  const int L = hd.L;
-
-  // thread t owns keys [t*KPT, t*KPT + KPT): registers i < nvalid hold a key.  (A layout with
-  // contiguous rows per wave makes the compaction twice as long.)
-  const int j0 = tid * KPT;
-  const int nvalid = L - j0 < 0 ? 0 : (L - j0 > KPT ? KPT : L - j0);
-  float ext[KPT + 2 * R];  // scores j0-R .. j0+KPT+R-1; -inf outside the sequence
-  if (kStaged) {
-    // The head comes in with coalesced 16-byte loads (a thread reading its own run straight from memory makes
-    // every load instruction touch 64 cache lines, and the halo loads as many again) and is dealt out to its
-    // owners through LDS.  Row t of the staging area is thread t's run; rows are KPT + 4 words apart, which keeps
-    // them 16-byte aligned and spreads consecutive rows over the banks.
-    extern __shared__ float stage[];
-    constexpr int kRow = KPT + 4;
-    static_assert(R <= 4, "the halo of a run is read as one 16-byte piece of each neighbouring row");
-    if ((reinterpret_cast<uintptr_t>(hd.src) & 15) == 0) {
-#pragma unroll
-      for (int it = 0; it < KPT / 4; ++it) {
-        const int g = (it * THREADS + tid) * 4;
-        if (g + 4 <= L) {
-          *reinterpret_cast<float4*>(&stage[(g / KPT) * kRow + (g % KPT)]) = *reinterpret_cast<const float4*>(hd.src + g);
-        } else {
-          for (int k = 0; k < 4 && g + k < L; ++k) stage[(g / KPT) * kRow + (g % KPT) + k] = hd.src[g + k];
-        }
-      }
-    } else {
-      for (int j = tid; j < L; j += THREADS) stage[(j / KPT) * kRow + (j % KPT)] = hd.src[j];
-    }
-    __syncthreads();
-    // (words of the area that no key was written to are never selected below)
-#pragma unroll
-    for (int i = 0; i < KPT; i += 4) {
-      const float4 v = *reinterpret_cast<const float4*>(&stage[tid * kRow + i]);
-      ext[R + i] = i < nvalid ? v.x : -INFINITY;
-      ext[R + i + 1] = i + 1 < nvalid ? v.y : -INFINITY;
-      ext[R + i + 2] = i + 2 < nvalid ? v.z : -INFINITY;
-      ext[R + i + 3] = i + 3 < nvalid ? v.w : -INFINITY;
-    }
-    if (R > 0) {
-      float left[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY}, right[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-      if (tid > 0) {
-        const float4 v = *reinterpret_cast<const float4*>(&stage[(tid - 1) * kRow + KPT - 4]);
-        left[0] = v.x, left[1] = v.y, left[2] = v.z, left[3] = v.w;
-      }
-      if (tid + 1 < THREADS) {
-        const float4 v = *reinterpret_cast<const float4*>(&stage[(tid + 1) * kRow]);
-        right[0] = v.x, right[1] = v.y, right[2] = v.z, right[3] = v.w;
-      }
-#pragma unroll
-      for (int r = 0; r < R; ++r) {
-        const int jl = j0 - R + r, jr = j0 + KPT + r;
-        ext[r] = (jl >= 0 && jl < L) ? left[4 - R + r] : -INFINITY;
-        ext[R + KPT + r] = jr < L ? right[r] : -INFINITY;
-      }
-    }
-  } else {
-    if (nvalid == KPT && (reinterpret_cast<uintptr_t>(hd.src + j0) & 15) == 0) {
-#pragma unroll
-      for (int i = 0; i < KPT; i += 4) {
-        const float4 v = *reinterpret_cast<const float4*>(hd.src + j0 + i);
-        ext[R + i] = v.x;
-        ext[R + i + 1] = v.y;
-        ext[R + i + 2] = v.z;
-        ext[R + i + 3] = v.w;
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < KPT; ++i) ext[R + i] = i < nvalid ? hd.src[j0 + i] : -INFINITY;
-    }
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-      const int jl = j0 - R + r, jr = j0 + KPT + r;
-      ext[r] = (jl >= 0 && jl < L) ? hd.src[jl] : -INFINITY;
-      ext[R + KPT + r] = jr < L ? hd.src[jr] : -INFINITY;
-    }
-  }
-  uint32_t key[KPT];
-#pragma unroll
-  for (int i = 0; i < KPT; ++i) {
-    float m = ext[i];
-#pragma unroll
-    for (int t = 1; t <= 2 * R; ++t) m = fmaxf(m, ext[i + t]);
-    if (p.pooled_out != nullptr && i < nvalid) p.pooled_out[(hd.src - p.pooled) + j0 + i] = m;
-    // registers past the end of the head hold 0, which no key is (a key is at least 1): everything below can then
-    // tell them by value, and no per-register validity mask has to stay alive through the kernel
-    const uint32_t k = order_key(m);
-    key[i] = i < nvalid ? (k > 1u ? k : 1u) : 0u;
-  }
-  if (hd.done) return;
 
   // ---- radix select: threshold T = the keep-th largest key, need = how many keys == T to take
   uint32_t prefix = 0, mask = 0;
-  int need = hd.keep;
+  int need = keep;
   for (int e = tid; e < 256; e += THREADS) hists[0][e] = 0;
   if (tid == 0) tail_n = 0;
   __syncthreads();
@@ -315,7 +254,7 @@ __global__ __launch_bounds__(THREADS) void topk_reg_kernel(TopkParams p) {
       uint64_t fields = 0;
 #pragma unroll
       for (int i = 0; i < KPT; ++i) fields += 1ull << ((((key[i] >> 24) - dmin) * 8u) & 63u);
-      fields -= (uint64_t)(KPT - nvalid) << (((0u - dmin) * 8u) & 63u);
+      fields -= (uint64_t)n_empty << (((0u - dmin) * 8u) & 63u);
       // two bins per 32-bit word, 16 bits each: a wave's count is at most 64 * KPT < 65536
       uint32_t pair[4];
 #pragma unroll
@@ -433,11 +372,162 @@ __global__ __launch_bounds__(THREADS) void topk_reg_kernel(TopkParams p) {
     const bool eq = key[i] == T;
     const bool take = key[i] > T || (eq && pre_eq < un);
     if (__ballot(take) != 0) {  // survivors are few: most of a wave's registers hold none
-      if (take) hd.out[pos] = j0 + i;
+      if (take) emit(i, pos);
     }
     pos += take ? 1u : 0u;
     pre_eq += eq ? 1u : 0u;
   }
+}
+
+// ---- heads that fit in registers.  R > 0: the input is the un-pooled score and the kernel applies
+// the max-pool of radius R itself (window clipped at the ends of the sequence) before selecting.
+template <int THREADS, int KPT, int R>
+__global__ __launch_bounds__(THREADS) void topk_reg_kernel(TopkParams p) {
+  constexpr bool kStaged = reg_variant_is_staged(THREADS, KPT);
+  const int tid = threadIdx.x;
+  const TopkHead hd = topk_head(p);
+  if (hd.foreign || (hd.done && p.pooled_out == nullptr)) return;  // a finished head may still owe its pooled scores
+  const int L = hd.L;
+  // position j of this piece is a position of its head (the pooling window does not stop at the end of a piece)
+  auto in_head = [&](int j) { return (unsigned)(hd.base + j) < (unsigned)hd.head_len; };
+
+  // thread t owns keys [t*KPT, t*KPT + KPT): registers i < nvalid hold a key.  (A layout with
+  // contiguous rows per wave makes the compaction twice as long.)
+  const int j0 = tid * KPT;
+  const int nvalid = L - j0 < 0 ? 0 : (L - j0 > KPT ? KPT : L - j0);
+  float ext[KPT + 2 * R];  // scores j0-R .. j0+KPT+R-1; -inf outside the sequence
+  if (kStaged) {
+    // The head comes in with coalesced 16-byte loads (a thread reading its own run straight from memory makes
+    // every load instruction touch 64 cache lines, and the halo loads as many again) and is dealt out to its
+    // owners through LDS.  Row t + 1 of the staging area is thread t's run; rows are KPT + 4 words apart, which keeps
+    // them 16-byte aligned and spreads consecutive rows over the banks.  Row 0 ends with the four scores before the
+    // piece and row THREADS + 1 starts with the four after it (neighbouring pieces of a long head), if the head has them.
+    extern __shared__ float stage_area[];
+    constexpr int kRow = KPT + 4;
+    float* stage = stage_area + kRow;  // row 0 of `stage` is thread 0's
+    static_assert(R <= 4, "the halo of a run is read as one 16-byte piece of each neighbouring row");
+    if ((reinterpret_cast<uintptr_t>(hd.src) & 15) == 0) {
+#pragma unroll
+      for (int it = 0; it < KPT / 4; ++it) {
+        const int g = (it * THREADS + tid) * 4;
+        if (g + 4 <= L) {
+          *reinterpret_cast<float4*>(&stage[(g / KPT) * kRow + (g % KPT)]) = *reinterpret_cast<const float4*>(hd.src + g);
+        } else {
+          for (int k = 0; k < 4 && g + k < L; ++k) stage[(g / KPT) * kRow + (g % KPT) + k] = hd.src[g + k];
+        }
+      }
+    } else {
+      for (int j = tid; j < L; j += THREADS) stage[(j / KPT) * kRow + (j % KPT)] = hd.src[j];
+    }
+    if (R > 0 && tid < 8) {
+      const int j = tid < 4 ? tid - 4 : THREADS * KPT + (tid - 4);
+      const float v = in_head(j) ? hd.src[j] : -INFINITY;
+      if (tid < 4) stage[-kRow + KPT - 4 + tid] = v;
+      else stage[THREADS * kRow + (tid - 4)] = v;
+    }
+    __syncthreads();
+    // (words of the area that no key was written to are never selected below)
+#pragma unroll
+    for (int i = 0; i < KPT; i += 4) {
+      const float4 v = *reinterpret_cast<const float4*>(&stage[tid * kRow + i]);
+      ext[R + i] = i < nvalid ? v.x : -INFINITY;
+      ext[R + i + 1] = i + 1 < nvalid ? v.y : -INFINITY;
+      ext[R + i + 2] = i + 2 < nvalid ? v.z : -INFINITY;
+      ext[R + i + 3] = i + 3 < nvalid ? v.w : -INFINITY;
+    }
+    if (R > 0) {
+      const float4 lv = *reinterpret_cast<const float4*>(&stage[(tid - 1) * kRow + KPT - 4]);
+      const float4 rv = *reinterpret_cast<const float4*>(&stage[(tid + 1) * kRow]);
+      const float left[4] = {lv.x, lv.y, lv.z, lv.w}, right[4] = {rv.x, rv.y, rv.z, rv.w};
+#pragma unroll
+      for (int r = 0; r < R; ++r) {  // (words of the area nobody wrote lie outside the head)
+        ext[r] = in_head(j0 - R + r) ? left[4 - R + r] : -INFINITY;
+        ext[R + KPT + r] = in_head(j0 + KPT + r) ? right[r] : -INFINITY;
+      }
+    }
+  } else {
+    if (nvalid == KPT && (reinterpret_cast<uintptr_t>(hd.src + j0) & 15) == 0) {
+#pragma unroll
+      for (int i = 0; i < KPT; i += 4) {
+        const float4 v = *reinterpret_cast<const float4*>(hd.src + j0 + i);
+        ext[R + i] = v.x;
+        ext[R + i + 1] = v.y;
+        ext[R + i + 2] = v.z;
+        ext[R + i + 3] = v.w;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < KPT; ++i) ext[R + i] = i < nvalid ? hd.src[j0 + i] : -INFINITY;
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int jl = j0 - R + r, jr = j0 + KPT + r;
+      ext[r] = in_head(jl) ? hd.src[jl] : -INFINITY;
+      ext[R + KPT + r] = in_head(jr) ? hd.src[jr] : -INFINITY;
+    }
+  }
+  uint32_t key[KPT];
+#pragma unroll
+  for (int i = 0; i < KPT; ++i) {
+    float m = ext[i];
+#pragma unroll
+    for (int t = 1; t <= 2 * R; ++t) m = fmaxf(m, ext[i + t]);
+    if (p.pooled_out != nullptr && i < nvalid) p.pooled_out[(hd.src - p.pooled) + j0 + i] = m;
+    // registers past the end of the head hold 0, which no key is (a key is at least 1): everything below can then
+    // tell them by value, and no per-register validity mask has to stay alive through the kernel
+    const uint32_t k = order_key(m);
+    key[i] = i < nvalid ? (k > 1u ? k : 1u) : 0u;
+  }
+  if (hd.done) return;
+
+
+  topk_select<THREADS, KPT>(key, KPT - nvalid, hd.keep, [&](int i, uint32_t slot) {
+    hd.out[slot] = hd.base + j0 + i;
+    if (hd.out_key != nullptr) hd.out_key[slot] = key[i];
+  });
+}
+
+// ---- a long head whose pieces have been through topk_reg_kernel: the `keep` largest of the candidates they left.
+// A thread owns KPT consecutive slots of the head's [n_segs][budget] candidate lists; the slots a piece did not fill
+// are empty.  Candidates are in ascending position inside a list and the lists in piece order, so ties still go to
+// the lowest position and the result is ascending.
+constexpr int kTopkMaxSegs = 64;
+template <int THREADS, int KPT>
+__global__ __launch_bounds__(THREADS) void topk_merge_kernel(TopkParams p) {
+  __shared__ int32_t seg_count[kTopkMaxSegs];
+  const int tid = threadIdx.x;
+  const int kv = blockIdx.x, b = blockIdx.y, layer = blockIdx.z;
+  int L;
+  if (p.cu_seqlens == nullptr) L = (int)(p.total_tokens / p.batch);
+  else L = p.cu_seqlens[b + 1] - p.cu_seqlens[b];
+  if (L < p.min_len || L > p.max_len) return;
+  int want = p.budget_per_seq ? p.budget_per_seq[b] : p.budget;
+  want = want < 0 ? 0 : (want > p.budget ? p.budget : want);
+  const int keep = want < L ? want : L;
+  const int64_t head = ((int64_t)layer * p.batch + b) * p.n_kv_heads + kv;
+  if (tid == 0) p.count[head] = keep;
+  if (keep == 0) return;
+  const int nseg = p.n_segs, slots = nseg * p.budget;
+  if (tid < nseg) seg_count[tid] = p.cand_count[head * nseg + tid];
+  __syncthreads();
+  const uint32_t* ck = p.cand_key + head * slots;
+  const int32_t* ci = p.cand_idx + head * slots;
+  int32_t* out = p.idx + head * p.budget;
+  const int s0 = tid * KPT;
+  int seg = s0 / p.budget, r = s0 - seg * p.budget;
+  uint32_t key[KPT];
+  int n_empty = 0;
+#pragma unroll
+  for (int i = 0; i < KPT; ++i) {
+    const bool valid = s0 + i < slots && r < seg_count[seg < nseg ? seg : 0];
+    key[i] = valid ? ck[s0 + i] : 0u;
+    n_empty += valid ? 0 : 1;
+    if (++r == p.budget) {
+      r = 0;
+      ++seg;
+    }
+  }
+  topk_select<THREADS, KPT>(key, n_empty, keep, [&](int i, uint32_t slot) { out[slot] = ci[s0 + i]; });
 }
 
 // ---- longer heads
@@ -608,6 +698,23 @@ int launch_reg(RegVariant v, dim3 grid, hipStream_t st, const TopkParams& p) {
   return DAPQ_OK;
 }
 
+int launch_reg_radius(int radius, RegVariant v, dim3 grid, hipStream_t st, const TopkParams& p) {
+  switch (radius) {
+    case 0: return launch_reg<0>(v, grid, st, p);
+    case 1: return launch_reg<1>(v, grid, st, p);
+    case 2: return launch_reg<2>(v, grid, st, p);
+    case 3: return launch_reg<3>(v, grid, st, p);
+    default: return launch_reg<4>(v, grid, st, p);
+  }
+}
+
+void launch_merge(RegVariant v, dim3 grid, hipStream_t st, const TopkParams& p) {
+  if (v.threads == 256 && v.kpt == 32) hipLaunchKernelGGL((topk_merge_kernel<256, 32>), grid, dim3(256), 0, st, p);
+  else if (v.threads == 256) hipLaunchKernelGGL((topk_merge_kernel<256, 64>), grid, dim3(256), 0, st, p);
+  else if (v.kpt == 32) hipLaunchKernelGGL((topk_merge_kernel<1024, 32>), grid, dim3(1024), 0, st, p);
+  else hipLaunchKernelGGL((topk_merge_kernel<1024, 64>), grid, dim3(1024), 0, st, p);
+}
+
 int topk_common_checks(const dapq_shape* shape, const float* in, int32_t budget, const int32_t* idx, const int32_t* count) {
   int rc = check_shape(shape, false, false, false);
   if (rc != DAPQ_OK) return rc;
@@ -619,79 +726,88 @@ int topk_common_checks(const dapq_shape* shape, const float* in, int32_t budget,
   return DAPQ_OK;
 }
 
-}  // namespace
-}  // namespace dapq
+// Which kernels a batch goes to.  Heads that fit the chosen register variant go there; longer ones go in pieces of
+// kTopkPieceLen keys through the variant for 32768 keys and a merge (if the caller brought the workspace for the
+// candidate lists), else to the streaming kernel.  A dense batch knows its length; a ragged one launches both kinds,
+// each skipping the heads of the other.
+constexpr int kTopkPieceLen = 1024 * 32;
+struct TopkRoute {
+  RegVariant variant;
+  int64_t reg_max;     // heads up to this length: the register variant
+  bool any_short, any_long;
+  // the long heads in pieces
+  bool pieces_possible;
+  int n_segs;
+  size_t off_key, off_idx, off_count, pieces_bytes;
+};
 
-extern "C" DAPQ_API int dapq_topk(const dapq_shape* shape, const float* pooled, int32_t budget, const int32_t* budget_per_seq,
-                         int32_t* idx, int32_t* count, void* workspace, size_t workspace_bytes, void* stream) {
-  (void)workspace;
-  (void)workspace_bytes;
-  int rc = topk_common_checks(shape, pooled, budget, idx, count);
-  if (rc != DAPQ_OK) return rc;
-  TopkParams p;
-  p.pooled = pooled;
-  p.pooled_out = nullptr;
-  p.cu_seqlens = shape->cu_seqlens;
-  p.budget_per_seq = budget_per_seq;
-  p.idx = idx;
-  p.count = count;
-  p.total_tokens = shape->total_tokens;
-  p.batch = shape->batch;
-  p.n_kv_heads = shape->n_kv_heads;
-  p.budget = budget;
-  // Heads that fit the chosen register variant go there, longer ones to the streaming kernel.  A
-  // dense batch knows its length; a ragged one launches both kernels, each skipping the heads of
-  // the other.
-  const dim3 grid((unsigned)shape->n_kv_heads, (unsigned)shape->batch, (unsigned)shape->n_layers);
-  hipStream_t st = static_cast<hipStream_t>(stream);
+TopkRoute topk_route(const dapq_shape* shape, int32_t budget) {
+  TopkRoute r;
+  const bool ragged = shape->cu_seqlens != nullptr;
   const int64_t mean = shape->total_tokens / shape->batch;
-  const int64_t longest = shape->cu_seqlens == nullptr ? mean : shape->total_tokens;
+  const int64_t longest = ragged ? shape->total_tokens : mean;
   // a ragged batch sizes the variant for 1.5 x its mean length (or everything, if that is less)
-  const int64_t sized_for = shape->cu_seqlens == nullptr ? mean : (mean + mean / 2 < longest ? mean + mean / 2 : longest);
-  const RegVariant variant = reg_variant_for(sized_for);
-  const int64_t reg_max = variant.max_len();
-  p.min_len = 0;
-  p.max_len = (int32_t)reg_max;
-  if (shape->cu_seqlens != nullptr || mean <= reg_max) {  // (a dense batch of longer heads has nothing for it)
-    if ((rc = launch_reg<0>(variant, grid, st, p)) != DAPQ_OK) return rc;
-    DAPQ_HIP_LAUNCH_CHECK("topk_reg_kernel");
+  const int64_t sized_for = !ragged ? mean : (mean + mean / 2 < longest ? mean + mean / 2 : longest);
+  r.variant = reg_variant_for(sized_for);
+  r.reg_max = r.variant.max_len();
+  r.any_short = ragged || mean <= r.reg_max;  // (a dense batch of longer heads has nothing for the register variant)
+  r.any_long = longest > r.reg_max;
+  const int64_t n_segs = (longest + kTopkPieceLen - 1) / kTopkPieceLen;
+  r.pieces_possible = r.any_long && n_segs <= kTopkMaxSegs && n_segs * budget <= 65536 &&
+                      (int64_t)shape->n_kv_heads * n_segs <= 0x7FFFFFFF;
+  r.n_segs = (int)n_segs;
+  r.off_key = r.off_idx = r.off_count = r.pieces_bytes = 0;
+  if (r.pieces_possible) {
+    const size_t heads = (size_t)shape->n_layers * shape->batch * shape->n_kv_heads;
+    const size_t list = align_up(heads * (size_t)n_segs * (size_t)budget * 4, 256);
+    r.off_key = 0;
+    r.off_idx = list;
+    r.off_count = 2 * list;
+    r.pieces_bytes = 2 * list + align_up(heads * (size_t)n_segs * 4, 256);
   }
-  if (longest > reg_max) {
-    p.min_len = (int32_t)reg_max + 1;
-    p.max_len = INT32_MAX;
-    // heads of up to kTopkLdsKeys keys are staged in LDS; if none of this launch can be that short the staging
-    // area is left out
-    const int lds_bytes = (kStreamLdsHead + (p.min_len <= kTopkLdsKeys ? kTopkLdsKeys : 0)) * (int)sizeof(uint32_t);
-    // the limit is raised once, to the size with the staging area
-    const int rc_lds = set_max_dynamic_lds(reinterpret_cast<const void*>(topk_stream_kernel),
-                                           (kStreamLdsHead + kTopkLdsKeys) * (int)sizeof(uint32_t));
-    if (rc_lds != DAPQ_OK) return rc_lds;
-    hipLaunchKernelGGL(topk_stream_kernel, grid, dim3(kTopkThreads), lds_bytes, st, p);
-    DAPQ_HIP_LAUNCH_CHECK("topk_stream_kernel");
+  return r;
+}
+
+// The kernels for the long heads of a launch whose TopkParams are filled except for the long-head fields.
+// radius > 0: the kernels of the pieces pool the scores themselves.
+int launch_long_heads(const dapq_shape* shape, const TopkRoute& r, TopkParams p, int radius, void* workspace,
+                      size_t workspace_bytes, hipStream_t st) {
+  p.min_len = (int32_t)r.reg_max + 1;
+  p.max_len = INT32_MAX;
+  const dim3 grid((unsigned)shape->n_kv_heads, (unsigned)shape->batch, (unsigned)shape->n_layers);
+  if (r.pieces_possible && workspace != nullptr && workspace_bytes >= r.pieces_bytes) {
+    char* ws = static_cast<char*>(workspace);
+    p.n_segs = r.n_segs;
+    p.seg_len = kTopkPieceLen;
+    p.cand_key = reinterpret_cast<uint32_t*>(ws + r.off_key);
+    p.cand_idx = reinterpret_cast<int32_t*>(ws + r.off_idx);
+    p.cand_count = reinterpret_cast<int32_t*>(ws + r.off_count);
+    const dim3 piece_grid((unsigned)(shape->n_kv_heads * r.n_segs), (unsigned)shape->batch, (unsigned)shape->n_layers);
+    const int rc = launch_reg_radius(radius, RegVariant{1024, 32}, piece_grid, st, p);
+    if (rc != DAPQ_OK) return rc;
+    DAPQ_HIP_LAUNCH_CHECK("topk_reg_kernel (pieces)");
+    launch_merge(reg_variant_for((int64_t)r.n_segs * p.budget), grid, st, p);
+    DAPQ_HIP_LAUNCH_CHECK("topk_merge_kernel");
+    return DAPQ_OK;
   }
+  DAPQ_REQUIRE(radius == 0, DAPQ_ERR_INVALID_ARG, "internal: the streaming kernel does not pool");
+  // heads of up to kTopkLdsKeys keys are staged in LDS; if none of this launch can be that short the staging
+  // area is left out
+  const int lds_bytes = (kStreamLdsHead + (p.min_len <= kTopkLdsKeys ? kTopkLdsKeys : 0)) * (int)sizeof(uint32_t);
+  // the limit is raised once, to the size with the staging area
+  const int rc_lds = set_max_dynamic_lds(reinterpret_cast<const void*>(topk_stream_kernel),
+                                         (kStreamLdsHead + kTopkLdsKeys) * (int)sizeof(uint32_t));
+  if (rc_lds != DAPQ_OK) return rc_lds;
+  hipLaunchKernelGGL(topk_stream_kernel, grid, dim3(kTopkThreads), lds_bytes, st, p);
+  DAPQ_HIP_LAUNCH_CHECK("topk_stream_kernel");
   return DAPQ_OK;
 }
 
-extern "C" DAPQ_API int dapq_pool_topk(const dapq_shape* shape, const float* scores, int32_t width, int32_t budget,
-                                       const int32_t* budget_per_seq, int32_t* idx, int32_t* count, float* pooled,
-                                       void* stream) {
-  int rc = topk_common_checks(shape, scores, budget, idx, count);
-  if (rc != DAPQ_OK) return rc;
-  DAPQ_REQUIRE(width >= 1 && width <= 63 && (width & 1) == 1, DAPQ_ERR_INVALID_ARG,
-               "width (%d) must be odd and in [1, 63]", width);
-  DAPQ_REQUIRE(pooled != scores, DAPQ_ERR_INVALID_ARG, "pooled must not alias scores");
-  // one kernel if every head fits the register variant and the window is one of the compiled radii
-  const int64_t longest = shape->cu_seqlens == nullptr ? shape->total_tokens / shape->batch : shape->total_tokens;
-  const bool fused = width <= 9 && longest <= 64 * kTopkThreads;
-  if (!fused) {
-    DAPQ_REQUIRE(pooled != nullptr, DAPQ_ERR_UNSUPPORTED,
-                 "width %d / head length %lld need the two-kernel path: pass a pooled buffer", width, (long long)longest);
-    if ((rc = dapq_pool(shape, scores, pooled, width, stream)) != DAPQ_OK) return rc;
-    return dapq_topk(shape, pooled, budget, budget_per_seq, idx, count, nullptr, 0, stream);
-  }
+TopkParams topk_params(const dapq_shape* shape, const float* in, float* pooled_out, int32_t budget,
+                       const int32_t* budget_per_seq, int32_t* idx, int32_t* count) {
   TopkParams p;
-  p.pooled = scores;
-  p.pooled_out = pooled;
+  p.pooled = in;
+  p.pooled_out = pooled_out;
   p.cu_seqlens = shape->cu_seqlens;
   p.budget_per_seq = budget_per_seq;
   p.idx = idx;
@@ -702,17 +818,70 @@ extern "C" DAPQ_API int dapq_pool_topk(const dapq_shape* shape, const float* sco
   p.budget = budget;
   p.min_len = 0;
   p.max_len = INT32_MAX;
-  const RegVariant variant = reg_variant_for(longest);
+  p.n_segs = 1;
+  p.seg_len = 0;
+  p.cand_key = nullptr;
+  p.cand_idx = nullptr;
+  p.cand_count = nullptr;
+  return p;
+}
+
+}  // namespace
+}  // namespace dapq
+
+extern "C" DAPQ_API size_t dapq_topk_workspace_bytes(const dapq_shape* shape, int32_t budget) {
+  if (check_shape(shape, false, false, false) != DAPQ_OK || budget < 1) return 0;
+  return topk_route(shape, budget).pieces_bytes;
+}
+
+extern "C" DAPQ_API int dapq_topk(const dapq_shape* shape, const float* pooled, int32_t budget, const int32_t* budget_per_seq,
+                         int32_t* idx, int32_t* count, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = topk_common_checks(shape, pooled, budget, idx, count);
+  if (rc != DAPQ_OK) return rc;
+  TopkParams p = topk_params(shape, pooled, nullptr, budget, budget_per_seq, idx, count);
+  const TopkRoute route = topk_route(shape, budget);
   const dim3 grid((unsigned)shape->n_kv_heads, (unsigned)shape->batch, (unsigned)shape->n_layers);
   hipStream_t st = static_cast<hipStream_t>(stream);
-  switch (width / 2) {
-    case 0: rc = launch_reg<0>(variant, grid, st, p); break;
-    case 1: rc = launch_reg<1>(variant, grid, st, p); break;
-    case 2: rc = launch_reg<2>(variant, grid, st, p); break;
-    case 3: rc = launch_reg<3>(variant, grid, st, p); break;
-    default: rc = launch_reg<4>(variant, grid, st, p); break;
+  if (route.any_short) {
+    p.max_len = (int32_t)route.reg_max;
+    if ((rc = launch_reg<0>(route.variant, grid, st, p)) != DAPQ_OK) return rc;
+    DAPQ_HIP_LAUNCH_CHECK("topk_reg_kernel");
   }
-  if (rc != DAPQ_OK) return rc;
-  DAPQ_HIP_LAUNCH_CHECK("topk_reg_kernel");
+  if (route.any_long) return launch_long_heads(shape, route, p, 0, workspace, workspace_bytes, st);
   return DAPQ_OK;
+}
+
+extern "C" DAPQ_API int dapq_pool_topk(const dapq_shape* shape, const float* scores, int32_t width, int32_t budget,
+                                       const int32_t* budget_per_seq, int32_t* idx, int32_t* count, float* pooled,
+                                       void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = topk_common_checks(shape, scores, budget, idx, count);
+  if (rc != DAPQ_OK) return rc;
+  DAPQ_REQUIRE(width >= 1 && width <= 63 && (width & 1) == 1, DAPQ_ERR_INVALID_ARG,
+               "width (%d) must be odd and in [1, 63]", width);
+  DAPQ_REQUIRE(pooled != scores, DAPQ_ERR_INVALID_ARG, "pooled must not alias scores");
+  const int64_t longest = shape->cu_seqlens == nullptr ? shape->total_tokens / shape->batch : shape->total_tokens;
+  const dim3 grid((unsigned)shape->n_kv_heads, (unsigned)shape->batch, (unsigned)shape->n_layers);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  TopkParams p = topk_params(shape, scores, pooled, budget, budget_per_seq, idx, count);
+  if (width <= 9 && longest <= 64 * kTopkThreads) {
+    // one kernel: every head fits a register variant, which pools on the way in
+    if ((rc = launch_reg_radius(width / 2, reg_variant_for(longest), grid, st, p)) != DAPQ_OK) return rc;
+    DAPQ_HIP_LAUNCH_CHECK("topk_reg_kernel");
+    return DAPQ_OK;
+  }
+  const TopkRoute route = topk_route(shape, budget);
+  if (width <= 9 && route.pieces_possible && workspace != nullptr && workspace_bytes >= route.pieces_bytes) {
+    // the same with the long heads in pieces: their kernels pool across the piece boundaries
+    if (route.any_short) {
+      p.max_len = (int32_t)route.reg_max;
+      if ((rc = launch_reg_radius(width / 2, route.variant, grid, st, p)) != DAPQ_OK) return rc;
+      DAPQ_HIP_LAUNCH_CHECK("topk_reg_kernel");
+    }
+    return launch_long_heads(shape, route, p, width / 2, workspace, workspace_bytes, st);
+  }
+  DAPQ_REQUIRE(pooled != nullptr, DAPQ_ERR_UNSUPPORTED,
+               "width %d / head length %lld need the two-kernel path: pass a pooled buffer (or, for width <= 9, a "
+               "workspace of dapq_topk_workspace_bytes())", width, (long long)longest);
+  if ((rc = dapq_pool(shape, scores, pooled, width, stream)) != DAPQ_OK) return rc;
+  return dapq_topk(shape, pooled, budget, budget_per_seq, idx, count, workspace, workspace_bytes, stream);
 }

@@ -83,19 +83,25 @@ class Problem:
         D.dapq_pool(self.shape, S, P, width)
         return P
 
-    def topk(self, P, budget, per_seq=None):
+    def topk_workspace(self, budget, pieces=True):
+        """The optional workspace of the selection calls (long heads go in pieces through it), filled with a
+        pattern: the calls must not rely on its contents.  None if the shape needs none or `pieces` is False."""
+        n = D.topk_workspace_bytes(self.shape, budget) if pieces else 0
+        return torch.full((n,), 0xA5, dtype=torch.uint8, device=self.device) if n else None
+
+    def topk(self, P, budget, per_seq=None, pieces=True):
         idx = torch.full((self.layers, self.batch, self.Hkv, budget), -7, dtype=torch.int32, device=self.device)
         count = torch.full((self.layers, self.batch, self.Hkv), -7, dtype=torch.int32, device=self.device)
         ps = None if per_seq is None else torch.tensor(per_seq, dtype=torch.int32, device=self.device)
-        D.dapq_topk(self.shape, P, budget, ps, idx, count, self.ws)
+        D.dapq_topk(self.shape, P, budget, ps, idx, count, self.topk_workspace(budget, pieces))
         return idx, count
 
-    def pool_topk(self, S, width, budget, per_seq=None, want_pooled=True):
+    def pool_topk(self, S, width, budget, per_seq=None, want_pooled=True, pieces=False):
         idx = torch.full((self.layers, self.batch, self.Hkv, budget), -7, dtype=torch.int32, device=self.device)
         count = torch.full((self.layers, self.batch, self.Hkv), -7, dtype=torch.int32, device=self.device)
         ps = None if per_seq is None else torch.tensor(per_seq, dtype=torch.int32, device=self.device)
         P = torch.full_like(S, float("nan")) if want_pooled else None
-        D.dapq_pool_topk(self.shape, S, width, budget, ps, idx, count, P)
+        D.dapq_pool_topk(self.shape, S, width, budget, ps, idx, count, P, workspace=self.topk_workspace(budget, pieces))
         return idx, count, P
 
     def gather(self, idx, count, budget):

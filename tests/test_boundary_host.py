@@ -127,14 +127,14 @@ def test_invalid_arguments_of_the_entry_points_around_the_step(lib):
     assert lib.dapq_score_stats_extend(sp, FAKE, FAKE, kp[0], kp[1], kp[2], i64(64), FAKE, None) == ERR_INVALID   # row < d
     assert lib.dapq_score_stats_extend(sp, FAKE, FAKE, kp[0], kp[1], i64(132), kp[3], FAKE, None) == ERR_UNSUPPORTED
     # pooling + selection in one call
-    assert lib.dapq_pool_topk(sp, FAKE, 4, 8, None, FAKE, FAKE, None, None) == ERR_INVALID             # even width
-    assert lib.dapq_pool_topk(sp, FAKE, 7, 0, None, FAKE, FAKE, None, None) == ERR_INVALID             # budget
-    assert lib.dapq_pool_topk(sp, FAKE, 7, 8, None, FAKE, FAKE, FAKE, None) == ERR_INVALID             # pooled aliases scores
-    assert lib.dapq_pool_topk(sp, FAKE, 11, 8, None, FAKE, FAKE, None, None) == ERR_UNSUPPORTED        # needs the buffer
+    assert lib.dapq_pool_topk(sp, FAKE, 4, 8, None, FAKE, FAKE, None, None, 0, None) == ERR_INVALID             # even width
+    assert lib.dapq_pool_topk(sp, FAKE, 7, 0, None, FAKE, FAKE, None, None, 0, None) == ERR_INVALID             # budget
+    assert lib.dapq_pool_topk(sp, FAKE, 7, 8, None, FAKE, FAKE, FAKE, None, 0, None) == ERR_INVALID             # pooled aliases scores
+    assert lib.dapq_pool_topk(sp, FAKE, 11, 8, None, FAKE, FAKE, None, None, 0, None) == ERR_UNSUPPORTED        # needs the buffer
     assert b"pooled" in lib.dapq_last_error()
     long_heads = good_shape(total_tokens=70000, k_strides=(70000 * 8 * 128, 0, 128, 8 * 128),
                             v_strides=(70000 * 8 * 128, 0, 128, 8 * 128))
-    assert lib.dapq_pool_topk(C.byref(long_heads), FAKE, 7, 8, None, FAKE, FAKE, None, None) == ERR_UNSUPPORTED
+    assert lib.dapq_pool_topk(C.byref(long_heads), FAKE, 7, 8, None, FAKE, FAKE, None, None, 0, None) == ERR_UNSUPPORTED
     # recall
     assert lib.dapq_recall(sp, FAKE, FAKE, 8, FAKE, FAKE, 8, None, None, None) == ERR_INVALID
     assert lib.dapq_recall(sp, FAKE, FAKE, 0, FAKE, FAKE, 8, FAKE, None, None) == ERR_INVALID

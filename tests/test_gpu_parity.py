@@ -217,10 +217,10 @@ def test_pool_dense_batch_unaligned_total(H):
 
 
 # ----------------------------------------------------------------------------------------- top-K
-def _topk_case(H, lens, budget, P, per_seq=None, layers=1, Hkv=2, dense=False):
+def _topk_case(H, lens, budget, P, per_seq=None, layers=1, Hkv=2, dense=False, pieces=True):
     q, k, v, cu = random_problem(4, layers, lens, Hkv, Hkv, 1)
     prob = H.Problem(q, k, v, Hkv, None if dense else cu, "thd")
-    idx, count = prob.topk(torch.from_numpy(P).cuda(), budget, per_seq)
+    idx, count = prob.topk(torch.from_numpy(P).cuda(), budget, per_seq, pieces)
     idx, count = idx.cpu().numpy(), count.cpu().numpy()
     for l in range(layers):
         for b in range(len(lens)):
@@ -281,12 +281,35 @@ def test_topk_both_signs_over_many_binades(H, L):
         _topk_case(H, [L], budget, P, dense=True)
 
 
-def test_topk_long_sequence_not_staged_in_lds(H):
-    announce("topk L=70000 (streams from memory)")
+@pytest.mark.parametrize("pieces", [False, True])
+def test_topk_long_sequence_not_staged_in_lds(H, pieces):
+    """A head longer than a workgroup's registers hold: streamed from memory (no workspace) or selected in pieces of
+    32768 keys whose candidates are then selected among (with the workspace)."""
+    announce(f"topk L=70000 pieces={pieces}")
     r = np.random.default_rng(7)
     P = r.random((1, 1, 70000)).astype(np.float32)
     P[0, 0, 5000:5100] = 2.0
-    _topk_case(H, [70000], 2048, P, Hkv=1)
+    _topk_case(H, [70000], 2048, P, Hkv=1, pieces=pieces)
+
+
+@pytest.mark.parametrize("lens,dense,budget", [([131072], True, 3932), ([200001], True, 983), ([65537] * 2, True, 5),
+                                               ([70000, 3, 0, 140001, 9000], False, 2048),
+                                               ([98304], True, 40000)])
+def test_topk_long_heads_in_pieces(H, lens, dense, budget):
+    """Long heads through the candidate lists: the 70B-class length, a length that is no multiple of anything, a
+    ragged batch that mixes heads of every kind, ties that straddle the piece boundaries, a plateau over a whole
+    piece, and a budget larger than a piece (every piece survives whole)."""
+    announce(f"topk in pieces lens={lens} budget={budget}")
+    r = np.random.default_rng(sum(lens) + budget)
+    tot = sum(lens)
+    P = (r.random((1, 2, tot)) ** 5).astype(np.float32)
+    P[0, 0] = np.round(P[0, 0] * 16) / 16                       # 17 distinct values: ties across every boundary
+    P[0, 1, 30000:66000] = 0.5                                  # plateau over all of the second piece
+    if budget * ((max(lens) + 32767) // 32768) > 65536:
+        q, k, v, cu = random_problem(4, 1, lens, 2, 2, 1)
+        prob = H.Problem(q, k, v, 2, None if dense else cu, "thd")
+        assert H.D.topk_workspace_bytes(prob.shape, budget) == 0   # too many candidates: the streaming kernel serves
+    _topk_case(H, lens, budget, P, dense=dense, pieces=True)
 
 
 @pytest.mark.parametrize("L,batch", [(8192, 1), (8193, 3), (16384, 2), (16385, 1), (20001, 2), (32767, 3), (32768, 1),
@@ -304,14 +327,20 @@ def test_topk_dense_lengths_around_the_variant_limits(H, L, batch):
         _topk_case(H, [L] * batch, budget, P, Hkv=1, dense=True)
 
 
+_POOL_TOPK_SHAPES = [([5000], True), ([8193] * 2, True), ([20001] * 2, True), ([40000], True), ([70000], True),
+                     ([131072], True), ([1, 6, 100, 1025, 0, 4097], False), ([70000, 3, 0, 40000], False)]
+# long heads (more than 65536 keys; a ragged batch counts with its total) also go in pieces through the workspace
+_POOL_TOPK_CASES = [(lens, dense, pieces) for lens, dense in _POOL_TOPK_SHAPES
+                    for pieces in ([False, True] if (max(lens) if dense else sum(lens)) > 65536 else [False])]
+
+
 @pytest.mark.parametrize("width", [1, 3, 5, 7, 9, 11])
-@pytest.mark.parametrize("lens,dense", [([5000], True), ([8193] * 2, True), ([20001] * 2, True), ([40000], True), ([70000], True),
-                                        ([1, 6, 100, 1025, 0, 4097], False)])
-def test_pool_topk_one_call_equals_the_two(H, width, lens, dense):
+@pytest.mark.parametrize("lens,dense,pieces", _POOL_TOPK_CASES)
+def test_pool_topk_one_call_equals_the_two(H, width, lens, dense, pieces):
     """dapq_pool_topk against the oracle's pool followed by its top-K, for windows the selection kernel
     pools itself (<= 9), a window it does not (11), head lengths of every kernel variant and a ragged
     batch (sequence ends clip the window); with and without the pooled output."""
-    announce(f"pool+topk width={width} lens={lens} dense={dense}")
+    announce(f"pool+topk width={width} lens={lens} dense={dense} pieces={pieces}")
     r = np.random.default_rng(width * 1000 + len(lens))
     tot = sum(lens)
     S = (r.random((1, 2, tot)) ** 4).astype(np.float32)
@@ -319,13 +348,13 @@ def test_pool_topk_one_call_equals_the_two(H, width, lens, dense):
     q, k, v, cu = random_problem(4, 1, lens, 2, 2, 1)
     prob = H.Problem(q, k, v, 2, None if dense else cu, "thd")
     Sd = torch.from_numpy(S).cuda()
-    fusable = width <= 9 and (max(lens) if dense else tot) <= 65536
+    fusable = width <= 9 and ((max(lens) if dense else tot) <= 65536 or pieces)
     for budget, want_pooled in ((983, True), (64, False)):
         if not want_pooled and not fusable:
             with pytest.raises(H.D.DapqError):
-                prob.pool_topk(Sd, width, budget, None, False)
+                prob.pool_topk(Sd, width, budget, None, False, pieces)
             continue
-        idx, count, P = prob.pool_topk(Sd, width, budget, None, want_pooled)
+        idx, count, P = prob.pool_topk(Sd, width, budget, None, want_pooled, pieces)
         idx, count = idx.cpu().numpy(), count.cpu().numpy()
         for b in range(len(lens)):
             for kv in range(2):
