@@ -709,8 +709,7 @@ int launch_reg_radius(int radius, RegVariant v, dim3 grid, hipStream_t st, const
 }
 
 void launch_merge(RegVariant v, dim3 grid, hipStream_t st, const TopkParams& p) {
-  if (v.threads == 256 && v.kpt == 32) hipLaunchKernelGGL((topk_merge_kernel<256, 32>), grid, dim3(256), 0, st, p);
-  else if (v.threads == 256) hipLaunchKernelGGL((topk_merge_kernel<256, 64>), grid, dim3(256), 0, st, p);
+  if (v.threads == 256) hipLaunchKernelGGL((topk_merge_kernel<256, 32>), grid, dim3(256), 0, st, p);
   else if (v.kpt == 32) hipLaunchKernelGGL((topk_merge_kernel<1024, 32>), grid, dim3(1024), 0, st, p);
   else hipLaunchKernelGGL((topk_merge_kernel<1024, 64>), grid, dim3(1024), 0, st, p);
 }
@@ -786,7 +785,10 @@ int launch_long_heads(const dapq_shape* shape, const TopkRoute& r, TopkParams p,
     const int rc = launch_reg_radius(radius, RegVariant{1024, 32}, piece_grid, st, p);
     if (rc != DAPQ_OK) return rc;
     DAPQ_HIP_LAUNCH_CHECK("topk_reg_kernel (pieces)");
-    launch_merge(reg_variant_for((int64_t)r.n_segs * p.budget), grid, st, p);
+    // (one workgroup per long head: from 8193 candidate slots on, the large workgroup's sixteen waves)
+    const int64_t slots = (int64_t)r.n_segs * p.budget;
+    launch_merge(slots <= 256 * 32 ? RegVariant{256, 32} : (slots <= 1024 * 32 ? RegVariant{1024, 32} : RegVariant{1024, 64}),
+                 grid, st, p);
     DAPQ_HIP_LAUNCH_CHECK("topk_merge_kernel");
     return DAPQ_OK;
   }
