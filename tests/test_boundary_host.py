@@ -68,6 +68,23 @@ def test_workspace_bytes_over_a_sweep_of_shapes(lib):
     assert seen > 300
 
 
+def test_topk_workspace_bytes(lib):
+    """The optional workspace of the selection calls: nothing unless a head can be longer than 65536 keys; then two
+    candidate lists of heads x pieces x budget 4-byte entries and a count per piece (pieces of 32768 keys)."""
+    def align(n):
+        return (n + 255) // 256 * 256
+    assert D.topk_workspace_bytes(good_shape(), 983) == 0                                   # 4096 keys per head
+    assert D.topk_workspace_bytes(good_shape(total_tokens=65536), 983) == 0
+    long_heads = good_shape(n_layers=3, total_tokens=131072)                                # 3 x 1 x 8 heads, 4 pieces
+    assert D.topk_workspace_bytes(long_heads, 3932) == 2 * align(24 * 4 * 3932 * 4) + align(24 * 4 * 4)
+    assert D.topk_workspace_bytes(good_shape(total_tokens=65537), 5) == 2 * align(16 * 3 * 5 * 4) + align(16 * 3 * 4)
+    assert D.topk_workspace_bytes(long_heads, 20000) == 0          # 4 x 20000 candidates are more than a merge holds
+    assert D.topk_workspace_bytes(long_heads, 0) == 0
+    ragged = good_shape(batch=8, total_tokens=78821)
+    ragged.cu_seqlens = FAKE                                                                # never dereferenced here
+    assert D.topk_workspace_bytes(ragged, 512) == 2 * align(2 * 8 * 8 * 3 * 512 * 4) + align(2 * 8 * 8 * 3 * 4)
+
+
 FAKE = 0x1000  # never dereferenced: every call below must fail validation first
 
 
