@@ -74,17 +74,20 @@ def check_all_heads(ctx, w):
 
 
 @pytest.mark.parametrize("name,layers,samples", [
-    ("C2", None, [(0, 0), (17, 5), (31, 7)]),
+    ("C2", None, [(0, 0), (3, 2), (9, 6), (17, 5), (22, 1), (27, 4), (31, 3), (31, 7)]),
     # the 70B-class shape at its full 128k prompt, 2 of its 80 layers: 512 query rows per KV head (two row groups)
-    # and heads of 131072 keys, which take the streaming selection kernel and the separate pooling kernel
+    # and heads of 131072 keys, which the selection takes in four pieces of 32768 keys (pooling across the piece
+    # boundaries) and a merge of their candidates
     ("C5", 2, [(0, 3), (1, 7)]),
     # the same shape as the configuration names it: all 80 layers resident (21.5 GB of keys, as much of values), so
-    # that the key, value, score and index offsets of the last layers lie far beyond 4 GiB; heads of the first, a
-    # middle and the last layer against the oracle, every head through the properties
-    ("C5", None, [(0, 2), (40, 3), (79, 7)]),
-    # the ends of the window-size sweep at its 64k prompt, one layer each: 64 and 2048 query rows per KV head
-    ("C4:16", 1, [(0, 1)]),
-    ("C4:512", 1, [(0, 6)]),
+    # that the key, value, score and index offsets of the last layers lie far beyond 4 GiB; heads of the first,
+    # middle and last layers against the oracle, every head through the properties
+    ("C5", None, [(0, 2), (13, 0), (40, 3), (57, 6), (78, 1), (79, 7)]),
+    # the window-size sweep at its 64k prompt, one layer each: 64, 512, 1024 and 2048 query rows per KV head
+    ("C4:16", 1, [(0, 1), (0, 5)]),
+    ("C4:128", 1, [(0, 3)]),
+    ("C4:256", 1, [(0, 4)]),
+    ("C4:512", 1, [(0, 6), (0, 2)]),
 ])
 def test_full_size_dense_workload(env, name, layers, samples):
     bench, H = env
