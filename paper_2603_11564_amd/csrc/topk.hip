@@ -1,8 +1,8 @@
 // M_retain = TopK_j S(j) (Sec. 4.2): per (layer, sequence, KV head) the budget positions with the
 // largest pooled score, equal scores lowest position first, written in ascending position.
 //
-// One workgroup of 1024 threads per head.  Selection is an exact radix select on the
-// order-preserving integer image of the fp32 score: four 8-bit digits from the top, each pass a
+// One workgroup per head (256 threads for short heads, 1024 from 8193 keys on).  Selection is an exact radix
+// select on the order-preserving integer image of the fp32 score: four 8-bit digits from the top, each pass a
 // 256-bin LDS histogram followed by a suffix scan that fixes one digit of the threshold T and the
 // number of keys equal to T still needed.  The last step is an ordered compaction: key j is kept if
 // score > T, or score == T and fewer than `need` equal keys precede it; prefix counts of (greater,
@@ -19,8 +19,10 @@
 // owning the consecutive keys [t*KPT, (t+1)*KPT): every pass runs out of registers and the
 // compaction needs a single workgroup scan.  Because a thread holds a run of consecutive scores, the
 // same kernel can apply the max-pool that precedes selection (Sec. 1 / Sec. 5.1) on the way in
-// (dapq_pool_topk): three halo scores per side for the window of 7, no pooled array in HBM.  Longer heads (topk_stream_kernel) stage what fits in
-// LDS (36864 keys) or re-read the scores from L2 on every pass.
+// (dapq_pool_topk): three halo scores per side for the window of 7, no pooled array in HBM.
+// Longer heads go through the same kernel in pieces of 32768 keys, each leaving its survivors in candidate lists
+// (caller's workspace), and topk_merge_kernel selects among the candidates of a head; without the workspace
+// topk_stream_kernel stages what fits in LDS (36864 keys) or re-reads the scores on every pass.
 #include "dapq_internal.h"
 
 namespace dapq {
