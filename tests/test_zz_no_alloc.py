@@ -48,6 +48,27 @@ def test_static_scratch_matches_caller_workspace_twice_in_a_row():
     assert torch.equal(S_again, ref_big)
 
 
+def test_static_scratch_serves_a_ragged_batch():
+    """A ragged batch keeps a prefix of chunk counts and the ticket counter of its work list in the scratch array; both
+    are rewritten by every call, so calls in a row (another batch in between) give the scores of dapq_score."""
+    rng = np.random.default_rng(13)
+    lens = [700, 0, 45, 1300]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    q = O.f64_to_bf16_bits(rng.standard_normal((2, len(lens), 8, 32, 128)))
+    k = O.f64_to_bf16_bits(rng.standard_normal((2, int(cu[-1]), 2, 128)))
+    ragged = Problem(q, k, k, 2, cu, "thd", 128 ** -0.5)
+    dense = make_problem(14, layers=1, L=900, n_pseudo=16)
+    assert D.workspace_bytes(ragged.shape) <= D.score_static_capacity()
+    ref_ragged, ref_dense = ragged.score(), dense.score()
+    S1, S2, S3 = new_scores(ragged), new_scores(dense), new_scores(ragged)
+    D.dapq_score_static(ragged.shape, ragged.q, ragged.k, S1)
+    D.dapq_score_static(dense.shape, dense.q, dense.k, S2)
+    D.dapq_score_static(ragged.shape, ragged.q, ragged.k, S3)
+    torch.cuda.synchronize()
+    assert torch.equal(S1, ref_ragged) and torch.equal(S2, ref_dense) and torch.equal(S3, ref_ragged)
+    assert_scores_close(S1.cpu().numpy(), O.score(ragged.q_bits, ragged.k_bits, 2, cu, 128 ** -0.5), "static ragged")
+
+
 def test_static_scratch_refuses_what_does_not_fit():
     w = W.workload("C3")                                        # ragged batch: 134 MB of workspace
     cu = torch.zeros(w.batch + 1, dtype=torch.int32, device="cuda")
