@@ -310,6 +310,8 @@ def test_topk_long_heads_in_pieces(H, lens, dense, budget):
         prob = H.Problem(q, k, v, 2, None if dense else cu, "thd")
         assert H.D.topk_workspace_bytes(prob.shape, budget) == 0   # too many candidates: the streaming kernel serves
     _topk_case(H, lens, budget, P, dense=dense, pieces=True)
+    if not dense:   # per-sequence budgets, one of them 0, one larger than the common budget
+        _topk_case(H, lens, budget, P, per_seq=[100, 5, 0, 10 * budget, 0][:len(lens)], dense=False, pieces=True)
 
 
 @pytest.mark.parametrize("L,batch", [(8192, 1), (8193, 3), (16384, 2), (16385, 1), (20001, 2), (32767, 3), (32768, 1),
