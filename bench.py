@@ -320,7 +320,46 @@ def ceilings(ctx, args):
     out["passes_ms"] = {name: time_passes(ctx, shape, args.warmup, args.steps) for name, shape in placements.items()}
     out["passes_ns_per_slice"] = {name: {k: v * 1e6 / slices for k, v in r.items() if not k.endswith("_mhz")}
                                   for name, r in out["passes_ms"].items()}
+    # the key slab on chip across the passes: both passes over G layers at a time (G x 64 MiB of keys at C2, against
+    # the 256 MB memory-side cache), so that pass 2 finds the keys pass 1 just read; the same kernels, the planner
+    # choosing the chunks of each G-layer launch
+    if w.layout == "hnd" and w.batch == 1:
+        out["both_passes_ms_by_layer_group"] = time_layer_groups(ctx, args.warmup, max(1, args.steps // 6))
     return out
+
+
+def time_layer_groups(ctx, warm, reps):
+    """ms for pass 1 + pass 2 over all layers when they are run G layers at a time (pass 1 then pass 2 of a group,
+    then the next group), for several G; G = all layers is the two plain launches."""
+    import torch
+    D, w, stream = ctx.D, ctx.w, ctx.stream
+    res = {}
+    for G in (1, 2, 3, 4, 8, 16, w.n_layers):
+        if G > w.n_layers:
+            continue
+        sub = type(ctx.shape).from_buffer_copy(ctx.shape)
+        sub.n_layers = G
+        last = type(ctx.shape).from_buffer_copy(ctx.shape)
+        last.n_layers = w.n_layers % G
+        need = max(D.workspace_bytes(sub), D.workspace_bytes(last) if last.n_layers else 0)
+        ws = ctx.ws if need <= ctx.ws.numel() else torch.empty(need, dtype=torch.uint8, device=ctx.dev)
+
+        def sweep():
+            for l0 in range(0, w.n_layers, G):
+                shp = sub if l0 + G <= w.n_layers else last
+                l1 = l0 + shp.n_layers
+                D.dapq_score_stats(shp, ctx.q[l0:l1], ctx.k[l0:l1], ctx.lse2[l0:l1], ws, stream)
+                D.dapq_score_accumulate(shp, ctx.q[l0:l1], ctx.k[l0:l1], ctx.lse2[l0:l1], ctx.S[l0:l1], ws, stream)
+        for _ in range(max(1, warm // 4)):
+            sweep()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            sweep()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        res[f"{G}_layers_at_a_time"] = e0.elapsed_time(e1) / reps
+    return res
 
 
 class pseudo_query_problem:
