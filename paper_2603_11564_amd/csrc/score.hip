@@ -60,6 +60,7 @@ struct ScoreParams {
   int64_t total_tokens;
   int32_t n_layers, batch, n_q_heads, n_kv_heads, group, n_pseudo;
   int32_t rows, rows_pad, n_groups, chunk_keys, max_chunks;
+  int32_t wg_groups;          // row groups that sit side by side in a workgroup (dense launches; 1, 2 or 4)
   float c;  // scale * log2(e)
 };
 
@@ -252,12 +253,14 @@ __global__ void score_combine_kernel(ScoreParams p) {
 constexpr int kWaveStages1 = 5;           // pass 1: ring slots (40 KB per wave, 160 KB per compute unit)
 constexpr int kWaveStages2 = 5;           // pass 2: the same
 constexpr int kSubVec = kSubBytes / 16;   // 512 16-byte chunks per sub-block
-// A launch whose waves all fit the chip at once (one per SIMD: dense batches are planned that way) starts them
-// four to a workgroup, one per SIMD of a compute unit, each with its own chunk and its own ring: they share nothing
-// and never meet at a barrier, but the dispatcher places a quarter as many workgroups, which lets the stream-bound
-// shapes (few query rows) start faster (2-3 % there; nothing at 256 rows).  Every other launch keeps one wave per
-// workgroup: a workgroup holds its LDS until its last wave is done, so queued workgroups would leave SIMDs idle.
-// (Ragged batches: see the DYN form of the kernels.)
+// Dense launches start their waves up to four to a workgroup, one per SIMD of a compute unit, each with its own ring:
+// they never meet at a barrier.  The waves of a workgroup are the row groups of a chunk side by side (a KV head with
+// more than 256 query rows: they read the same keys at the same time, and the second reader finds them in the compute
+// unit's L2 instead of fetching them through the fabric again: 6 % at 512 and 1024 rows) and then consecutive chunks
+// (the dispatcher places fewer workgroups and the waves of a compute unit read one head's queries once: 2-3 % for the
+// stream-bound shapes).  Every workgroup must be full -- waves of a half-empty one would idle their SIMDs for the whole
+// launch -- so the number of consecutive chunks is the largest of 4, 2, 1 (divided by the row groups) that divides
+// the chunk count.  (Ragged batches: see the DYN form of the kernels.)
 constexpr int kWavesPerGroup = 4;
 constexpr int kWaveLds1 = kWaveStages1 * kSubBytes;
 constexpr int kWaveLds2 = kWaveStages2 * kSubBytes;
@@ -627,6 +630,20 @@ __device__ __forceinline__ unsigned pass1_item(const ScoreParams& p, u32x4* ring
   return next;
 }
 
+// Which (chunk, row group) a wave of a dense launch works on.  The waves of a workgroup take p.wg_groups row groups of
+// the same chunk side by side, then the next chunk: the row groups of a chunk read the same keys at the same time, and
+// in one compute unit the second reader finds them in L2 instead of fetching them through the fabric again.
+struct WaveSlot {
+  int chunk, group;
+};
+__device__ __forceinline__ WaveSlot wave_slot(const ScoreParams& p, int wave_id) {
+  const int waves = (int)(blockDim.x >> 6), gpw = p.wg_groups, cpw = waves / gpw;
+  WaveSlot s;
+  s.chunk = uniform_i32((int)blockIdx.x * cpw + wave_id / gpw);
+  s.group = uniform_i32((int)blockIdx.y * gpw + wave_id % gpw);
+  return s;
+}
+
 // DYN = false (dense batches): the grid names the items, one per wave: (chunk, row group, layer x KV head).
 // DYN = true (ragged batches, whose lengths the host does not know): one persistent wave per SIMD takes items from a
 // work list in device memory until it is empty.  Items are numbered so that consecutive ones share the KV head, the
@@ -642,9 +659,9 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 1) void score_wave_pass1_kerne
   sub_dma_lane_offsets(voff, p.k_stride_token, lane);
   bf16x8 qf[NRB][8];
   if (!DYN) {
-    const int chunk_id = (int)blockIdx.x * (int)(blockDim.x >> 6) + wave_id;
-    if (locate_uniform(p, chunk_id).nkeys == 0) return;
-    pass1_item<NRB, true>(p, ring, chunk_id, (int)blockIdx.y, (int)blockIdx.z, qf, voff, lane, nullptr);
+    const WaveSlot slot = wave_slot(p, wave_id);
+    if (locate_uniform(p, slot.chunk).nkeys == 0) return;
+    pass1_item<NRB, true>(p, ring, slot.chunk, slot.group, (int)blockIdx.z, qf, voff, lane, nullptr);
     return;
   }
   const ItemList items = item_list(p);
@@ -742,9 +759,9 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 1) void score_wave_pass2_kerne
   bf16x8 qf[NRB][8];
   float off2[NRB][16];
   if (!DYN) {
-    const int chunk_id = (int)blockIdx.x * (int)(blockDim.x >> 6) + wave_id;
-    if (locate_uniform(p, chunk_id).nkeys == 0) return;
-    pass2_item<NRB, true>(p, ring, chunk_id, (int)blockIdx.y, (int)(gridDim.z - 1 - blockIdx.z), qf, off2, voff, lane, nullptr);
+    const WaveSlot slot = wave_slot(p, wave_id);
+    if (locate_uniform(p, slot.chunk).nkeys == 0) return;
+    pass2_item<NRB, true>(p, ring, slot.chunk, slot.group, (int)(gridDim.z - 1 - blockIdx.z), qf, off2, voff, lane, nullptr);
     return;
   }
   const ItemList items = item_list(p);
@@ -849,10 +866,22 @@ int simd_count() {
   return simds[dev];
 }
 
-// Waves per workgroup for a launch of `waves` waves in `chunks` chunks along the key axis (see kWavesPerGroup; the
-// waves of a workgroup take consecutive chunks, so the chunk count has to be a multiple or SIMDs would sit idle).
-int waves_per_group(const dapq_shape* s, int64_t waves, int64_t chunks) {
-  return (s->cu_seqlens == nullptr && waves <= simd_count() && chunks % kWavesPerGroup == 0) ? kWavesPerGroup : 1;
+// How a dense launch packs its waves into workgroups: `waves` to a workgroup (kWavesPerGroup or 1), of which `groups`
+// are the row groups of one chunk side by side (see wave_slot) and waves / groups consecutive chunks.
+struct GroupShape {
+  int waves, groups;
+  dim3 grid(const ScorePlan& plan, const dapq_shape* s) const {
+    const int cpw = waves / groups;
+    return dim3((unsigned)((plan.max_chunks + cpw - 1) / cpw), (unsigned)(plan.n_groups / groups),
+                (unsigned)(s->n_layers * s->n_kv_heads));
+  }
+};
+GroupShape group_shape(const dapq_shape* s, const ScorePlan& plan) {
+  if (s->cu_seqlens != nullptr) return {1, 1};
+  const int groups = plan.n_groups % 4 == 0 ? 4 : (plan.n_groups % 2 == 0 ? 2 : 1);
+  int chunks = kWavesPerGroup / groups;  // consecutive chunks in a workgroup: every workgroup must be full
+  while (chunks > 1 && plan.max_chunks % chunks != 0) chunks /= 2;
+  return {groups * chunks, groups};
 }
 
 int fill_params(const dapq_shape* s, const ScorePlan& plan, ScoreParams* p) {
@@ -866,6 +895,7 @@ int fill_params(const dapq_shape* s, const ScorePlan& plan, ScoreParams* p) {
   p->group = s->n_q_heads / s->n_kv_heads; p->n_pseudo = s->n_pseudo;
   p->rows = plan.rows; p->rows_pad = plan.rows_pad; p->n_groups = plan.n_groups;
   p->chunk_keys = plan.chunk_keys; p->max_chunks = (int32_t)plan.max_chunks;
+  p->wg_groups = 1;
   p->c = s->scale * 1.4426950408889634f;
   return DAPQ_OK;
 }
@@ -884,13 +914,14 @@ int launch_stats(const dapq_shape* s, const ScorePlan& plan, ScoreParams p, hipS
   }
   int rc = DAPQ_OK;
   const int64_t waves = plan.max_chunks * plan.n_groups * s->n_layers * s->n_kv_heads;
-  const int wpg = waves_per_group(s, waves, plan.max_chunks);
+  const GroupShape gs = group_shape(s, plan);
+  const int wpg = gs.waves;
+  p.wg_groups = gs.groups;
   // ragged: persistent waves, one per SIMD, take their chunks from a work list (32-bit tickets)
   const bool dyn = s->cu_seqlens != nullptr && waves < ((int64_t)1 << 31);
   const int simds = simd_count();
   const dim3 dyn_grid((unsigned)(waves < simds ? waves : simds));
-  const dim3 grid((unsigned)((plan.max_chunks + wpg - 1) / wpg), (unsigned)plan.n_groups,
-                  (unsigned)(s->n_layers * s->n_kv_heads));
+  const dim3 grid = gs.grid(plan, s);
 #define DAPQ_LAUNCH_W1(NRBV)                                                                                        \
   do {                                                                                                              \
     if (dyn) {                                                                                                      \
@@ -921,13 +952,14 @@ int launch_accumulate(const dapq_shape* s, const ScorePlan& plan, ScoreParams p,
   }
   int rc = DAPQ_OK;
   const int64_t waves = plan.max_chunks * plan.n_groups * s->n_layers * s->n_kv_heads;
-  const int wpg = waves_per_group(s, waves, plan.max_chunks);
+  const GroupShape gs = group_shape(s, plan);
+  const int wpg = gs.waves;
+  p.wg_groups = gs.groups;
   // ragged: persistent waves, one per SIMD, take their chunks from a work list (32-bit tickets)
   const bool dyn = s->cu_seqlens != nullptr && waves < ((int64_t)1 << 31);
   const int simds = simd_count();
   const dim3 dyn_grid((unsigned)(waves < simds ? waves : simds));
-  const dim3 grid((unsigned)((plan.max_chunks + wpg - 1) / wpg), (unsigned)plan.n_groups,
-                  (unsigned)(s->n_layers * s->n_kv_heads));
+  const dim3 grid = gs.grid(plan, s);
 #define DAPQ_LAUNCH_W2(NRBV)                                                                                        \
   do {                                                                                                              \
     if (dyn) {                                                                                                      \
