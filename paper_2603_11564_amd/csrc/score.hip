@@ -45,12 +45,14 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));  // 16 bytes; native vector, stays in registers
 
+constexpr int kLists = 8;  // work lists of a ragged batch, one per XCD (see ItemLists)
+
 struct ScoreParams {
   const uint16_t* q;
   const uint16_t* k;
   const int32_t* cu_seqlens;  // NULL = dense
   int32_t* cu_chunks;         // [batch+1] prefix of per-sequence chunk counts (ragged only)
-  unsigned* work;             // ragged only: the next (head, row group, chunk) item to hand out; zeroed with cu_chunks
+  unsigned* work;             // ragged only: [kLists] next ticket of every work list; zeroed with cu_chunks
   float2* parts;              // [layer*Hkv][max_chunks][rows_pad] (reference, sum) in the log2 domain
   float* lse2;                // [layer][batch][Hq][N]
   float* scores;              // [layer][Hkv][total_tokens]
@@ -189,10 +191,8 @@ __device__ __forceinline__ bf16x8 lds_read16(unsigned lane_addr, int const_off) 
 __global__ void score_chunk_prefix_kernel(const int32_t* cu_seqlens, int32_t* cu_chunks, unsigned* work,
                                          int batch, int chunk_keys) {
   const int lane = threadIdx.x;  // launched with exactly 64 threads
-  if (lane == 0) {
-    cu_chunks[0] = 0;
-    *work = 0u;  // the pass that follows hands its items out from here
-  }
+  if (lane == 0) cu_chunks[0] = 0;
+  if (lane < kLists) work[lane] = 0u;  // the pass that follows hands its items out from here (one counter per work list)
   int carry = 0;
   for (int b0 = 0; b0 < batch; b0 += 64) {
     const int b = b0 + lane;
@@ -250,8 +250,11 @@ __global__ void score_combine_kernel(ScoreParams p) {
 // ---------------------------------------------------------------------------------------------
 // The score kernels: one wave = a group of query rows x its own key stream.
 // ---------------------------------------------------------------------------------------------
-constexpr int kWaveStages1 = 5;           // pass 1: ring slots (40 KB per wave, 160 KB per compute unit)
-constexpr int kWaveStages2 = 5;           // pass 2: the same
+constexpr int kWaveStages = 5;            // ring slots (40 KB per wave, 160 KB per compute unit)
+// Persistent workgroups of several waves (ragged batches with more than 256 query rows per KV head) need a few bytes
+// of LDS to pass tickets around, which five slots per wave leave no room for; the ring depth makes no measurable
+// difference between 3 and 5.
+constexpr int kTeamStages = 4;
 constexpr int kSubVec = kSubBytes / 16;   // 512 16-byte chunks per sub-block
 // Dense launches start their waves up to four to a workgroup, one per SIMD of a compute unit, each with its own ring:
 // they never meet at a barrier.  The waves of a workgroup are the row groups of a chunk side by side (a KV head with
@@ -262,8 +265,7 @@ constexpr int kSubVec = kSubBytes / 16;   // 512 16-byte chunks per sub-block
 // launch -- so the number of consecutive chunks is the largest of 4, 2, 1 (divided by the row groups) that divides
 // the chunk count.  (Ragged batches: see the DYN form of the kernels.)
 constexpr int kWavesPerGroup = 4;
-constexpr int kWaveLds1 = kWaveStages1 * kSubBytes;
-constexpr int kWaveLds2 = kWaveStages2 * kSubBytes;
+constexpr int wave_lds(int nst) { return nst * kSubBytes; }
 
 // Per-lane byte offsets of the four distinct 16-byte chunks a lane fetches in sub_dma: transfer i
 // moves key rows 4i..4i+3, lane (row0 = lane / 16, pos = lane % 16) fills LDS position pos of row
@@ -510,42 +512,83 @@ __device__ __forceinline__ unsigned take_item(unsigned* work, int lane) {
   return (unsigned)uniform_i32((int)v);
 }
 
-// The work list of a ragged batch: item = (head * row groups + group) * chunks + chunk, so that consecutive items
-// share the KV head, the row group and mostly the sequence.  (The host launches this form only if the item count
-// fits 31 bits whatever the lengths are.)
+// The work lists of a ragged batch: one per XCD (kLists of them: each XCD has its own L2).  List x holds the chunks c of
+// the packed key axis with c mod kLists == x, for every head and every block of row groups; ticket t of list x is item
+// ((head * chunks_x + c') * blocks + block) with c = c' * kLists + x.  A block is the row groups that the waves of one
+// workgroup (a team) take side by side: they read the same keys at the same time, so the second reader finds them in
+// the compute unit's L2 and the keys go through the fabric once.  A team takes tickets from the list of the XCD it
+// runs on (consecutive tickets are blocks of the same chunk: the same keys again, behind the same L2); when that list is
+// empty it goes on to the others', so every list is drained whatever runs where.  (The host launches this form only
+// if the item count fits 31 bits whatever the lengths are.)
 struct Item {
-  int head, group, chunk, seq, nkeys;
+  int head, block, chunk, seq, nkeys;
 };
-struct ItemList {
-  unsigned chunks, per_head, heads, total;
+struct ItemLists {
+  unsigned chunks, blocks, heads;
+  __device__ __forceinline__ unsigned chunks_of(int x) const { return (chunks + (unsigned)(kLists - 1 - x)) / kLists; }
+  __device__ __forceinline__ unsigned count(int x) const { return heads * chunks_of(x) * blocks; }
   // `reversed`: heads and chunks from the far end (pass 2)
-  __device__ __forceinline__ Item at(const ScoreParams& p, unsigned item, bool reversed) const {
-    const unsigned head = uniform_u32(item / per_head), rest = item - head * per_head;
-    const unsigned group = uniform_u32(rest / chunks), chunk = rest - group * chunks;
+  __device__ __forceinline__ Item at(const ScoreParams& p, int x, unsigned ticket, bool reversed) const {
+    const unsigned cx = chunks_of(x);
+    const unsigned u = uniform_u32(ticket / blocks), block = ticket - u * blocks;
+    const unsigned head = uniform_u32(u / cx), c = u - head * cx;
     Item it;
     it.head = (int)(reversed ? heads - 1 - head : head);
-    it.group = (int)group;
-    it.chunk = (int)(reversed ? chunks - 1 - chunk : chunk);
+    it.block = (int)block;
+    it.chunk = (int)((reversed ? cx - 1 - c : c) * kLists + (unsigned)x);
     const Work w = locate_uniform(p, it.chunk);
     it.seq = w.seq;
     it.nkeys = w.nkeys;
     return it;
   }
 };
-__device__ __forceinline__ ItemList item_list(const ScoreParams& p) {
-  ItemList l;
+__device__ __forceinline__ ItemLists item_lists(const ScoreParams& p) {
+  ItemLists l;
   l.chunks = (unsigned)uniform_i32(p.cu_chunks[p.batch]);
-  l.per_head = l.chunks * (unsigned)p.n_groups;
+  l.blocks = (unsigned)(p.n_groups / p.wg_groups);
   l.heads = (unsigned)(p.n_layers * p.n_kv_heads);
-  l.total = l.per_head * l.heads;
   return l;
 }
 
+// The tickets of a team.  A team of one wave keeps its ticket in a register; in a larger team wave 0 takes the ticket and
+// leaves it in one of two LDS words (behind the rings), which the others read after the barrier that starts the item:
+// the slots alternate, so a slot is rewritten only after two more barriers.
+struct TeamTickets {
+  unsigned* slots;  // LDS, two words (teams of more than one wave)
+  unsigned mine;    // team of one: the ticket
+  int parity;
+  bool team, leader;
+  __device__ __forceinline__ void post(unsigned ticket, int lane) {
+    if (!team) mine = ticket;
+    else if (leader && lane == 0) slots[parity] = ticket;
+  }
+  __device__ __forceinline__ unsigned next() {
+    if (!team) return mine;
+    __syncthreads();
+    const unsigned t = uniform_u32(slots[parity]);
+    parity ^= 1;
+    return t;
+  }
+};
+__device__ __forceinline__ TeamTickets team_tickets(u32x4* rings, int nst, int wave_id) {
+  TeamTickets t;
+  const int waves = (int)(blockDim.x >> 6);
+  t.slots = reinterpret_cast<unsigned*>(rings + waves * (wave_lds(nst) / 16));
+  t.mine = 0;
+  t.parity = 0;
+  t.team = waves > 1;
+  t.leader = wave_id == 0;
+  return t;
+}
+// The XCD this wave runs on (hardware register XCC_ID, bits 3:0).
+__device__ __forceinline__ int home_list() {
+  return (int)(__builtin_amdgcn_s_getreg(20 | (0 << 6) | ((4 - 1) << 11)) & (unsigned)(kLists - 1));
+}
+
 // Pass 1 of one chunk: `head` = layer * n_kv_heads + KV head, `group` = row group, `chunk_id` = chunk along the packed
-// key axis.  LOAD_Q: fetch the query fragments first (otherwise qf holds them already: same head, row group and
-// sequence as the wave's last chunk).  If `work` is not NULL the ticket for the wave's next item is taken while the
-// chunk drains (so its round trip costs nothing) and returned.  The chunk must have keys.
-template <int NRB, bool LOAD_Q>
+// key axis.  If `work` is not NULL the ticket for the wave's next item is taken from it while the chunk drains (so
+// its round trip costs nothing) and returned.  The chunk must have keys.
+template <int NRB, int NST>
 __device__ __forceinline__ unsigned pass1_item(const ScoreParams& p, u32x4* ring, int chunk_id, int group, int head,
                                                bf16x8 (&qf)[NRB][8], const unsigned (&voff)[4], int lane,
                                                unsigned* work) {
@@ -561,12 +604,10 @@ __device__ __forceinline__ unsigned pass1_item(const ScoreParams& p, u32x4* ring
   const int nsubs = (w.nkeys + 31) / 32, nfull = w.nkeys / 32;
   // the ring is filled whether the sub-blocks exist or not (sub_dma): the waits count operations
 #pragma unroll
-  for (int i = 0; i < kWaveStages1; ++i) sub_dma(ring + i * kSubVec, kbase, p.k_stride_token, i * 32, w.nkeys, voff);
-  if (LOAD_Q) {
+  for (int i = 0; i < NST; ++i) sub_dma(ring + i * kSubVec, kbase, p.k_stride_token, i * 32, w.nkeys, voff);
 #pragma unroll
-    for (int rb = 0; rb < NRB; ++rb) frag_from_q(qf[rb], p, qbase, gbase + rb * 32 + n, h);
-    if (NRB == 8) pin_q_in_agprs<NRB>(qf);
-  }
+  for (int rb = 0; rb < NRB; ++rb) frag_from_q(qf[rb], p, qbase, gbase + rb * 32 + n, h);
+  if (NRB == 8) pin_q_in_agprs<NRB>(qf);
 
   float ref[NRB], z[NRB];
 #pragma unroll
@@ -575,20 +616,20 @@ __device__ __forceinline__ unsigned pass1_item(const ScoreParams& p, u32x4* ring
     z[rb] = 0.0f;
   }
   bf16x8 kf[8];
-  wait_subblocks(kWaveStages1 - 1);
+  wait_subblocks(NST - 1);
   wave_load_frags<NRB>(kf, ring, n, h);
   // sub-block 0 the plain way: it fixes the reference logits
   wave_sub_simple<NRB, false, true>(kf, qf, p.c, ref, z, 0, w.nkeys, h);
   if (nsubs > 1) {
-    wait_subblocks(kWaveStages1 - 2);
+    wait_subblocks(NST - 2);
     wave_load_frags<NRB>(kf, ring + kSubVec, n, h);
-    sub_dma(ring, kbase, p.k_stride_token, kWaveStages1 * 32, w.nkeys, voff);  // slot 0 is free
+    sub_dma(ring, kbase, p.k_stride_token, NST * 32, w.nkeys, voff);  // slot 0 is free
     if (nfull > 1) {
       float off[NRB], zs[NRB];
 #pragma unroll
       for (int rb = 0; rb < NRB; ++rb) off[rb] = -ref[rb];
       const float no_off2[1][16] = {};
-      wave_walk<NRB, 1, kWaveStages1>(ring, kbase, p.k_stride_token, w.nkeys, 1, nfull, kf, qf, p.c, off, no_off2, zs,
+      wave_walk<NRB, 1, NST>(ring, kbase, p.k_stride_token, w.nkeys, 1, nfull, kf, qf, p.c, off, no_off2, zs,
                                       nullptr, voff, n, h);
 #pragma unroll
       for (int rb = 0; rb < NRB; ++rb) z[rb] += zs[rb];
@@ -645,15 +686,14 @@ __device__ __forceinline__ WaveSlot wave_slot(const ScoreParams& p, int wave_id)
 }
 
 // DYN = false (dense batches): the grid names the items, one per wave: (chunk, row group, layer x KV head).
-// DYN = true (ragged batches, whose lengths the host does not know): one persistent wave per SIMD takes items from a
-// work list in device memory until it is empty.  Items are numbered so that consecutive ones share the KV head, the
-// row group and mostly the sequence -- a wave that takes several in a row loads its query fragments once -- and a short
-// chunk costs a ticket and a ring refill instead of a workgroup launch; the hand-out also evens out the ragged tail.
-template <int NRB, bool DYN>
+// DYN = true (ragged batches, whose lengths the host does not know): one persistent wave per SIMD takes items from
+// work lists in device memory until they are empty (see ItemLists).  A short chunk costs a ticket and a ring refill
+// instead of a workgroup launch; the hand-out also evens out the ragged tail.
+template <int NRB, bool DYN, int NST>
 __global__ __launch_bounds__(64 * kWavesPerGroup, 1) void score_wave_pass1_kernel(ScoreParams p) {
   extern __shared__ u32x4 rings[];
   const int wave_id = uniform_i32((int)(threadIdx.x >> 6));
-  u32x4* ring = rings + wave_id * (kWaveLds1 / 16);
+  u32x4* ring = rings + wave_id * (wave_lds(NST) / 16);
   const int lane = threadIdx.x & 63;
   unsigned voff[4];
   sub_dma_lane_offsets(voff, p.k_stride_token, lane);
@@ -661,28 +701,33 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 1) void score_wave_pass1_kerne
   if (!DYN) {
     const WaveSlot slot = wave_slot(p, wave_id);
     if (locate_uniform(p, slot.chunk).nkeys == 0) return;
-    pass1_item<NRB, true>(p, ring, slot.chunk, slot.group, (int)blockIdx.z, qf, voff, lane, nullptr);
+    pass1_item<NRB, NST>(p, ring, slot.chunk, slot.group, (int)blockIdx.z, qf, voff, lane, nullptr);
     return;
   }
-  const ItemList items = item_list(p);
-  unsigned item = take_item(p.work, lane);
-  while (item < items.total) {  // every wave leaves: the tickets only grow
-    const Item a = items.at(p, item, false);
-    if (a.nkeys == 0) {  // (no chunk of the list is empty; if one were, it would only cost its ticket)
-      item = take_item(p.work, lane);
-      continue;
-    }
-    item = pass1_item<NRB, true>(p, ring, a.chunk, a.group, a.head, qf, voff, lane, p.work);
-    while (item < items.total) {  // the run of items that use the same queries
-      const Item b = items.at(p, item, false);
-      if (b.head != a.head || b.group != a.group || b.seq != a.seq || b.nkeys == 0) break;
-      item = pass1_item<NRB, false>(p, ring, b.chunk, b.group, b.head, qf, voff, lane, p.work);
+  const ItemLists lists = item_lists(p);
+  const int home = home_list();
+  TeamTickets tickets = team_tickets(rings, NST, wave_id);
+  for (int k = 0; k < kLists; ++k) {  // this XCD's list first, then the others: no list is left undrained
+    const int x = (home + k) & (kLists - 1);
+    unsigned* work = tickets.leader ? p.work + x : nullptr;  // (only the leader of a team takes tickets)
+    const unsigned n_items = lists.count(x);
+    tickets.post(work != nullptr ? take_item(work, lane) : 0u, lane);
+    for (;;) {  // every team leaves: the tickets only grow
+      const unsigned ticket = tickets.next();
+      if (ticket >= n_items) break;
+      const Item a = lists.at(p, x, ticket, false);
+      if (a.nkeys == 0) {  // (no chunk of a list is empty; if one were, it would only cost its ticket)
+        tickets.post(work != nullptr ? take_item(work, lane) : 0u, lane);
+        continue;
+      }
+      tickets.post(pass1_item<NRB, NST>(p, ring, a.chunk, a.block * p.wg_groups + wave_id, a.head, qf, voff, lane, work),
+                   lane);
     }
   }
 }
 
 // Pass 2 of one chunk (arguments as pass1_item).
-template <int NRB, bool LOAD_Q>
+template <int NRB, int NST>
 __device__ __forceinline__ unsigned pass2_item(const ScoreParams& p, u32x4* ring, int chunk_id, int group, int head,
                                                bf16x8 (&qf)[NRB][8], float (&off2)[NRB][16],
                                                const unsigned (&voff)[4], int lane, unsigned* work) {
@@ -702,9 +747,9 @@ __device__ __forceinline__ unsigned pass2_item(const ScoreParams& p, u32x4* ring
   float* out = const_cast<float*>(uniform_ptr(plane + ((int64_t)layer * p.n_kv_heads + kv) * p.total_tokens + w.tok0));
   const int nsubs = (w.nkeys + 31) / 32;
 #pragma unroll
-  for (int i = 0; i < kWaveStages2; ++i)
+  for (int i = 0; i < NST; ++i)
     sub_dma(ring + i * kSubVec, kbase, p.k_stride_token, (nsubs - 1 - i) * 32, w.nkeys, voff);
-  if (LOAD_Q) {
+  {
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) frag_from_q(qf[rb], p, qbase, gbase + rb * 32 + n, h);
     if (NRB == 8) pin_q_in_agprs<NRB>(qf);
@@ -733,12 +778,12 @@ __device__ __forceinline__ unsigned pass2_item(const ScoreParams& p, u32x4* ring
     }
   }
   bf16x8 kf[8];
-  wait_subblocks(kWaveStages2 - 1);
+  wait_subblocks(NST - 1);
   wave_load_frags<NRB>(kf, ring, n, h);
   float unused_off[NRB], unused_acc[NRB];
 #pragma unroll
   for (int rb = 0; rb < NRB; ++rb) unused_off[rb] = 0.0f;
-  wave_walk<NRB, 2, kWaveStages2, true>(ring, kbase, p.k_stride_token, w.nkeys, 0, nsubs, kf, qf, p.c, unused_off, off2,
+  wave_walk<NRB, 2, NST, true>(ring, kbase, p.k_stride_token, w.nkeys, 0, nsubs, kf, qf, p.c, unused_off, off2,
                                         unused_acc, out, voff, n, h, nsubs - 1);
   const unsigned next = work != nullptr ? take_item(work, lane) : 0u;
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -748,11 +793,11 @@ __device__ __forceinline__ unsigned pass2_item(const ScoreParams& p, u32x4* ring
 // (DYN as in pass 1.)  Heads and, inside a chunk, the keys are walked in the opposite order to pass 1: what pass 1
 // read last (the ends of the chunks in flight, the heads of the last round) is still in the 256 MB memory-side cache
 // when pass 2 starts.
-template <int NRB, bool DYN>
+template <int NRB, bool DYN, int NST>
 __global__ __launch_bounds__(64 * kWavesPerGroup, 1) void score_wave_pass2_kernel(ScoreParams p) {
   extern __shared__ u32x4 rings[];
   const int wave_id = uniform_i32((int)(threadIdx.x >> 6));
-  u32x4* ring = rings + wave_id * (kWaveLds2 / 16);
+  u32x4* ring = rings + wave_id * (wave_lds(NST) / 16);
   const int lane = threadIdx.x & 63;
   unsigned voff[4];
   sub_dma_lane_offsets(voff, p.k_stride_token, lane);
@@ -761,22 +806,27 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 1) void score_wave_pass2_kerne
   if (!DYN) {
     const WaveSlot slot = wave_slot(p, wave_id);
     if (locate_uniform(p, slot.chunk).nkeys == 0) return;
-    pass2_item<NRB, true>(p, ring, slot.chunk, slot.group, (int)(gridDim.z - 1 - blockIdx.z), qf, off2, voff, lane, nullptr);
+    pass2_item<NRB, NST>(p, ring, slot.chunk, slot.group, (int)(gridDim.z - 1 - blockIdx.z), qf, off2, voff, lane, nullptr);
     return;
   }
-  const ItemList items = item_list(p);
-  unsigned item = take_item(p.work, lane);
-  while (item < items.total) {
-    const Item a = items.at(p, item, true);
-    if (a.nkeys == 0) {
-      item = take_item(p.work, lane);
-      continue;
-    }
-    item = pass2_item<NRB, true>(p, ring, a.chunk, a.group, a.head, qf, off2, voff, lane, p.work);
-    while (item < items.total) {
-      const Item b = items.at(p, item, true);
-      if (b.head != a.head || b.group != a.group || b.seq != a.seq || b.nkeys == 0) break;
-      item = pass2_item<NRB, false>(p, ring, b.chunk, b.group, b.head, qf, off2, voff, lane, p.work);
+  const ItemLists lists = item_lists(p);
+  const int home = home_list();
+  TeamTickets tickets = team_tickets(rings, NST, wave_id);
+  for (int k = 0; k < kLists; ++k) {  // this XCD's list first, then the others: no list is left undrained
+    const int x = (home + k) & (kLists - 1);
+    unsigned* work = tickets.leader ? p.work + x : nullptr;  // (only the leader of a team takes tickets)
+    const unsigned n_items = lists.count(x);
+    tickets.post(work != nullptr ? take_item(work, lane) : 0u, lane);
+    for (;;) {  // every team leaves: the tickets only grow
+      const unsigned ticket = tickets.next();
+      if (ticket >= n_items) break;
+      const Item a = lists.at(p, x, ticket, true);
+      if (a.nkeys == 0) {  // (no chunk of a list is empty; if one were, it would only cost its ticket)
+        tickets.post(work != nullptr ? take_item(work, lane) : 0u, lane);
+        continue;
+      }
+      tickets.post(pass2_item<NRB, NST>(p, ring, a.chunk, a.block * p.wg_groups + wave_id, a.head, qf, off2, voff, lane, work),
+                   lane);
     }
   }
 }
@@ -884,6 +934,9 @@ GroupShape group_shape(const dapq_shape* s, const ScorePlan& plan) {
   return {groups * chunks, groups};
 }
 
+// Waves of a persistent team of a ragged launch: the row groups of a chunk side by side (see ItemLists).
+int team_size(const ScorePlan& plan) { return plan.n_groups % 4 == 0 ? 4 : (plan.n_groups % 2 == 0 ? 2 : 1); }
+
 int fill_params(const dapq_shape* s, const ScorePlan& plan, ScoreParams* p) {
   p->cu_seqlens = s->cu_seqlens;
   p->k_stride_layer = s->k_stride_layer; p->k_stride_seq = s->k_stride_seq;
@@ -916,20 +969,32 @@ int launch_stats(const dapq_shape* s, const ScorePlan& plan, ScoreParams p, hipS
   const int64_t waves = plan.max_chunks * plan.n_groups * s->n_layers * s->n_kv_heads;
   const GroupShape gs = group_shape(s, plan);
   const int wpg = gs.waves;
-  p.wg_groups = gs.groups;
-  // ragged: persistent waves, one per SIMD, take their chunks from a work list (32-bit tickets)
+  // ragged: persistent teams (one wave per SIMD; a team = the row groups of a chunk side by side) take their chunks
+  // from work lists (32-bit tickets)
   const bool dyn = s->cu_seqlens != nullptr && waves < ((int64_t)1 << 31);
-  const int simds = simd_count();
-  const dim3 dyn_grid((unsigned)(waves < simds ? waves : simds));
+  const int team = dyn ? team_size(plan) : 1;
+  p.wg_groups = dyn ? team : gs.groups;
+  const int64_t teams = waves / team, team_slots = simd_count() / team;
+  const dim3 dyn_grid((unsigned)(teams < team_slots ? teams : team_slots));
   const dim3 grid = gs.grid(plan, s);
 #define DAPQ_LAUNCH_W1(NRBV)                                                                                        \
   do {                                                                                                              \
-    if (dyn) {                                                                                                      \
-      if ((rc = set_lds(score_wave_pass1_kernel<NRBV, true>, kWaveLds1)) != DAPQ_OK) return rc;                      \
-      hipLaunchKernelGGL((score_wave_pass1_kernel<NRBV, true>), dyn_grid, dim3(64), kWaveLds1, stream, p);           \
+    if (dyn && team > 1) { /* (more than 256 rows: eight row blocks per wave) */                                    \
+      const int lds = team * wave_lds(kTeamStages) + 16;                                                            \
+      if ((rc = set_lds(score_wave_pass1_kernel<8, true, kTeamStages>, kWavesPerGroup * wave_lds(kTeamStages) + 16)) != \
+          DAPQ_OK)                                                                                                  \
+        return rc;                                                                                                  \
+      hipLaunchKernelGGL((score_wave_pass1_kernel<8, true, kTeamStages>), dyn_grid, dim3(64 * team), lds, stream, p);   \
+    } else if (dyn) {                                                                                               \
+      if ((rc = set_lds(score_wave_pass1_kernel<NRBV, true, kWaveStages>, wave_lds(kWaveStages))) != DAPQ_OK) return rc; \
+      hipLaunchKernelGGL((score_wave_pass1_kernel<NRBV, true, kWaveStages>), dyn_grid, dim3(64), wave_lds(kWaveStages), \
+                         stream, p);                                                                                \
     } else {                                                                                                        \
-      if ((rc = set_lds(score_wave_pass1_kernel<NRBV, false>, kWavesPerGroup * kWaveLds1)) != DAPQ_OK) return rc;    \
-      hipLaunchKernelGGL((score_wave_pass1_kernel<NRBV, false>), grid, dim3(64 * wpg), wpg * kWaveLds1, stream, p);  \
+      if ((rc = set_lds(score_wave_pass1_kernel<NRBV, false, kWaveStages>, kWavesPerGroup * wave_lds(kWaveStages))) !=  \
+          DAPQ_OK)                                                                                                  \
+        return rc;                                                                                                  \
+      hipLaunchKernelGGL((score_wave_pass1_kernel<NRBV, false, kWaveStages>), grid, dim3(64 * wpg),                     \
+                         wpg * wave_lds(kWaveStages), stream, p);                                                   \
     }                                                                                                               \
   } while (0)
   if (plan.row_blocks == 2) DAPQ_LAUNCH_W1(2);
@@ -954,20 +1019,32 @@ int launch_accumulate(const dapq_shape* s, const ScorePlan& plan, ScoreParams p,
   const int64_t waves = plan.max_chunks * plan.n_groups * s->n_layers * s->n_kv_heads;
   const GroupShape gs = group_shape(s, plan);
   const int wpg = gs.waves;
-  p.wg_groups = gs.groups;
-  // ragged: persistent waves, one per SIMD, take their chunks from a work list (32-bit tickets)
+  // ragged: persistent teams (one wave per SIMD; a team = the row groups of a chunk side by side) take their chunks
+  // from work lists (32-bit tickets)
   const bool dyn = s->cu_seqlens != nullptr && waves < ((int64_t)1 << 31);
-  const int simds = simd_count();
-  const dim3 dyn_grid((unsigned)(waves < simds ? waves : simds));
+  const int team = dyn ? team_size(plan) : 1;
+  p.wg_groups = dyn ? team : gs.groups;
+  const int64_t teams = waves / team, team_slots = simd_count() / team;
+  const dim3 dyn_grid((unsigned)(teams < team_slots ? teams : team_slots));
   const dim3 grid = gs.grid(plan, s);
 #define DAPQ_LAUNCH_W2(NRBV)                                                                                        \
   do {                                                                                                              \
-    if (dyn) {                                                                                                      \
-      if ((rc = set_lds(score_wave_pass2_kernel<NRBV, true>, kWaveLds2)) != DAPQ_OK) return rc;                      \
-      hipLaunchKernelGGL((score_wave_pass2_kernel<NRBV, true>), dyn_grid, dim3(64), kWaveLds2, stream, p);           \
+    if (dyn && team > 1) { /* (more than 256 rows: eight row blocks per wave) */                                    \
+      const int lds = team * wave_lds(kTeamStages) + 16;                                                            \
+      if ((rc = set_lds(score_wave_pass2_kernel<8, true, kTeamStages>, kWavesPerGroup * wave_lds(kTeamStages) + 16)) != \
+          DAPQ_OK)                                                                                                  \
+        return rc;                                                                                                  \
+      hipLaunchKernelGGL((score_wave_pass2_kernel<8, true, kTeamStages>), dyn_grid, dim3(64 * team), lds, stream, p);   \
+    } else if (dyn) {                                                                                               \
+      if ((rc = set_lds(score_wave_pass2_kernel<NRBV, true, kWaveStages>, wave_lds(kWaveStages))) != DAPQ_OK) return rc; \
+      hipLaunchKernelGGL((score_wave_pass2_kernel<NRBV, true, kWaveStages>), dyn_grid, dim3(64), wave_lds(kWaveStages), \
+                         stream, p);                                                                                \
     } else {                                                                                                        \
-      if ((rc = set_lds(score_wave_pass2_kernel<NRBV, false>, kWavesPerGroup * kWaveLds2)) != DAPQ_OK) return rc;    \
-      hipLaunchKernelGGL((score_wave_pass2_kernel<NRBV, false>), grid, dim3(64 * wpg), wpg * kWaveLds2, stream, p);  \
+      if ((rc = set_lds(score_wave_pass2_kernel<NRBV, false, kWaveStages>, kWavesPerGroup * wave_lds(kWaveStages))) !=  \
+          DAPQ_OK)                                                                                                  \
+        return rc;                                                                                                  \
+      hipLaunchKernelGGL((score_wave_pass2_kernel<NRBV, false, kWaveStages>), grid, dim3(64 * wpg),                     \
+                         wpg * wave_lds(kWaveStages), stream, p);                                                   \
     }                                                                                                               \
   } while (0)
   if (plan.row_blocks == 2) DAPQ_LAUNCH_W2(2);
