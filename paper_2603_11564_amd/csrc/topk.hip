@@ -682,7 +682,7 @@ struct RegVariant {
 
 RegVariant reg_variant_for(int64_t len) {
   if (len <= 256 * 32) return {256, 32};
-  if (len <= 256 * 64) return {256, 64};
+  if (len <= 512 * 32) return {512, 32};  // (32 keys per thread is the lean code: 64 per thread spills scalar registers)
   if (len <= 1024 * 32) return {1024, 32};
   return {1024, 64};
 }
@@ -690,7 +690,7 @@ RegVariant reg_variant_for(int64_t len) {
 template <int R>
 int launch_reg(RegVariant v, dim3 grid, hipStream_t st, const TopkParams& p) {
   if (v.threads == 256 && v.kpt == 32) hipLaunchKernelGGL((topk_reg_kernel<256, 32, R>), grid, dim3(256), 0, st, p);
-  else if (v.threads == 256) hipLaunchKernelGGL((topk_reg_kernel<256, 64, R>), grid, dim3(256), 0, st, p);
+  else if (v.threads == 512) hipLaunchKernelGGL((topk_reg_kernel<512, 32, R>), grid, dim3(512), 0, st, p);
   else if (v.kpt == 32) {
     constexpr int kBytes = reg_variant_stage_bytes(1024, 32);
     const int rc = set_max_dynamic_lds(reinterpret_cast<const void*>(topk_reg_kernel<1024, 32, R>), kBytes);

@@ -317,8 +317,8 @@ def test_topk_long_heads_in_pieces(H, lens, dense, budget):
 @pytest.mark.parametrize("L,batch", [(8192, 1), (8193, 3), (16384, 2), (16385, 1), (20001, 2), (32767, 3), (32768, 1),
                                      (32769, 2), (50001, 1), (65536, 1), (65537, 1)])
 def test_topk_dense_lengths_around_the_variant_limits(H, L, batch):
-    """Dense batches at the lengths where the kernel variant changes (8, 32, 64 keys per thread,
-    then streaming), with sequence starts that are not 16-byte aligned, heavy ties and a plateau
+    """Dense batches at the lengths where the kernel variant changes (256, 512 or 1024 threads with 32 keys each, 1024
+    with 64, then pieces or streaming), with sequence starts that are not 16-byte aligned, heavy ties and a plateau
     across the threshold."""
     announce(f"topk dense L={L} batch={batch}")
     r = np.random.default_rng(L)
