@@ -204,24 +204,26 @@ int dapq_pool(const dapq_shape* shape, const float* scores, float* pooled, int32
  *   budget_per_seq   optional device int32 [batch]: budget of each sequence (clamped to [0, budget]); NULL = budget
  *   idx, count       out; idx slots past count are left untouched
  *   workspace, workspace_bytes   optional device scratch of dapq_topk_workspace_bytes() bytes (256-byte aligned).
- *                    Heads that fit in the registers of a workgroup (up to 65536 keys; fewer in a ragged batch whose
- *                    mean length is short) never use it.  Longer heads are selected in pieces of 32768 keys whose
- *                    survivors go to candidate lists in the workspace and are then selected among; without the
- *                    workspace (NULL or too small) one workgroup streams such a head from memory five times, which
- *                    gives the same result several times slower.  Contents need not be initialised and mean nothing
- *                    after the call; calls that share a workspace must not overlap. */
+ *                    Heads of up to 32768 keys are selected by one workgroup each, out of its registers, and never
+ *                    use it.  With the workspace, longer heads are selected in pieces of 32768 keys whose survivors
+ *                    go to candidate lists in the workspace and are then selected among.  Without it (NULL or too
+ *                    small) heads of up to 65536 keys still fit one workgroup (64 keys per thread, slower per key),
+ *                    and longer ones are streamed from memory five times by one workgroup each: the same result,
+ *                    several times slower.  Contents need not be initialised and mean nothing after the call; calls
+ *                    that share a workspace must not overlap. */
 int dapq_topk(const dapq_shape* shape, const float* pooled, int32_t budget, const int32_t* budget_per_seq,
               int32_t* idx, int32_t* count, void* workspace, size_t workspace_bytes, void* stream);
 
-/* Bytes of the optional workspace of dapq_topk / dapq_pool_topk for this shape and budget: 0 if no head can be long
- * enough to go in pieces (or the shape is invalid), else 2 x 4 bytes per candidate slot (heads x pieces x budget)
- * plus a count per piece.  Host arithmetic only. */
+/* Bytes of the optional workspace of dapq_topk / dapq_pool_topk for this shape and budget: 0 if no head can have more
+ * than 32768 keys (a ragged batch: more than the workgroup size chosen for its mean length), if the candidates of a
+ * head would be more than 65536, or if the shape is invalid; else 2 x 4 bytes per candidate slot
+ * (heads x pieces x budget) plus a count per piece.  Host arithmetic only. */
 size_t dapq_topk_workspace_bytes(const dapq_shape* shape, int32_t budget);
 
 /* dapq_pool followed by dapq_topk as one call.  For width <= 9 the selection kernels pool on the way in (each thread
  * pools its run of scores in registers, window clipped at the sequence ends) and the pooled scores never travel
  * through HBM: always when every head has at most 65536 keys, and for longer heads when the workspace of
- * dapq_topk_workspace_bytes() is passed (their pieces pool across the piece boundaries).  `pooled` may then be NULL,
+ * dapq_topk_workspace_bytes() is passed (heads in pieces pool across the piece boundaries).  `pooled` may then be NULL,
  * and if it is not NULL it receives the pooled scores as dapq_pool would write them.  Otherwise the two kernels
  * run one after the other and `pooled` (fp32 [n_layers][n_kv_heads][total_tokens], not aliasing
  * scores) is required as the intermediate: DAPQ_ERR_UNSUPPORTED if it is NULL.  Results are identical

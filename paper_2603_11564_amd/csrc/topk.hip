@@ -742,13 +742,16 @@ struct TopkRoute {
   size_t off_key, off_idx, off_count, pieces_bytes;
 };
 
-TopkRoute topk_route(const dapq_shape* shape, int32_t budget) {
+// with_pieces: the caller brought the workspace, so heads of more than one piece's length (32768 keys) need not go
+// to the variant with 64 keys per thread (slower per key than two pieces and a merge) or to the streaming kernel.
+TopkRoute topk_route(const dapq_shape* shape, int32_t budget, bool with_pieces) {
   TopkRoute r;
   const bool ragged = shape->cu_seqlens != nullptr;
   const int64_t mean = shape->total_tokens / shape->batch;
   const int64_t longest = ragged ? shape->total_tokens : mean;
   // a ragged batch sizes the variant for 1.5 x its mean length (or everything, if that is less)
-  const int64_t sized_for = !ragged ? mean : (mean + mean / 2 < longest ? mean + mean / 2 : longest);
+  int64_t sized_for = !ragged ? mean : (mean + mean / 2 < longest ? mean + mean / 2 : longest);
+  if (with_pieces && sized_for > kTopkPieceLen) sized_for = kTopkPieceLen;
   r.variant = reg_variant_for(sized_for);
   r.reg_max = r.variant.max_len();
   r.any_short = ragged || mean <= r.reg_max;  // (a dense batch of longer heads has nothing for the register variant)
@@ -835,15 +838,26 @@ TopkParams topk_params(const dapq_shape* shape, const float* in, float* pooled_o
 
 extern "C" DAPQ_API size_t dapq_topk_workspace_bytes(const dapq_shape* shape, int32_t budget) {
   if (check_shape(shape, false, false, false) != DAPQ_OK || budget < 1) return 0;
-  return topk_route(shape, budget).pieces_bytes;
+  return topk_route(shape, budget, true).pieces_bytes;
 }
+
+namespace dapq {
+namespace {
+// The route of a call: with the pieces if the caller's workspace holds their candidate lists.
+TopkRoute topk_route_for(const dapq_shape* shape, int32_t budget, const void* workspace, size_t workspace_bytes) {
+  const TopkRoute with = topk_route(shape, budget, true);
+  if (with.pieces_possible && workspace != nullptr && workspace_bytes >= with.pieces_bytes) return with;
+  return topk_route(shape, budget, false);
+}
+}  // namespace
+}  // namespace dapq
 
 extern "C" DAPQ_API int dapq_topk(const dapq_shape* shape, const float* pooled, int32_t budget, const int32_t* budget_per_seq,
                          int32_t* idx, int32_t* count, void* workspace, size_t workspace_bytes, void* stream) {
   int rc = topk_common_checks(shape, pooled, budget, idx, count);
   if (rc != DAPQ_OK) return rc;
   TopkParams p = topk_params(shape, pooled, nullptr, budget, budget_per_seq, idx, count);
-  const TopkRoute route = topk_route(shape, budget);
+  const TopkRoute route = topk_route_for(shape, budget, workspace, workspace_bytes);
   const dim3 grid((unsigned)shape->n_kv_heads, (unsigned)shape->batch, (unsigned)shape->n_layers);
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (route.any_short) {
@@ -867,21 +881,23 @@ extern "C" DAPQ_API int dapq_pool_topk(const dapq_shape* shape, const float* sco
   const dim3 grid((unsigned)shape->n_kv_heads, (unsigned)shape->batch, (unsigned)shape->n_layers);
   hipStream_t st = static_cast<hipStream_t>(stream);
   TopkParams p = topk_params(shape, scores, pooled, budget, budget_per_seq, idx, count);
-  if (width <= 9 && longest <= 64 * kTopkThreads) {
-    // one kernel: every head fits a register variant, which pools on the way in
-    if ((rc = launch_reg_radius(width / 2, reg_variant_for(longest), grid, st, p)) != DAPQ_OK) return rc;
-    DAPQ_HIP_LAUNCH_CHECK("topk_reg_kernel");
-    return DAPQ_OK;
-  }
-  const TopkRoute route = topk_route(shape, budget);
-  if (width <= 9 && route.pieces_possible && workspace != nullptr && workspace_bytes >= route.pieces_bytes) {
-    // the same with the long heads in pieces: their kernels pool across the piece boundaries
+  const TopkRoute route = topk_route_for(shape, budget, workspace, workspace_bytes);
+  if (width <= 9 && route.any_long && route.pieces_possible && workspace != nullptr &&
+      workspace_bytes >= route.pieces_bytes) {
+    // heads of more than 32768 keys in pieces, whose kernels pool across the piece boundaries; the others in one
+    // workgroup each
     if (route.any_short) {
       p.max_len = (int32_t)route.reg_max;
       if ((rc = launch_reg_radius(width / 2, route.variant, grid, st, p)) != DAPQ_OK) return rc;
       DAPQ_HIP_LAUNCH_CHECK("topk_reg_kernel");
     }
     return launch_long_heads(shape, route, p, width / 2, workspace, workspace_bytes, st);
+  }
+  if (width <= 9 && longest <= 64 * kTopkThreads) {
+    // one kernel: every head fits a register variant, which pools on the way in
+    if ((rc = launch_reg_radius(width / 2, reg_variant_for(longest), grid, st, p)) != DAPQ_OK) return rc;
+    DAPQ_HIP_LAUNCH_CHECK("topk_reg_kernel");
+    return DAPQ_OK;
   }
   DAPQ_REQUIRE(pooled != nullptr, DAPQ_ERR_UNSUPPORTED,
                "width %d / head length %lld need the two-kernel path: pass a pooled buffer (or, for width <= 9, a "

@@ -69,12 +69,13 @@ def test_workspace_bytes_over_a_sweep_of_shapes(lib):
 
 
 def test_topk_workspace_bytes(lib):
-    """The optional workspace of the selection calls: nothing unless a head can be longer than 65536 keys; then two
+    """The optional workspace of the selection calls: nothing unless a head can be longer than 32768 keys; then two
     candidate lists of heads x pieces x budget 4-byte entries and a count per piece (pieces of 32768 keys)."""
     def align(n):
         return (n + 255) // 256 * 256
     assert D.topk_workspace_bytes(good_shape(), 983) == 0                                   # 4096 keys per head
-    assert D.topk_workspace_bytes(good_shape(total_tokens=65536), 983) == 0
+    assert D.topk_workspace_bytes(good_shape(total_tokens=32768), 983) == 0                 # one piece: one workgroup
+    assert D.topk_workspace_bytes(good_shape(total_tokens=65536), 983) == 2 * align(16 * 2 * 983 * 4) + align(16 * 2 * 4)
     long_heads = good_shape(n_layers=3, total_tokens=131072)                                # 3 x 1 x 8 heads, 4 pieces
     assert D.topk_workspace_bytes(long_heads, 3932) == 2 * align(24 * 4 * 3932 * 4) + align(24 * 4 * 4)
     assert D.topk_workspace_bytes(good_shape(total_tokens=65537), 5) == 2 * align(16 * 3 * 5 * 4) + align(16 * 3 * 4)

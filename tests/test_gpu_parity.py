@@ -331,9 +331,9 @@ def test_topk_dense_lengths_around_the_variant_limits(H, L, batch):
 
 _POOL_TOPK_SHAPES = [([5000], True), ([8193] * 2, True), ([20001] * 2, True), ([40000], True), ([70000], True),
                      ([131072], True), ([1, 6, 100, 1025, 0, 4097], False), ([70000, 3, 0, 40000], False)]
-# long heads (more than 65536 keys; a ragged batch counts with its total) also go in pieces through the workspace
+# long heads (more than 32768 keys; a ragged batch counts with its total) also go in pieces through the workspace
 _POOL_TOPK_CASES = [(lens, dense, pieces) for lens, dense in _POOL_TOPK_SHAPES
-                    for pieces in ([False, True] if (max(lens) if dense else sum(lens)) > 65536 else [False])]
+                    for pieces in ([False, True] if (max(lens) if dense else sum(lens)) > 32768 else [False])]
 
 
 @pytest.mark.parametrize("width", [1, 3, 5, 7, 9, 11])
