@@ -19,6 +19,10 @@
  *   - Calls may be in flight on several streams at once as long as they share no output buffer and no
  *     workspace: a workspace belongs to one call until the work of that call has finished on its stream.
  *   - Results are deterministic: the same inputs give the same bits on every run.
+ *   - Every call only launches kernels on `stream` (no memset or copy nodes, no synchronisation), so a sequence
+ *     of calls can be recorded into a HIP graph and replayed; counters in the workspace are cleared by the
+ *     kernels of each call.  The first call of an entry point on a device also raises its kernels' dynamic-LDS
+ *     limits and reads the device's unit count, which is host work: make one ordinary call before capturing.
  *   - bf16 tensors are passed as void* (16-bit patterns).  head_dim must be 128.
  *
  * Tensor layouts (element strides, the last dimension d is contiguous)

@@ -1,0 +1,78 @@
+"""The whole step recorded into a HIP graph and replayed.
+
+The library allocates nothing, clears its counters with kernels of its own and keeps no state between calls
+besides the workspaces the caller owns, so a step (rotation of the pseudo queries, both score passes, max-pool +
+TopK, gather) can be captured once and replayed by a serving loop.  Each case replays the graph several times, with
+eager work of the program and synchronisations between the replays, and compares every replay bit for bit with the
+eager step on the same inputs.  One eager step runs before the capture: the first call on a device does the
+library's one-time set-up (dynamic-LDS limits, unit counts), which is not stream work.
+"""
+import os
+import sys
+from dataclasses import replace
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import workloads as W  # noqa: E402
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+def _cases():
+    dense = W.workload("C1")                                                    # one wave per chunk, four to a workgroup
+    ragged = replace(W.workload("C3"), n_layers=2, batch=5, ragged=(300, 2500), budget=96)   # teams, work lists, tickets
+    empty_mix = replace(W.workload("C3"), n_layers=1, batch=4, ragged=(0, 700), n_pseudo=32, budget=40)
+    long_head = replace(W.workload("C5"), n_layers=1, seq_len=70000, budget=1500, needles=8)  # selection in pieces
+    return [("dense", dense, 3), ("ragged", ragged, 5), ("ragged-short", empty_mix, 11), ("long-head", long_head, 7)]
+
+
+@pytest.mark.parametrize("name,w,seed", _cases(), ids=[c[0] for c in _cases()])
+def test_step_replays_from_a_graph(name, w, seed):
+    import bench
+    print(f"graph replay: {name} seed {seed}", flush=True)
+    dev = torch.device("cuda:0")
+    ctx = bench.Context(w, seed, dev)
+    other = bench.Context(W.workload("C1"), seed + 1, dev)      # the program's own eager work between replays
+    outs = [ctx.q, ctx.lse2, ctx.S, ctx.idx, ctx.count, ctx.k_out, ctx.v_out]
+
+    ctx.step()
+    torch.cuda.synchronize()
+    want = [t.clone() for t in outs]
+    # every replay starts from scribbled intermediates and workspaces; what a step leaves untouched (index and cache
+    # slots beyond a head's count) is not scribbled and is compared as the eager step left it
+    def scribble():
+        ctx.q.fill_(0)
+        ctx.lse2.fill_(float("nan"))
+        ctx.S.fill_(-1.0)
+        ctx.ws.fill_(0xA5)
+        if ctx.topk_ws is not None:
+            ctx.topk_ws.fill_(0x5A)
+
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    eager_stream = ctx.stream
+    with torch.cuda.graph(graph, stream=side):
+        ctx.stream = torch.cuda.current_stream()
+        ctx.step()
+    ctx.stream = eager_stream
+
+    for replay in range(4):
+        scribble()
+        other.step()
+        torch.cuda.synchronize()
+        graph.replay()
+        if replay % 2:
+            other.step()                                         # eager work queued right behind a replay as well
+        torch.cuda.synchronize()
+        for t, ref, what in zip(outs, want, ["q", "lse2", "scores", "idx", "count", "k_out", "v_out"]):
+            a, b = t.view(torch.uint8).reshape(-1), ref.view(torch.uint8).reshape(-1)
+            assert torch.equal(a, b), f"{name}: replay {replay}: {what} differs from the eager step"
+    counts = ctx.count.cpu().numpy()
+    lens = np.asarray(ctx.lens)
+    assert (counts == np.minimum(lens, w.budget)[None, :, None]).all()
