@@ -76,3 +76,38 @@ def test_step_replays_from_a_graph(name, w, seed):
     counts = ctx.count.cpu().numpy()
     lens = np.asarray(ctx.lens)
     assert (counts == np.minimum(lens, w.budget)[None, :, None]).all()
+
+
+def test_static_scores_replay_from_a_graph():
+    """dapq_score_static is the entry point for callers under capture: recorded once (after an ordinary first call, which
+    looks up the address of the built-in scratch array), replayed between other users of the same array."""
+    import paper_2603_11564_amd as D
+    from dapq_harness import Problem
+    print("graph replay: dapq_score_static", flush=True)
+    rng = np.random.default_rng(21)
+    lens = [900, 0, 37, 2100]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    q = W.to_bf16_bits(rng.standard_normal((2, len(lens), 8, 32, 128)))
+    k = W.to_bf16_bits(rng.standard_normal((2, int(cu[-1]), 2, 128)))
+    ragged = Problem(q, k, k, 2, cu, "thd", 128 ** -0.5)
+    qd = W.to_bf16_bits(rng.standard_normal((1, 1, 8, 64, 128)))
+    kd = W.to_bf16_bits(rng.standard_normal((1, 3000, 2, 128)))
+    dense = Problem(qd, kd, kd, 2, None, "thd", 128 ** -0.5)
+    want_ragged, want_dense = ragged.score(), dense.score()
+    S_ragged = torch.empty_like(want_ragged)
+    S_dense = torch.empty_like(want_dense)
+    D.dapq_score_static(dense.shape, dense.q, dense.k, S_dense)          # first call on the device: set-up
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        D.dapq_score_static(ragged.shape, ragged.q, ragged.k, S_ragged, torch.cuda.current_stream())
+    for replay in range(3):
+        S_ragged.fill_(float("nan"))
+        S_dense.fill_(float("nan"))
+        D.dapq_score_static(dense.shape, dense.q, dense.k, S_dense)      # another user of the scratch array, in order
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(S_dense, want_dense), f"replay {replay}: eager call between replays"
+        assert torch.equal(S_ragged, want_ragged), f"replay {replay}: captured call"
