@@ -52,6 +52,37 @@ def test_rope_matches_oracle_bits(H, pairing):
     assert np.array_equal(got[0], bits[0])                     # position 0 is the identity
 
 
+@pytest.mark.parametrize("pairing", [0, 1])
+def test_rope_narrow_and_wide_kernels_agree(H, pairing):
+    """Buffers that are only 2-byte aligned, or an odd number of channel pairs, take the kernel with one pair per thread;
+    aligned ones take two pairs per thread.  Same bits either way, and the oracle's."""
+    announce(f"rope narrow / wide, pairing={pairing}")
+    import paper_2603_11564_amd as D
+    r = np.random.default_rng(300 + pairing)
+    rows, heads, d = 130, 11, 128
+    bits = W.to_bf16_bits(r.standard_normal((rows, heads, d)))
+    pos = r.integers(0, 200000, size=rows).astype(np.int32)
+    want = O.rope_apply(bits, pos, 500000.0, "half" if pairing == 0 else "interleaved")
+    wide = H.rope_gpu(bits, pos, 500000.0, pairing)
+    flat_in = torch.zeros(bits.size + 1, dtype=torch.bfloat16, device="cuda")
+    flat_out = torch.zeros_like(flat_in)
+    x, y = flat_in[1:].view(rows, heads, d), flat_out[1:].view(rows, heads, d)
+    assert x.data_ptr() % 4 == 2
+    x.copy_(H.dev_bf16(bits))
+    D.dapq_rope_apply(x, y, torch.from_numpy(pos).cuda(), rows, heads, d, heads * d, d, 500000.0, pairing)
+    narrow = H.host_bits(y)
+    assert np.array_equal(narrow, wide)
+    diff = wide.astype(np.int32) - want.astype(np.int32)
+    assert np.abs(diff).max() <= 1 and np.count_nonzero(diff) <= 2
+    for small_d in (2, 6, 4):                                   # one pair, an odd number of pairs, two pairs
+        b = W.to_bf16_bits(r.standard_normal((37, 3, small_d)))
+        ps = r.integers(0, 5000, size=37).astype(np.int32)
+        got = H.rope_gpu(b, ps, 10000.0, pairing)
+        ref = O.rope_apply(b, ps, 10000.0, "half" if pairing == 0 else "interleaved")
+        dd = got.astype(np.int32) - ref.astype(np.int32)
+        assert np.abs(dd).max() <= 1 and np.count_nonzero(dd) <= 1, f"head_dim {small_d}"
+
+
 def test_rope_in_place_and_pseudo_query_positions(H):
     announce("rope in place, C1 pseudo queries")
     w = W.workload("C1")
