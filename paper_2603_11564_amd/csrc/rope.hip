@@ -1,11 +1,10 @@
 // Position assignment (Sec. 4.1): rotary embedding of bf16 vectors at given absolute positions.
 // The pseudo queries get positions L_p .. L_p+N-1, the positions of the first N decode steps.
 //
-// One thread owns two neighbouring channel pairs of a row (one if the buffers are not 4-byte aligned)
-// and a run of heads: it evaluates the angles pos * theta^(-2c/d) and their sines / cosines once in
-// fp64 and then walks its heads, reading and writing two elements per access, so the transcendental
-// work (more than ten times the work of one rotation) is shared by the heads of a run; runs are
-// 8 heads long, longer (up to 64) while the launch still has thousands of waves.
+// One thread owns one (row, channel pair) and a run of heads: it evaluates the angle
+// pos * theta^(-2c/d) and its sine / cosine once in fp64 and then walks its heads, so the
+// transcendental work (more than ten times the work of one rotation) is shared by the heads of a
+// run; runs are 8 heads long, longer (up to 64) while the launch still has thousands of waves.
 // fp64 keeps the angle exact enough at positions beyond 10^5 (an fp32 product pos * omega would be
 // off by ~1e-2 rad there); the rotation is done in fp64 as well and rounded to bf16 once, which is
 // what makes the result equal to a float64 evaluation bit for bit, and what the kernel's time goes
@@ -34,69 +33,43 @@ __device__ __forceinline__ uint16_t f64_to_bf16(double x) {
   return __builtin_bit_cast(uint16_t, (__bf16)__uint_as_float(u));
 }
 
-// CPT = channel pairs per thread: 1, or 2 neighbouring ones, whose elements are then read and written two at a
-// time (4-byte accesses; the launcher checks the alignment this needs).
-template <int CPT>
 __global__ void rope_kernel(const uint16_t* x_in, uint16_t* x_out, const int32_t* __restrict__ pos,
                             int64_t rows, int heads, int head_dim, int64_t stride_row, int64_t stride_head,
                             double neg_log2_theta_2_over_d, int pairing, int heads_per_thread) {
   const int half = head_dim >> 1;
-  const int per_row = half / CPT;
   const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (gid >= rows * per_row) return;
-  const int64_t row = gid / per_row;
-  const int c = (int)(gid - row * per_row) * CPT;
-  double sn[CPT], cs[CPT];
-#pragma unroll
-  for (int t = 0; t < CPT; ++t) {
-    const double omega = exp2((double)(c + t) * neg_log2_theta_2_over_d);  // theta^(-2c/d)
-    sincos((double)pos[row] * omega, &sn[t], &cs[t]);
-  }
-  // element offsets of the thread's first accesses: the a and b of pair c (CPT = 1), or two words that hold the
-  // a's and the b's of pairs c, c+1 (half pairing) / the (a, b) of pair c and of pair c+1 (interleaved pairing)
-  const int i0 = pairing == 0 ? c : 2 * c;
-  const int i1 = pairing == 0 ? c + half : 2 * c + (CPT == 1 ? 1 : 2);
+  if (gid >= rows * half) return;
+  const int64_t row = gid / half;
+  const int c = (int)(gid - row * half);
+  const double omega = exp2((double)c * neg_log2_theta_2_over_d);  // theta^(-2c/d)
+  double sn, cs;
+  sincos((double)pos[row] * omega, &sn, &cs);
+  const int ia = pairing == 0 ? c : 2 * c;
+  const int ib = pairing == 0 ? c + half : 2 * c + 1;
   const uint16_t* src = x_in + row * stride_row;
   uint16_t* dst = x_out + row * stride_row;
   const int hd0 = blockIdx.y * heads_per_thread;
   const int hd1 = hd0 + heads_per_thread < heads ? hd0 + heads_per_thread : heads;
-  auto rotate = [&](int hd, uint32_t r0, uint32_t r1) {
-    if constexpr (CPT == 1) {
-      const double a = bf16_to_f64((uint16_t)r0), b = bf16_to_f64((uint16_t)r1);
-      dst[(int64_t)hd * stride_head + i0] = f64_to_bf16(a * cs[0] - b * sn[0]);
-      dst[(int64_t)hd * stride_head + i1] = f64_to_bf16(b * cs[0] + a * sn[0]);
-    } else {
-      // half pairing: r0 = (a0, a1), r1 = (b0, b1); interleaved: r0 = (a0, b0), r1 = (a1, b1)
-      const uint16_t a0 = (uint16_t)r0, a1 = pairing == 0 ? (uint16_t)(r0 >> 16) : (uint16_t)r1;
-      const uint16_t b0 = pairing == 0 ? (uint16_t)r1 : (uint16_t)(r0 >> 16), b1 = (uint16_t)(r1 >> 16);
-      const double fa0 = bf16_to_f64(a0), fb0 = bf16_to_f64(b0), fa1 = bf16_to_f64(a1), fb1 = bf16_to_f64(b1);
-      const uint32_t oa0 = f64_to_bf16(fa0 * cs[0] - fb0 * sn[0]), ob0 = f64_to_bf16(fb0 * cs[0] + fa0 * sn[0]);
-      const uint32_t oa1 = f64_to_bf16(fa1 * cs[1] - fb1 * sn[1]), ob1 = f64_to_bf16(fb1 * cs[1] + fa1 * sn[1]);
-      uint32_t* d0 = reinterpret_cast<uint32_t*>(dst + (int64_t)hd * stride_head + i0);
-      uint32_t* d1 = reinterpret_cast<uint32_t*>(dst + (int64_t)hd * stride_head + i1);
-      *d0 = pairing == 0 ? (oa0 | (oa1 << 16)) : (oa0 | (ob0 << 16));
-      *d1 = pairing == 0 ? (ob0 | (ob1 << 16)) : (oa1 | (ob1 << 16));
-    }
-  };
-  auto fetch = [&](int hd, int i) -> uint32_t {
-    const uint16_t* p = src + (int64_t)hd * stride_head + i;
-    if constexpr (CPT == 1) return *p;
-    else return *reinterpret_cast<const uint32_t*>(p);
-  };
   int hd = hd0;
   for (; hd + 4 <= hd1; hd += 4) {  // four heads per trip: eight loads in flight before the first rotation
-    uint32_t r0[4], r1[4];
+    uint16_t ra[4], rb[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      r0[u] = fetch(hd + u, i0);
-      r1[u] = fetch(hd + u, i1);
+      ra[u] = src[(int64_t)(hd + u) * stride_head + ia];
+      rb[u] = src[(int64_t)(hd + u) * stride_head + ib];
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) rotate(hd + u, r0[u], r1[u]);
+    for (int u = 0; u < 4; ++u) {
+      const double a = bf16_to_f64(ra[u]), b = bf16_to_f64(rb[u]);
+      dst[(int64_t)(hd + u) * stride_head + ia] = f64_to_bf16(a * cs - b * sn);
+      dst[(int64_t)(hd + u) * stride_head + ib] = f64_to_bf16(b * cs + a * sn);
+    }
   }
   for (; hd < hd1; ++hd) {
-    const uint32_t r0 = fetch(hd, i0), r1 = fetch(hd, i1);
-    rotate(hd, r0, r1);
+    const double a = bf16_to_f64(src[(int64_t)hd * stride_head + ia]);
+    const double b = bf16_to_f64(src[(int64_t)hd * stride_head + ib]);
+    dst[(int64_t)hd * stride_head + ia] = f64_to_bf16(a * cs - b * sn);
+    dst[(int64_t)hd * stride_head + ib] = f64_to_bf16(b * cs + a * sn);
   }
 }
 
@@ -161,30 +134,18 @@ extern "C" DAPQ_API int dapq_rope_apply(const void* x_in, void* x_out, const int
   DAPQ_REQUIRE(stride_head >= head_dim && stride_row >= 0, DAPQ_ERR_INVALID_ARG,
                "stride_head (%lld) must cover head_dim and stride_row (%lld) must be >= 0", (long long)stride_head,
                (long long)stride_row);
-  // two channel pairs per thread when every access of a thread is then a whole aligned 4-byte word
-  const bool wide = (head_dim / 2) % 2 == 0 && stride_row % 2 == 0 && stride_head % 2 == 0 &&
-                    (reinterpret_cast<uintptr_t>(x_in) | reinterpret_cast<uintptr_t>(x_out)) % 4 == 0;
-  const int cpt = wide ? 2 : 1;
-  // enough waves to keep every SIMD busy while the runs are as long as possible (measured on the pseudo queries of
-  // the 8B shape: 64 rows x 1024 heads)
-  const int64_t min_waves = wide ? 2048 : 4096;
-  const int64_t work = rows * (head_dim / 2 / cpt);
+  const int64_t work = rows * (head_dim / 2);
   DAPQ_REQUIRE(work / 256 < ((int64_t)1 << 31), DAPQ_ERR_UNSUPPORTED, "too many rows");
   if (work == 0) return DAPQ_OK;
   int hpt = 8;
-  while (hpt < 64 && hpt * 2 <= heads && (work / 64) * ((heads + 2 * hpt - 1) / (2 * hpt)) >= min_waves) hpt *= 2;
+  while (hpt < 64 && hpt * 2 <= heads && (work / 64) * ((heads + 2 * hpt - 1) / (2 * hpt)) >= 4096) hpt *= 2;
   const int64_t head_runs = ((int64_t)heads + hpt - 1) / hpt;
   DAPQ_REQUIRE(head_runs <= 65535, DAPQ_ERR_UNSUPPORTED, "heads (%d) exceeds %d", heads, 65535 * hpt);
   const double e = -2.0 * log2(theta) / (double)head_dim;
-  const dim3 grid((unsigned)((work + 255) / 256), (unsigned)head_runs);
-  if (cpt == 2)
-    hipLaunchKernelGGL(rope_kernel<2>, grid, dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<const uint16_t*>(x_in), static_cast<uint16_t*>(x_out), pos, rows, heads, head_dim,
-                       stride_row, stride_head, e, pairing, hpt);
-  else
-    hipLaunchKernelGGL(rope_kernel<1>, grid, dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<const uint16_t*>(x_in), static_cast<uint16_t*>(x_out), pos, rows, heads, head_dim,
-                       stride_row, stride_head, e, pairing, hpt);
+  hipLaunchKernelGGL(rope_kernel, dim3((unsigned)((work + 255) / 256), (unsigned)head_runs), dim3(256), 0,
+                     static_cast<hipStream_t>(stream),
+                     static_cast<const uint16_t*>(x_in), static_cast<uint16_t*>(x_out), pos, rows, heads, head_dim,
+                     stride_row, stride_head, e, pairing, hpt);
   DAPQ_HIP_LAUNCH_CHECK("rope_kernel");
   return DAPQ_OK;
 }

@@ -53,10 +53,10 @@ def test_rope_matches_oracle_bits(H, pairing):
 
 
 @pytest.mark.parametrize("pairing", [0, 1])
-def test_rope_narrow_and_wide_kernels_agree(H, pairing):
-    """Buffers that are only 2-byte aligned, or an odd number of channel pairs, take the kernel with one pair per thread;
-    aligned ones take two pairs per thread.  Same bits either way, and the oracle's."""
-    announce(f"rope narrow / wide, pairing={pairing}")
+def test_rope_unaligned_buffers_and_small_head_dims(H, pairing):
+    """Buffers that are only 2-byte aligned give the bits of aligned ones (and the oracle's); head_dim 2, 4 and 6 (one
+    channel pair, two, an odd number)."""
+    announce(f"rope unaligned / small head_dim, pairing={pairing}")
     import paper_2603_11564_amd as D
     r = np.random.default_rng(300 + pairing)
     rows, heads, d = 130, 11, 128
@@ -74,7 +74,7 @@ def test_rope_narrow_and_wide_kernels_agree(H, pairing):
     assert np.array_equal(narrow, wide)
     diff = wide.astype(np.int32) - want.astype(np.int32)
     assert np.abs(diff).max() <= 1 and np.count_nonzero(diff) <= 2
-    for small_d in (2, 6, 4):                                   # one pair, an odd number of pairs, two pairs
+    for small_d in (2, 6, 4):
         b = W.to_bf16_bits(r.standard_normal((37, 3, small_d)))
         ps = r.integers(0, 5000, size=37).astype(np.int32)
         got = H.rope_gpu(b, ps, 10000.0, pairing)
