@@ -2,8 +2,9 @@
 """Benchmark of the DapQ eviction step on one MI355X.
 
 A step is one pass of the whole hot path over one synthetic batch, all layers and heads:
-  dapq_rope_apply (pseudo queries to positions L_p..L_p+N-1) -> dapq_score_stats (pass 1 over K)
-  -> dapq_score_accumulate (pass 2 over K) -> dapq_pool_topk (max-pool + TopK) -> dapq_gather.
+  dapq_rope_apply (pseudo queries to positions L_p..L_p+N-1) -> dapq_score (pass 1 and pass 2 over K: one kernel where
+  the library can run both in one launch, else dapq_score_stats and dapq_score_accumulate, timed separately)
+  -> dapq_pool_topk (max-pool + TopK) -> dapq_gather.
 Inputs are resident in HBM before the timed region.  Prints one JSON line:
   value     prompt keys scored+evicted per second (layers x KV heads x prompt keys / step time)
   roofline  the dominant kernel against the nearer roof (HBM for up to ~310 query rows per KV head,
@@ -68,6 +69,9 @@ def parse():
     ap.add_argument("--post-idle-steps", type=int, default=20,
                     help="steps timed right after set-up and a pause, before the clock governor has settled "
                          "(reported as ms_per_step_post_idle; 0 = skip)")
+    ap.add_argument("--split-passes", action="store_true",
+                    help="time the two score passes as separate launches even where the library can run both in one "
+                         "kernel (how the per-pass profiles are taken)")
     ap.add_argument("--extras", action="store_true",
                     help="also time the entry points around the step (extended normaliser, decode over the compact "
                          "cache, recall); reported under extras_ms, not part of value")
@@ -140,9 +144,11 @@ def cpu_baseline(w, seed, n_layers):
 class Context:
     """Everything one benchmark step needs, resident in HBM: inputs, outputs, workspace, and step()."""
 
-    def __init__(self, w, seed, dev, overrides=None, keep_pooled=False):
+    def __init__(self, w, seed, dev, overrides=None, keep_pooled=False, split_passes=False):
         """keep_pooled: also write the pooled scores to self.P (the tests look at them); otherwise pooling
         happens inside the selection kernel whenever dapq_pool_topk can fuse the two.
+        split_passes: call dapq_score_stats and dapq_score_accumulate even where dapq_score would run both passes
+        in one kernel (the per-pass profiles under profiles/ are taken this way).
         overrides: optional {(layer_index, sequence, kv_head): (k_bits [L, d], v_bits [L, d])} of post-RoPE
         host slices written over the device-generated ones; the parity tests use it to give the oracle and
         the GPU the same bits for the heads they compare."""
@@ -188,6 +194,10 @@ class Context:
                                   total_tokens=tokens, cu_seqlens=self.cu, k_strides=kstr, v_strides=kstr,
                                   q_strides=qstr, scale=w.scale)
         self.ws = torch.empty(D.workspace_bytes(self.shape), dtype=torch.uint8, device=dev)
+        # both passes in one kernel (dense batches of up to 256 rows per KV head and 1, 2 or 4 chunks per sequence)
+        self.single_launch = D.score_single_launch(self.shape) and not split_passes
+        self.names = (["rope", "score", "pool_topk", "gather"] if self.single_launch else
+                      ["rope", "score_pass1", "score_pass2", "pool_topk", "gather"])
         self.lse2 = torch.empty((nl, B, Hq, N), dtype=torch.float32, device=dev)
         self.S = torch.empty((nl, Hkv, tokens), dtype=torch.float32, device=dev)
         # dapq_pool_topk pools inside the selection kernels for windows up to 9: heads up to 65536 keys in one kernel,
@@ -205,26 +215,30 @@ class Context:
         self.stream = torch.cuda.current_stream()
         self.key_units = nl * Hkv * tokens
 
-    names = ["rope", "score_pass1", "score_pass2", "pool_topk", "gather"]
-
     def step(self, events=None):
+        """One step; events (len(self.names) + 1 of them) bracket the calls in the order of self.names."""
         D, w, stream = self.D, self.w, self.stream
         d, Hq, N, nl = w.head_dim, w.n_q_heads, w.n_pseudo, w.n_layers
+        at = [0]
 
-        def mark(i):
+        def mark():
             if events is not None:
-                events[i].record(stream)
-        mark(0)
+                events[at[0]].record(stream)
+            at[0] += 1
+        mark()
         D.dapq_rope_apply(self.q_pre, self.q, self.q_pos, w.batch * N, nl * Hq, d, d, w.batch * N * d, w.theta, 0, stream)
-        mark(1)
-        D.dapq_score_stats(self.shape, self.q, self.k, self.lse2, self.ws, stream)
-        mark(2)
-        D.dapq_score_accumulate(self.shape, self.q, self.k, self.lse2, self.S, self.ws, stream)
-        mark(3)
+        mark()
+        if self.single_launch:
+            D.dapq_score(self.shape, self.q, self.k, self.S, self.ws, stream)
+        else:
+            D.dapq_score_stats(self.shape, self.q, self.k, self.lse2, self.ws, stream)
+            mark()
+            D.dapq_score_accumulate(self.shape, self.q, self.k, self.lse2, self.S, self.ws, stream)
+        mark()
         D.dapq_pool_topk(self.shape, self.S, w.pool_width, w.budget, None, self.idx, self.count, self.P, stream, self.topk_ws)
-        mark(4)
+        mark()
         D.dapq_gather(self.shape, self.k, self.v, self.idx, self.count, w.budget, self.k_out, self.v_out, stream)
-        mark(5)
+        mark()
 
 
 def read_stream_gbs(dev, n_bytes=2 << 30):
@@ -289,7 +303,7 @@ def ceilings(ctx, args):
     from paper_2603_11564_amd import ceiling
     w, dev = ctx.w, ctx.dev
     g, N, d = w.n_q_heads // w.n_kv_heads, w.n_pseudo, w.head_dim
-    ctx.step()                      # rotated pseudo queries, a valid lse2
+    ctx.step()                      # rotated pseudo queries
     torch.cuda.synchronize()
     out = {"workload": f"{w.name}: {w.n_layers} layers, N {N}, L_p {ctx.lens[0]}", "reps": args.steps}
     # slices one SIMD runs per pass: (rows / 32) x (keys / 32) x (d / 16) MFMAs over all heads, on 1024 SIMDs
@@ -404,6 +418,7 @@ def time_extras(ctx, reps):
     dec = torch.empty((nl, B, Hq, d), dtype=torch.float32, device=dev)
     common = torch.empty((nl, B, Hkv), dtype=torch.int32, device=dev)
     rec = torch.empty((nl, B, Hkv), dtype=torch.float32, device=dev)
+    D.dapq_score_stats(ctx.shape, ctx.q, ctx.k, ctx.lse2, ctx.ws, stream)   # (a one-kernel step leaves no lse2)
     lse = ctx.lse2.clone()
     calls = {
         "score_stats_extend": lambda: D.dapq_score_stats_extend(ctx.shape, ctx.q, kp, (B * Hkv * N * d, Hkv * N * d, N * d, d),
@@ -458,10 +473,10 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    ctx = Context(w, args.seed, dev)
+    ctx = Context(w, args.seed, dev, split_passes=args.split_passes)
     lens, tokens = ctx.lens, ctx.tokens
     d, Hq, Hkv, N, nl, B = w.head_dim, w.n_q_heads, w.n_kv_heads, w.n_pseudo, w.n_layers, w.batch
-    names = Context.names
+    names = ctx.names
     if args.ceilings:
         print(json.dumps({"ceilings": ceilings(ctx, args)}), flush=True)
         return
@@ -510,9 +525,16 @@ def main():
     # algorithmic bytes of one score pass: every key row once (2*d bytes) + the 4-byte score (pass 2)
     # or nothing (pass 1), + the pseudo queries once per KV head
     q_bytes = nl * B * Hq * N * d * 2
-    bytes_pass = {"score_pass1": key_units * 2 * d + q_bytes, "score_pass2": key_units * (2 * d + 4) + q_bytes}
+    flops_one_pass = 2.0 * key_units * (Hq // Hkv) * N * d
+    if ctx.single_launch:
+        # one kernel walks K twice (pass 1 forward, pass 2 backward), reads the pseudo queries once, writes the scores
+        bytes_pass = {"score": key_units * (4 * d + 4) + q_bytes}
+        flops_of = {"score": 2 * flops_one_pass}
+    else:
+        bytes_pass = {"score_pass1": key_units * 2 * d + q_bytes, "score_pass2": key_units * (2 * d + 4) + q_bytes}
+        flops_of = {"score_pass1": flops_one_pass, "score_pass2": flops_one_pass}
     dom = max(bytes_pass, key=lambda n: per[n])
-    flops_pass = 2.0 * key_units * (Hq // Hkv) * N * d
+    flops_pass = flops_of[dom]
     hbm_gbs = bytes_pass[dom] / (per[dom] * 1e-3) / 1e9
     mfma_tflops = flops_pass / (per[dom] * 1e-3) / 1e12
     # which roof is nearer: a pass runs g*N*d*2 flop per 2*d bytes of K, the machine balances at peak/peak
@@ -540,7 +562,7 @@ def main():
         "algorithmic_bytes": step_alg, "design_bytes": step_design,
         "algorithmic_gbs": step_alg / (ms_per_step * 1e-3) / 1e9, "design_gbs": step_design / (ms_per_step * 1e-3) / 1e9,
         "design_frac_of_peak": step_design / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "mfma_frac_of_peak": {n: flops_pass / (per[n] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS for n in bytes_pass},
+        "mfma_frac_of_peak": {n: flops_of[n] / (per[n] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS for n in bytes_pass},
     }
 
     # what a read-only stream reaches on this machine, for scale next to the data-sheet peak (outside the timed region)

@@ -149,9 +149,17 @@ size_t dapq_pseudo_queries_workspace_bytes(const dapq_qproj* desc);
  * (App. C.1).  Two streaming passes over K, no N x L_p matrix is stored.
  *   scores   out, fp32 [n_layers][n_kv_heads][total_tokens]
  *   workspace  device scratch of at least dapq_workspace_bytes(shape), 256-byte aligned.
- * Equivalent to dapq_score_stats followed by dapq_score_accumulate. */
+ * Equivalent to dapq_score_stats followed by dapq_score_accumulate, bit for bit.  For a dense batch with at most
+ * 256 query rows per KV head whose sequences split into 1, 2 or 4 key chunks (dapq_score_single_launch() says
+ * whether a shape is one) both passes run in one kernel: the waves of a workgroup hold one (layer, sequence, KV head),
+ * merge their row statistics through LDS between the passes and keep the query fragments in registers. */
 int dapq_score(const dapq_shape* shape, const void* q, const void* k, float* scores, void* workspace,
                size_t workspace_bytes, void* stream);
+
+/* 1 if dapq_score (and dapq_score_static) runs both passes of this shape in one kernel, 0 if it runs them as
+ * separate launches, a negative DAPQ_ERR_* code if the shape is invalid.  Host-only: looks at the shape and the
+ * launch plan, touches no device memory. */
+int dapq_score_single_launch(const dapq_shape* shape);
 
 /* dapq_score for callers that cannot allocate device memory or hand over a workspace: code recorded into a HIP
  * graph, tight serving loops, harnesses that forbid hipMalloc.  Same inputs, same kernels and bit-identical

@@ -7,5 +7,5 @@ from .binding import (  # noqa: F401
     DapqError, Shape, Qproj, lib_path, load_library, make_shape, workspace_bytes,
     dapq_rope_apply, dapq_score, dapq_score_stats, dapq_score_accumulate, dapq_score_stats_extend, dapq_pool,
     dapq_topk, dapq_pool_topk, dapq_gather, dapq_recall, dapq_decode_attention, dapq_pseudo_tokens, dapq_pseudo_queries, pseudo_queries_workspace_bytes,
-    dapq_score_static, score_static_capacity, topk_workspace_bytes,
+    dapq_score_static, score_static_capacity, score_single_launch, topk_workspace_bytes,
 )

@@ -18,7 +18,7 @@ _lib = None
 EXPORTS = (
     "dapq_workspace_bytes", "dapq_last_error", "dapq_rope_apply", "dapq_pseudo_tokens", "dapq_pseudo_queries", "dapq_pseudo_queries_workspace_bytes", "dapq_score", "dapq_score_stats",
     "dapq_score_accumulate", "dapq_score_stats_extend", "dapq_pool", "dapq_topk", "dapq_pool_topk", "dapq_topk_workspace_bytes", "dapq_gather", "dapq_recall", "dapq_decode_attention",
-    "dapq_score_static", "dapq_score_static_capacity",
+    "dapq_score_static", "dapq_score_static_capacity", "dapq_score_single_launch",
 )
 
 
@@ -91,6 +91,7 @@ def load_library():
     lib.dapq_decode_attention.argtypes = [sp, vp, vp, vp, vp, i32, vp, vp]
     lib.dapq_score_static.argtypes = [sp, vp, vp, vp, vp]
     lib.dapq_score_static_capacity.argtypes = []
+    lib.dapq_score_single_launch.argtypes = [sp]
     for name in EXPORTS[2:]:
         getattr(lib, name).restype = C.c_int
     lib.dapq_pseudo_queries_workspace_bytes.restype = sz
@@ -146,6 +147,14 @@ def dapq_score(shape, q, k, scores, workspace, stream=None):
     _check(load_library().dapq_score(C.byref(shape), _ptr(q), _ptr(k), _ptr(scores), _ptr(workspace),
                                      0 if workspace is None else workspace.numel() * workspace.element_size(),
                                      _stream(stream)))
+
+
+def score_single_launch(shape) -> bool:
+    """Whether dapq_score runs both passes of this shape in one kernel."""
+    rc = load_library().dapq_score_single_launch(C.byref(shape))
+    if rc < 0:
+        _check(rc)
+    return bool(rc)
 
 
 def dapq_score_static(shape, q, k, scores, stream=None):

@@ -4,7 +4,9 @@
 //   pass 1  (score_wave_pass1_kernel + score_combine_kernel): lse2[row] = log2 sum_j 2^(c * q_row.k_j)
 //   pass 2  (score_wave_pass2_kernel [+ score_group_sum_kernel]): S(j) = sum_rows 2^(c * q_row.k_j - lse2[row])
 // with c = scale * log2(e).  "rows" are the R = g*N pseudo-query rows of the g query heads that
-// share one KV head.  Nothing of size N x L_p is ever stored.
+// share one KV head.  Nothing of size N x L_p is ever stored.  Where a (layer, sequence, KV head) fits one
+// workgroup -- one row group, 1, 2 or 4 chunks per sequence of a dense batch -- dapq_score runs both passes in
+// one launch (score_fused_kernel: the same two walks, the merge in between through LDS).
 //
 // Work split.  The unit of work is ONE wave (four independent ones are launched as a workgroup).  It keeps a group of up to 256 Q rows of one KV head in
 // registers as MFMA operand fragments (eight 32-row blocks = 256 registers, pinned to the
@@ -588,7 +590,9 @@ __device__ __forceinline__ int home_list() {
 // Pass 1 of one chunk: `head` = layer * n_kv_heads + KV head, `group` = row group, `chunk_id` = chunk along the packed
 // key axis.  If `work` is not NULL the ticket for the wave's next item is taken from it while the chunk drains (so
 // its round trip costs nothing) and returned.  The chunk must have keys.
-template <int NRB, int NST>
+// FUSED (score_fused_kernel): the chunk's (reference, sum) pairs go to the start of the wave's own ring, which is
+// drained by then, instead of to global memory.
+template <int NRB, int NST, bool FUSED = false>
 __device__ __forceinline__ unsigned pass1_item(const ScoreParams& p, u32x4* ring, int chunk_id, int group, int head,
                                                bf16x8 (&qf)[NRB][8], const unsigned (&voff)[4], int lane,
                                                unsigned* work) {
@@ -662,11 +666,20 @@ __device__ __forceinline__ unsigned pass1_item(const ScoreParams& p, u32x4* ring
   }
 
   // the two lane halves hold different keys of the same query
-  float2* outp = p.parts + ((int64_t)head * p.max_chunks + chunk_id) * p.rows_pad + gbase;
+  if constexpr (FUSED) {
+    float2* outp = reinterpret_cast<float2*>(ring);
 #pragma unroll
-  for (int rb = 0; rb < NRB; ++rb) {
-    const float zz = z[rb] + xhalf(z[rb]);
-    if (h == 0) outp[rb * 32 + n] = make_float2(ref[rb], zz);
+    for (int rb = 0; rb < NRB; ++rb) {
+      const float zz = z[rb] + xhalf(z[rb]);
+      if (h == 0) outp[rb * 32 + n] = make_float2(ref[rb], zz);
+    }
+  } else {
+    float2* outp = p.parts + ((int64_t)head * p.max_chunks + chunk_id) * p.rows_pad + gbase;
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+      const float zz = z[rb] + xhalf(z[rb]);
+      if (h == 0) outp[rb * 32 + n] = make_float2(ref[rb], zz);
+    }
   }
   return next;
 }
@@ -726,8 +739,9 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 1) void score_wave_pass1_kerne
   }
 }
 
-// Pass 2 of one chunk (arguments as pass1_item).
-template <int NRB, int NST>
+// Pass 2 of one chunk (arguments as pass1_item).  FUSED (score_fused_kernel): the query fragments are still in
+// registers from pass 1 and the caller has filled off2.
+template <int NRB, int NST, bool FUSED = false>
 __device__ __forceinline__ unsigned pass2_item(const ScoreParams& p, u32x4* ring, int chunk_id, int group, int head,
                                                bf16x8 (&qf)[NRB][8], float (&off2)[NRB][16],
                                                const unsigned (&voff)[4], int lane, unsigned* work) {
@@ -749,7 +763,7 @@ __device__ __forceinline__ unsigned pass2_item(const ScoreParams& p, u32x4* ring
 #pragma unroll
   for (int i = 0; i < NST; ++i)
     sub_dma(ring + i * kSubVec, kbase, p.k_stride_token, (nsubs - 1 - i) * 32, w.nkeys, voff);
-  {
+  if constexpr (!FUSED) {
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) frag_from_q(qf[rb], p, qbase, gbase + rb * 32 + n, h);
     if (NRB == 8) pin_q_in_agprs<NRB>(qf);
@@ -829,6 +843,67 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 1) void score_wave_pass2_kerne
                    lane);
     }
   }
+}
+
+// Both passes in one launch, for dense batches whose (layer, sequence, KV head) problems are one workgroup each: at
+// most 256 query rows (one row group) and as many chunks per sequence as the workgroup has waves.  A wave walks its
+// chunk forward for pass 1, the waves of the workgroup exchange their (reference, sum) pairs through LDS (their rings
+// are drained then) and each merges them -- the arithmetic of score_combine_kernel, chunk by chunk in the same order,
+// so lse2 and with it the scores have the bits of the three-kernel path -- and walks its chunk backward for pass 2 with
+// the query fragments still in registers.  What this saves is everything between the passes: a kernel boundary at
+// which every wave of the chip waits for the slowest, the combine kernel, the second placement of the workgroups and
+// the second read of the queries.  lse2 is not written anywhere.
+template <int NRB, int NST>
+__global__ __launch_bounds__(64 * kWavesPerGroup, 1) void score_fused_kernel(ScoreParams p) {
+  extern __shared__ u32x4 rings[];
+  const int wave_id = uniform_i32((int)(threadIdx.x >> 6)), waves = (int)(blockDim.x >> 6);
+  u32x4* ring = rings + wave_id * (wave_lds(NST) / 16);
+  const int lane = threadIdx.x & 63, h = lane >> 5;
+  unsigned voff[4];
+  sub_dma_lane_offsets(voff, p.k_stride_token, lane);
+  bf16x8 qf[NRB][8];
+  const int chunk = uniform_i32((int)blockIdx.x * waves + wave_id);  // blockIdx.x is the sequence
+  const int head = (int)blockIdx.z;
+  pass1_item<NRB, NST, true>(p, ring, chunk, 0, head, qf, voff, lane, nullptr);
+  __syncthreads();
+  // lse2 of rows lane, lane + 64, ...: every wave merges all chunks itself
+  constexpr int kRowsPerLane = NRB * 32 / 64;
+  float lse[kRowsPerLane];
+#pragma unroll
+  for (int r = 0; r < kRowsPerLane; ++r) {
+    const int row = r * 64 + lane;
+    float m = -INFINITY;
+    for (int w = 0; w < waves; ++w) {
+      const float2 v = reinterpret_cast<const float2*>(rings + w * (wave_lds(NST) / 16))[row];
+      if (v.y > 0.0f) m = fmaxf(m, v.x + log2f(v.y));
+    }
+    float sum = 0.0f;
+    for (int w = 0; w < waves; ++w) {
+      const float2 v = reinterpret_cast<const float2*>(rings + w * (wave_lds(NST) / 16))[row];
+      if (v.y > 0.0f) sum += exp2f(v.x + log2f(v.y) - m);
+    }
+    lse[r] = (sum > 0.0f) ? m + log2f(sum) : 0.0f;
+  }
+  __syncthreads();  // everybody has read everybody's pairs: the rings may be overwritten
+  // -lse2 of the rows this lane's accumulator registers hold, through the wave's own ring (rows beyond the head's: -inf,
+  // they then add 0)
+  float* mine = reinterpret_cast<float*>(ring);
+#pragma unroll
+  for (int r = 0; r < kRowsPerLane; ++r) mine[r * 64 + lane] = (r * 64 + lane) < p.rows ? -lse[r] : -INFINITY;
+  asm volatile("" ::: "memory");  // (the reads below are of another type than the writes above)
+  float off2[NRB][16];
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      const float4 v = *reinterpret_cast<const float4*>(mine + rb * 32 + acc_row(4 * b, h));
+      off2[rb][4 * b] = v.x;
+      off2[rb][4 * b + 1] = v.y;
+      off2[rb][4 * b + 2] = v.z;
+      off2[rb][4 * b + 3] = v.w;
+    }
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // off2 is out of the ring before pass 2 refills it
+  pass2_item<NRB, NST, true>(p, ring, chunk, 0, head, qf, off2, voff, lane, nullptr);
 }
 
 // The causal block of the pseudo tokens' own keys (Sec. 4.1: they are prefilled in-sequence): one wave
@@ -1063,6 +1138,34 @@ int launch_accumulate(const dapq_shape* s, const ScorePlan& plan, ScoreParams p,
   return DAPQ_OK;
 }
 
+// Whether one launch of score_fused_kernel can do both passes: a dense batch, one row group, and the chunks of a
+// sequence exactly the waves of a workgroup.
+bool fused_applies(const dapq_shape* s, const ScorePlan& plan) {
+  if (s->cu_seqlens != nullptr || plan.n_groups != 1 || s->total_tokens == 0) return false;
+  const GroupShape gs = group_shape(s, plan);
+  return gs.groups == 1 && plan.max_chunks == (int64_t)gs.waves * s->batch;
+}
+
+int launch_fused(const dapq_shape* s, const ScorePlan& plan, ScoreParams p, hipStream_t stream) {
+  const GroupShape gs = group_shape(s, plan);
+  p.wg_groups = 1;
+  const dim3 grid((unsigned)s->batch, 1u, (unsigned)(s->n_layers * s->n_kv_heads));
+  int rc = DAPQ_OK;
+#define DAPQ_LAUNCH_F(NRBV)                                                                                            \
+  do {                                                                                                                 \
+    if ((rc = set_lds(score_fused_kernel<NRBV, kWaveStages>, kWavesPerGroup * wave_lds(kWaveStages))) != DAPQ_OK)     \
+      return rc;                                                                                                       \
+    hipLaunchKernelGGL((score_fused_kernel<NRBV, kWaveStages>), grid, dim3(64 * gs.waves),                             \
+                       gs.waves * wave_lds(kWaveStages), stream, p);                                                   \
+  } while (0)
+  if (plan.row_blocks == 2) DAPQ_LAUNCH_F(2);
+  else if (plan.row_blocks == 4) DAPQ_LAUNCH_F(4);
+  else DAPQ_LAUNCH_F(8);
+#undef DAPQ_LAUNCH_F
+  DAPQ_HIP_LAUNCH_CHECK("score_fused_kernel");
+  return DAPQ_OK;
+}
+
 int check_workspace(void* workspace, size_t workspace_bytes, const ScorePlan& plan) {
   DAPQ_REQUIRE(workspace != nullptr, DAPQ_ERR_INVALID_ARG, "workspace is NULL");
   DAPQ_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 255) == 0, DAPQ_ERR_UNSUPPORTED,
@@ -1126,6 +1229,14 @@ extern "C" DAPQ_API int dapq_score_accumulate(const dapq_shape* shape, const voi
   return launch_accumulate(shape, plan, p, static_cast<hipStream_t>(stream));
 }
 
+extern "C" DAPQ_API int dapq_score_single_launch(const dapq_shape* shape) {
+  int rc = check_shape(shape, true, true, false);
+  if (rc != DAPQ_OK) return rc;
+  ScorePlan plan;
+  if ((rc = make_score_plan(shape, &plan)) != DAPQ_OK) return rc;
+  return fused_applies(shape, plan) ? 1 : 0;
+}
+
 extern "C" DAPQ_API int dapq_score(const dapq_shape* shape, const void* q, const void* k, float* scores,
                                    void* workspace, size_t workspace_bytes, void* stream) {
   int rc = check_shape(shape, true, true, false);
@@ -1134,6 +1245,21 @@ extern "C" DAPQ_API int dapq_score(const dapq_shape* shape, const void* q, const
   if ((rc = make_score_plan(shape, &plan)) != DAPQ_OK) return rc;
   DAPQ_REQUIRE(scores != nullptr, DAPQ_ERR_INVALID_ARG, "scores is NULL");
   if ((rc = check_workspace(workspace, workspace_bytes, plan)) != DAPQ_OK) return rc;
+  if (fused_applies(shape, plan)) {
+    if ((rc = aligned16(q, "q")) != DAPQ_OK) return rc;
+    if ((rc = aligned16(k, "k")) != DAPQ_OK) return rc;
+    ScoreParams p;
+    fill_params(shape, plan, &p);
+    p.q = static_cast<const uint16_t*>(q);
+    p.k = static_cast<const uint16_t*>(k);
+    p.cu_chunks = nullptr;
+    p.work = nullptr;
+    p.parts = nullptr;
+    p.partial = nullptr;
+    p.lse2 = nullptr;
+    p.scores = scores;
+    return launch_fused(shape, plan, p, static_cast<hipStream_t>(stream));
+  }
   float* lse2 = reinterpret_cast<float*>(static_cast<char*>(workspace) + plan.off_lse2);
   if ((rc = dapq_score_stats(shape, q, k, lse2, workspace, workspace_bytes, stream)) != DAPQ_OK) return rc;
   return dapq_score_accumulate(shape, q, k, lse2, scores, workspace, workspace_bytes, stream);

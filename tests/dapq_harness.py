@@ -61,6 +61,13 @@ class Problem:
         D.dapq_score(self.shape, self.q, self.k, S, self.ws)
         return S
 
+    def score_split(self):
+        """The same scores through the two separate entry points (pass 1 + merge, then pass 2)."""
+        lse = self.stats()
+        S = torch.full((self.layers, self.Hkv, self.tokens), float("nan"), dtype=torch.float32, device=self.device)
+        D.dapq_score_accumulate(self.shape, self.q, self.k, lse, S, self.ws)
+        return S
+
     def stats(self):
         lse = torch.full((self.layers, self.batch, self.Hq, self.N), float("nan"), dtype=torch.float32,
                          device=self.device)

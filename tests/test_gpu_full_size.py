@@ -105,6 +105,15 @@ def test_full_size_dense_workload(env, name, layers, samples):
     ctx.step()
     torch.cuda.synchronize()
     check_all_heads(ctx, w)
+    if ctx.single_launch:
+        # the step ran both passes in one kernel: every score of every head has the bits of the separate passes
+        announce(f"full size {name}: the separate passes, bit for bit")
+        S_split = torch.empty_like(ctx.S)
+        H.D.dapq_score_stats(ctx.shape, ctx.q, ctx.k, ctx.lse2, ctx.ws)
+        H.D.dapq_score_accumulate(ctx.shape, ctx.q, ctx.k, ctx.lse2, S_split, ctx.ws)
+        torch.cuda.synchronize()
+        assert torch.equal(ctx.S, S_split)
+        del S_split
     # planted needles survive in every head (the device generator plants the same rows as the host one)
     idx = ctx.idx.cpu().numpy()
     for li in range(w.n_layers):

@@ -145,6 +145,57 @@ def test_score_matches_oracle(H, case):
     announce(f"score {name}: max rel err {worst:.2e}")
 
 
+# dense batches whose sequences are 1, 2 or 4 chunks of keys and whose KV heads have at most 256 query rows: dapq_score
+# runs both passes in one kernel.  name, layers, batch, L, Hq, Hkv, N, layout
+FUSED_CASES = [
+    ("one chunk", 1, 1, 100, 4, 2, 16, "thd"),
+    ("two chunks", 2, 1, 200, 8, 2, 32, "thd"),
+    ("four chunks, ragged tail", 1, 1, 450, 8, 2, 64, "hnd"),
+    ("four full chunks", 1, 1, 512, 4, 1, 64, "thd"),
+    ("batch of three, four chunks each", 1, 3, 400, 8, 2, 16, "thd"),
+    ("batch of five, one chunk each", 2, 5, 77, 4, 2, 8, "thd"),
+    ("few rows (N=3, g=4)", 1, 1, 256, 8, 2, 3, "thd"),
+    ("many heads, 512-key chunks", 32, 1, 2048, 16, 8, 64, "hnd"),
+]
+
+
+@pytest.mark.parametrize("case", FUSED_CASES, ids=[c[0] for c in FUSED_CASES])
+def test_fused_score_equals_the_separate_passes(H, case):
+    """One kernel for both passes gives the bits of pass 1 + merge + pass 2 (same arithmetic in the same order), and the
+    oracle's scores."""
+    name, layers, batch, L, Hq, Hkv, N, layout = case
+    announce(f"fused score: {name}")
+    q, k, v, cu = random_problem(zlib.crc32(name.encode()) % 1000, layers, [L] * batch, Hq, Hkv, N)
+    prob = H.Problem(q, k, v, Hkv, None, layout)
+    assert H.D.score_single_launch(prob.shape), name
+    S = prob.score()
+    S_split = prob.score_split()
+    assert torch.equal(S, S_split), name
+    if layers <= 2:
+        H.assert_scores_close(S.cpu().numpy(), O.score(q, k, Hkv, cu if batch > 1 else None), name)
+    else:                                                           # the oracle on a sample of the heads
+        Sh = S.cpu().numpy()
+        g = Hq // Hkv
+        for l, kv in ((0, 0), (17, 3), (31, 7)):
+            want = O.score(q[l:l + 1, :, kv * g:(kv + 1) * g], k[l:l + 1, :, kv:kv + 1], 1)
+            H.assert_scores_close(Sh[l:l + 1, kv:kv + 1], want, f"{name} layer {l} head {kv}")
+
+
+def test_fused_score_dominant_late_key(H):
+    """The overflow path of pass 1 (a chunk redone with a running maximum) inside the one-kernel form."""
+    announce("fused score: dominant late key")
+    q, k, v, cu = random_problem(17, 1, [500], 4, 1, 16)
+    qf = O.bf16_bits_to_f64(q[0, 0, 0, 0])
+    k[0, 430, 0] = W.to_bf16_bits(40.0 * qf)
+    k[0, 17, 0] = W.to_bf16_bits(-40.0 * qf)
+    prob = H.Problem(q, k, v, 1, None, "thd")
+    assert H.D.score_single_launch(prob.shape)
+    S = prob.score()
+    assert torch.equal(S, prob.score_split())
+    H.assert_scores_close(S.cpu().numpy(), O.score(q, k, 1), "fused dominant key")
+    assert S[0, 0, 430].item() > 1.0
+
+
 def test_score_c1_workload_with_needles(H):
     announce("score C1 workload")
     w = W.workload("C1")
