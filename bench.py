@@ -35,6 +35,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # by what the same counter reads for kernels of known size in the same run (the 2 GiB read-stream probe; the
 # fp32 -> bf16 conversion of the input generator: 128 MiB read, 64 MiB written); profiles/score_c2_hbm_traffic.md.
 MEASURED_TRAFFIC_BYTES = {    # (workload, N, kernel)
+    ("C2", 64, "score"): 4.341e9,         # both passes in one kernel: 4.307 GB fetched (K twice, Q once) + 32 MiB written
+    ("C2", 32, "score"): 4.333e9,         # 4.299 GB fetched + 32 MiB written
     ("C2", 64, "score_pass2"): 2.201e9,   # 2.167 GB fetched (keys + the pseudo queries once per head) + 32 MiB written
     ("C2", 64, "score_pass1"): 2.171e9,   # 2.169 GB fetched + 2 MiB of partial row statistics written
     ("C2", 32, "score_pass2"): 2.190e9,   # 2.156 GB fetched + 32 MiB written
@@ -42,7 +44,7 @@ MEASURED_TRAFFIC_BYTES = {    # (workload, N, kernel)
 }
 # Where those figures come from: the profile file and the commit whose score kernels were profiled.  A CPU test
 # (tests/test_bench_host.py) fails when csrc/score.hip has changed since that commit, i.e. when they are stale.
-TRAFFIC_SOURCE = {"file": "profiles/score_c2_hbm_traffic.md", "commit": "ec2fe23"}
+TRAFFIC_SOURCE = {"file": "profiles/score_c2_hbm_traffic.md", "commit": "1cc0cf3"}
 
 
 def parse():

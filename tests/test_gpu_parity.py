@@ -777,54 +777,7 @@ def test_score_keys_with_a_huge_row_stride(H):
     H.assert_scores_close(S.cpu().numpy(), O.score(q_bits, k_bits, 1), "S, strided keys")
 
 
-# ----------------------------------------------------------------------------------------- the step from a HIP graph
-def test_step_replays_from_a_hip_graph(H):
-    """The library allocates nothing, clears nothing with memset calls and never synchronises, so the whole step
-    can be captured once and replayed: score (both passes), pooling + selection, gather on a ragged batch,
-    recorded into a HIP graph on a side stream, replayed three times with other work and synchronisations in
-    between; every replay must reproduce the eager results bit for bit."""
-    announce("the step captured in a HIP graph and replayed")
-    layers, lens, Hq, Hkv, N, budget = 2, [700, 40, 0, 300, 1500], 8, 2, 16, 96
-    q, k, v, cu = random_problem(77, layers, lens, Hq, Hkv, N)
-    prob = H.Problem(q, k, v, Hkv, cu, "thd")
-    D, dev = H.D, "cuda"
-
-    def buffers():
-        return dict(S=torch.zeros((layers, Hkv, prob.tokens), dtype=torch.float32, device=dev),
-                    idx=torch.zeros((layers, len(lens), Hkv, budget), dtype=torch.int32, device=dev),
-                    count=torch.zeros((layers, len(lens), Hkv), dtype=torch.int32, device=dev),
-                    ko=torch.zeros((layers, len(lens), Hkv, budget, 128), dtype=torch.bfloat16, device=dev),
-                    vo=torch.zeros((layers, len(lens), Hkv, budget, 128), dtype=torch.bfloat16, device=dev))
-
-    def chain(b, stream):
-        D.dapq_score(prob.shape, prob.q, prob.k, b["S"], prob.ws, stream)
-        D.dapq_pool_topk(prob.shape, b["S"], 7, budget, None, b["idx"], b["count"], None, stream)
-        D.dapq_gather(prob.shape, prob.k, prob.v, b["idx"], b["count"], budget, b["ko"], b["vo"], stream)
-
-    eager = buffers()
-    chain(eager, None)
-    torch.cuda.synchronize()
-    want = {name: t.clone() for name, t in eager.items()}
-
-    out = buffers()
-    side = torch.cuda.Stream()
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph, stream=side):
-        chain(out, side)
-    for replay in range(3):
-        for t in out.values():
-            t.fill_(0)                                     # a fill kernel, not a memset node
-        other = prob.score()                               # eager work of the same library between the replays
-        torch.cuda.synchronize()
-        graph.replay()
-        torch.cuda.synchronize()
-        assert torch.equal(other, want["S"])
-        for name in out:
-            assert torch.equal(out[name].view(torch.int16) if out[name].dtype == torch.bfloat16 else out[name],
-                               want[name].view(torch.int16) if want[name].dtype == torch.bfloat16 else want[name]), \
-                (name, replay)
-
-
+# ----------------------------------------------------------------------------------------- several streams
 def test_calls_on_two_streams_do_not_disturb_each_other(H):
     """Two problems scored at the same time on two streams, each with its own workspace and outputs, give the
     bits they give when run one after the other (the library keeps no state between or across calls)."""
