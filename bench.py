@@ -271,15 +271,33 @@ def shader_clock_mhz():
     return None
 
 
+def board_power_watts():
+    """(what the board draws right now, its power cap) in watts as the driver reports them (hwmon power1_input or
+    power1_average, power1_cap), or (None, None)."""
+    import glob
+    for hw in sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*")):
+        try:
+            cap = float(open(os.path.join(hw, "power1_cap")).read()) * 1e-6
+            for leaf in ("power1_input", "power1_average"):
+                path = os.path.join(hw, leaf)
+                if os.path.exists(path):
+                    return float(open(path).read()) * 1e-6, cap
+        except (OSError, ValueError):
+            continue
+    return None, None
+
+
 def time_passes(ctx, shape, warm, reps):
-    """Average duration (ms) of the two score passes for `shape`, each launched back to back on its own, and the
-    shader clock the driver reports while the queued launches run (<name>_mhz; None if it cannot be read)."""
+    """Average duration (ms) of the two score passes for `shape`, each launched back to back on its own, and of
+    dapq_score (both in one kernel where the library can), with the shader clock (<name>_mhz) and the board power
+    (<name>_watts; power_cap_watts) the driver reports while the queued launches run (None where it cannot be read)."""
     import torch
     D, stream = ctx.D, ctx.stream
-    res = {}
+    res = {"power_cap_watts": board_power_watts()[1]}
     calls = {
         "score_pass1": lambda: D.dapq_score_stats(shape, ctx.q, ctx.k, ctx.lse2, ctx.ws, stream),
         "score_pass2": lambda: D.dapq_score_accumulate(shape, ctx.q, ctx.k, ctx.lse2, ctx.S, ctx.ws, stream),
+        "score": lambda: D.dapq_score(shape, ctx.q, ctx.k, ctx.S, ctx.ws, stream),
     }
     for name, fn in calls.items():
         for _ in range(warm):
@@ -289,13 +307,15 @@ def time_passes(ctx, shape, warm, reps):
         for _ in range(reps):
             fn()
         e1.record(stream)
-        clocks = []
+        clocks, watts = [], []
         while not e1.query():       # the launches are queued: the GPU is still working through them
             time.sleep(0.03)
             clocks.append(shader_clock_mhz())
+            watts.append(board_power_watts()[0])
         torch.cuda.synchronize()
         res[name] = e0.elapsed_time(e1) / reps
         res[name + "_mhz"] = clocks[2:-1]       # (the first samples see the governor still settling)
+        res[name + "_watts"] = watts[2:-1]
     return res
 
 
@@ -334,7 +354,7 @@ def ceilings(ctx, args):
         placements["one_layer_of_keys_for_all"] = one_layer
         placements["one_head_of_keys_for_all"] = one_head
     out["passes_ms"] = {name: time_passes(ctx, shape, args.warmup, args.steps) for name, shape in placements.items()}
-    out["passes_ns_per_slice"] = {name: {k: v * 1e6 / slices for k, v in r.items() if not k.endswith("_mhz")}
+    out["passes_ns_per_slice"] = {name: {k: r[k] * 1e6 / (slices * n) for k, n in (("score_pass1", 1), ("score_pass2", 1), ("score", 2))}
                                   for name, r in out["passes_ms"].items()}
     # the key slab on chip across the passes: both passes over G layers at a time (G x 64 MiB of keys at C2, against
     # the 256 MB memory-side cache), so that pass 2 finds the keys pass 1 just read; the same kernels, the planner
