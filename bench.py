@@ -534,8 +534,22 @@ def main():
     stride = max(1, args.event_stride)
     for s in range(args.steps):
         ctx.step(evs[s] if s % stride == 0 else None)
+    # the host is far ahead of the stream: while it waits for the queued steps, a second thread reads what the driver
+    # says about power and clock (the wait itself is the plain synchronize, so the clock stops when the GPU does)
+    import threading
+    watts, mhz, waiting = [], [], threading.Event()
+
+    def sample():
+        while not waiting.is_set():
+            watts.append(board_power_watts()[0])
+            mhz.append(shader_clock_mhz())
+            time.sleep(0.02)
+    sampler = threading.Thread(target=sample, daemon=True)
+    sampler.start()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    waiting.set()
+    sampler.join()
     ms_per_step = dt * 1e3 / args.steps
     per = {n: float(np.mean([evs[s][i].elapsed_time(evs[s][i + 1]) for s in range(0, args.steps, stride)]))
            for i, n in enumerate(names)}
@@ -602,6 +616,11 @@ def main():
                                f"L_p {lens if w.ragged else lens[0]}, N {N}, budget {w.budget}, pool {w.pool_width}, "
                                f"K layout {w.layout}"},
         "kernel_ms": per,
+        # sampled every 20 ms while the timed steps ran (None where the driver's files cannot be read)
+        "board_power_watts": {"mean": float(np.mean([x for x in watts if x])) if any(watts) else None,
+                              "max": max([x for x in watts if x], default=None), "cap": board_power_watts()[1],
+                              "samples": len(watts)},
+        "shader_clock_mhz": float(np.mean([x for x in mhz if x])) if any(mhz) else None,
         "roofline": roofline,
         "step_hbm": step_hbm,
     }
