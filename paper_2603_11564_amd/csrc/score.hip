@@ -12,7 +12,8 @@
 // registers as MFMA operand fragments (eight 32-row blocks = 256 registers, pinned to the
 // accumulation half of the register file; one wave per SIMD owns the whole 512-register file) and
 // walks its own chunk of keys of one (layer, sequence, KV head).  Nothing is shared between waves:
-// no barrier anywhere, no cross-wave reduction.  Heads with more than 256 rows are split into row
+// no barrier anywhere in the separate-pass kernels (the one-launch form has two, between its passes),
+// no cross-wave reduction.  Heads with more than 256 rows are split into row
 // groups (grid.y): pass 1 needs nothing more (its sums are per row), pass 2 writes one plane of
 // column sums per group (group 0 into the result) and a small kernel adds the planes in group order.
 // Keys arrive through a per-wave ring of 32-key sub-blocks in LDS (buffer_load_dwordx4 ... lds, five
