@@ -69,6 +69,22 @@ def test_static_scratch_serves_a_ragged_batch():
     assert_scores_close(S1.cpu().numpy(), O.score(ragged.q_bits, ragged.k_bits, 2, cu, 128 ** -0.5), "static ragged")
 
 
+def test_static_scratch_one_kernel_shape():
+    """A shape whose two passes run in one kernel (no workspace is touched at all) between two that use the scratch
+    array: the scores of the separate passes with a caller workspace, bit for bit."""
+    one = make_problem(15, layers=2, L=400, n_pseudo=32)       # four chunks of a sequence = the waves of a workgroup
+    other = make_problem(16, layers=1, L=2000, n_pseudo=16)
+    assert D.score_single_launch(one.shape) and not D.score_single_launch(other.shape)
+    ref_one, ref_other = one.score_split(), other.score()
+    S1, S2, S3 = new_scores(other), new_scores(one), new_scores(other)
+    D.dapq_score_static(other.shape, other.q, other.k, S1)
+    D.dapq_score_static(one.shape, one.q, one.k, S2)
+    D.dapq_score_static(other.shape, other.q, other.k, S3)
+    torch.cuda.synchronize()
+    assert torch.equal(S1, ref_other) and torch.equal(S2, ref_one) and torch.equal(S3, ref_other)
+    assert_scores_close(S2.cpu().numpy(), O.score(one.q_bits, one.k_bits, one.Hkv, None, 128 ** -0.5), "static one-kernel")
+
+
 def test_static_scratch_refuses_what_does_not_fit():
     w = W.workload("C3")                                        # ragged batch: 134 MB of workspace
     cu = torch.zeros(w.batch + 1, dtype=torch.int32, device="cuda")
