@@ -196,7 +196,7 @@ class Context:
                                   total_tokens=tokens, cu_seqlens=self.cu, k_strides=kstr, v_strides=kstr,
                                   q_strides=qstr, scale=w.scale)
         self.ws = torch.empty(D.workspace_bytes(self.shape), dtype=torch.uint8, device=dev)
-        # both passes in one kernel (dense batches of up to 256 rows per KV head and 1, 2 or 4 chunks per sequence)
+        # both passes in one kernel (dense batches of up to 256 rows per KV head and at most 4 chunks per sequence)
         self.single_launch = D.score_single_launch(self.shape) and not split_passes
         self.names = (["rope", "score", "pool_topk", "gather"] if self.single_launch else
                       ["rope", "score_pass1", "score_pass2", "pool_topk", "gather"])

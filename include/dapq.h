@@ -150,7 +150,7 @@ size_t dapq_pseudo_queries_workspace_bytes(const dapq_qproj* desc);
  *   scores   out, fp32 [n_layers][n_kv_heads][total_tokens]
  *   workspace  device scratch of at least dapq_workspace_bytes(shape), 256-byte aligned.
  * Equivalent to dapq_score_stats followed by dapq_score_accumulate, bit for bit.  For a dense batch with at most
- * 256 query rows per KV head whose sequences split into 1, 2 or 4 key chunks (dapq_score_single_launch() says
+ * 256 query rows per KV head whose sequences split into at most 4 key chunks (dapq_score_single_launch() says
  * whether a shape is one) both passes run in one kernel: the waves of a workgroup hold one (layer, sequence, KV head),
  * merge their row statistics through LDS between the passes and keep the query fragments in registers. */
 int dapq_score(const dapq_shape* shape, const void* q, const void* k, float* scores, void* workspace,

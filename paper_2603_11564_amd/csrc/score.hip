@@ -5,7 +5,7 @@
 //   pass 2  (score_wave_pass2_kernel [+ score_group_sum_kernel]): S(j) = sum_rows 2^(c * q_row.k_j - lse2[row])
 // with c = scale * log2(e).  "rows" are the R = g*N pseudo-query rows of the g query heads that
 // share one KV head.  Nothing of size N x L_p is ever stored.  Where a (layer, sequence, KV head) fits one
-// workgroup -- one row group, 1, 2 or 4 chunks per sequence of a dense batch -- dapq_score runs both passes in
+// workgroup -- one row group, at most 4 chunks per sequence of a dense batch -- dapq_score runs both passes in
 // one launch (score_fused_kernel: the same two walks, the merge in between through LDS).
 //
 // Work split.  The unit of work is ONE wave (four independent ones are launched as a workgroup).  It keeps a group of up to 256 Q rows of one KV head in
@@ -847,7 +847,7 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, 1) void score_wave_pass2_kerne
 }
 
 // Both passes in one launch, for dense batches whose (layer, sequence, KV head) problems are one workgroup each: at
-// most 256 query rows (one row group) and as many chunks per sequence as the workgroup has waves.  A wave walks its
+// most 256 query rows (one row group) and as many chunks per sequence as the workgroup has waves (1 to 4).  A wave walks its
 // chunk forward for pass 1, the waves of the workgroup exchange their (reference, sum) pairs through LDS (their rings
 // are drained then) and each merges them -- the arithmetic of score_combine_kernel, chunk by chunk in the same order,
 // so lse2 and with it the scores have the bits of the three-kernel path -- and walks its chunk backward for pass 2 with
@@ -1141,14 +1141,17 @@ int launch_accumulate(const dapq_shape* s, const ScorePlan& plan, ScoreParams p,
 
 // Whether one launch of score_fused_kernel can do both passes: a dense batch, one row group, and the chunks of a
 // sequence exactly the waves of a workgroup.
-bool fused_applies(const dapq_shape* s, const ScorePlan& plan) {
-  if (s->cu_seqlens != nullptr || plan.n_groups != 1 || s->total_tokens == 0) return false;
-  const GroupShape gs = group_shape(s, plan);
-  return gs.groups == 1 && plan.max_chunks == (int64_t)gs.waves * s->batch;
+// Returns the waves of such a workgroup (1 to 4), or 0 if the passes have to be separate launches.
+int fused_waves(const dapq_shape* s, const ScorePlan& plan) {
+  if (s->cu_seqlens != nullptr || plan.n_groups != 1 || s->total_tokens == 0) return 0;
+  const int64_t chunks_per_seq = plan.max_chunks / s->batch;  // dense: max_chunks = batch * chunks per sequence
+  if (chunks_per_seq * s->batch != plan.max_chunks) return 0;
+  return chunks_per_seq >= 1 && chunks_per_seq <= kWavesPerGroup ? (int)chunks_per_seq : 0;
 }
+bool fused_applies(const dapq_shape* s, const ScorePlan& plan) { return fused_waves(s, plan) != 0; }
 
 int launch_fused(const dapq_shape* s, const ScorePlan& plan, ScoreParams p, hipStream_t stream) {
-  const GroupShape gs = group_shape(s, plan);
+  const GroupShape gs = {fused_waves(s, plan), 1};
   p.wg_groups = 1;
   const dim3 grid((unsigned)s->batch, 1u, (unsigned)(s->n_layers * s->n_kv_heads));
   int rc = DAPQ_OK;

@@ -88,14 +88,15 @@ def test_topk_workspace_bytes(lib):
 
 def test_score_single_launch_follows_the_launch_plan(lib):
     """dapq_score runs both passes in one kernel exactly when a (layer, sequence, KV head) is one workgroup: a dense
-    batch, at most 256 query rows per KV head, 1, 2 or 4 key chunks per sequence."""
+    batch, at most 256 query rows per KV head, at most 4 key chunks per sequence."""
     assert D.score_single_launch(good_shape(n_layers=32, total_tokens=32768))                # the 8B shape: 4 chunks of 8192
     assert D.score_single_launch(good_shape(n_layers=32, total_tokens=32768, n_pseudo=32))
     assert D.score_single_launch(good_shape(n_layers=1, total_tokens=512))                   # 4 chunks of 128
     assert D.score_single_launch(good_shape(n_layers=1, total_tokens=100))                   # one chunk
     assert D.score_single_launch(good_shape(n_layers=1, batch=3, total_tokens=1200))         # 4 chunks for each of 3
     assert not D.score_single_launch(good_shape(n_layers=1, total_tokens=1024))              # 8 chunks of 128
-    assert not D.score_single_launch(good_shape(n_layers=1, total_tokens=300))               # 3 chunks
+    assert D.score_single_launch(good_shape(n_layers=1, total_tokens=300))                   # 3 chunks: three waves
+    assert not D.score_single_launch(good_shape(n_layers=1, total_tokens=600))               # 5 chunks
     assert not D.score_single_launch(good_shape(n_layers=32, total_tokens=32768, n_pseudo=128))   # two row groups
     ragged = good_shape(batch=4, total_tokens=400)
     ragged.cu_seqlens = FAKE                                                                 # never dereferenced here

@@ -145,11 +145,14 @@ def test_score_matches_oracle(H, case):
     announce(f"score {name}: max rel err {worst:.2e}")
 
 
-# dense batches whose sequences are 1, 2 or 4 chunks of keys and whose KV heads have at most 256 query rows: dapq_score
+# dense batches whose sequences are at most 4 chunks of keys and whose KV heads have at most 256 query rows: dapq_score
 # runs both passes in one kernel.  name, layers, batch, L, Hq, Hkv, N, layout
 FUSED_CASES = [
     ("one chunk", 1, 1, 100, 4, 2, 16, "thd"),
     ("two chunks", 2, 1, 200, 8, 2, 32, "thd"),
+    ("three chunks", 2, 1, 300, 4, 2, 32, "thd"),
+    ("batch of four, three chunks each", 1, 4, 333, 8, 2, 64, "thd"),
+    ("batch of seven, two chunks each", 1, 7, 190, 4, 1, 16, "thd"),
     ("four chunks, ragged tail", 1, 1, 450, 8, 2, 64, "hnd"),
     ("four full chunks", 1, 1, 512, 4, 1, 64, "thd"),
     ("batch of three, four chunks each", 1, 3, 400, 8, 2, 16, "thd"),
