@@ -44,7 +44,7 @@ MEASURED_TRAFFIC_BYTES = {    # (workload, N, kernel)
 }
 # Where those figures come from: the profile file and the commit whose score kernels were profiled.  A CPU test
 # (tests/test_bench_host.py) fails when csrc/score.hip has changed since that commit, i.e. when they are stale.
-TRAFFIC_SOURCE = {"file": "profiles/score_c2_hbm_traffic.md", "commit": "627736b"}
+TRAFFIC_SOURCE = {"file": "profiles/score_c2_hbm_traffic.md", "commit": "ef1131b"}
 
 
 def parse():
