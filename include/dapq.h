@@ -171,7 +171,9 @@ int dapq_score_single_launch(const dapq_shape* shape);
  * Every call on a GPU uses that GPU's one array, which keeps the contents of the previous call (nothing in it has
  * to be cleared: the first pass writes everything the second reads).  Two calls in flight on the same GPU at the
  * same time -- different streams, or host threads -- race on it: serialise them, or use dapq_score with
- * separate workspaces.  dapq_score_static_capacity() returns DAPQ_STATIC_SCRATCH_BYTES as built. */
+ * separate workspaces.  (A shape whose passes run in one kernel, see dapq_score_single_launch(), uses no workspace
+ * at all; the size check above applies to it all the same.)  dapq_score_static_capacity() returns
+ * DAPQ_STATIC_SCRATCH_BYTES as built. */
 #define DAPQ_STATIC_SCRATCH_BYTES ((size_t)4 << 20)
 int dapq_score_static(const dapq_shape* shape, const void* q, const void* k, float* scores, void* stream);
 size_t dapq_score_static_capacity(void);
