@@ -580,7 +580,11 @@ def main():
     else:
         roofline = {"bound": "hbm", "kernel": dom, "achieved": hbm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": hbm_gbs / HBM_PEAK_GBS}
+    nrb = 2 if (Hq // Hkv) * N <= 64 else (4 if (Hq // Hkv) * N <= 128 else 8)      # 32-row blocks a wave holds
     roofline.update({
+        # the device function behind the kernel_ms entry named by "kernel", as a kernel trace shows it
+        "kernel_name": {"score": f"score_fused_kernel<{nrb}, 5>", "score_pass1": f"score_wave_pass1_kernel<{nrb}, ...>",
+                        "score_pass2": f"score_wave_pass2_kernel<{nrb}, ...>"}[dom],
         "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, N, dom)),
         "traffic_source": (f"{TRAFFIC_SOURCE['file']}, rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of the kernels at commit "
                            f"{TRAFFIC_SOURCE['commit']} (not measured in this run)"
